@@ -28,7 +28,7 @@ def test_config_shapes_and_budgets():
         new = sum(synth.blocks_for(int(b)) for b in w.budgets)
         assert abs((old + new) / w.n_blocks - occ) < 1e-3
     # config 4 must fit one MI355X
-    assert w4.pool_bytes() < 200 * 2**30
+    assert w4.pool_bytes() < 215 * 2**30
 
 
 def test_block_tables_are_disjoint_and_permuted():
