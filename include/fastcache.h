@@ -1,0 +1,164 @@
+/*
+ * fastcache.h - C ABI of the batched KV-cache compression stage for MI355X.
+ *
+ * The stage is the "batch compression" step of FastCache's serving loop
+ * (Algorithm 1: kv <- P.Store(M.Prefill(batch)); kv_c <- C(kv, lambda);
+ * decode; P.Release(kv_c)) together with the KV-cache memory pool it works on
+ * ("KV-cache Memory Pool" paragraph of the Dynamic Resource Management
+ * section: the pool reclaims the pre-compression "zombie" caches right after
+ * compression and manages the compressed ones centrally).  Stage hand-off is
+ * by block tables, i.e. by reference ("zero-copy mechanism", System
+ * Implementation section); the only data movement is the compaction copy.
+ *
+ * Every function returns FC_OK (0) or a negative error code.  On any error
+ * the pool, its free list and all caller buffers are left unchanged.
+ * "dev" pointers are device (HBM) addresses, "host" pointers are ordinary
+ * host memory.  All device work is issued on the hipStream_t passed as
+ * `stream` (NULL = the default stream) and is asynchronous with respect to
+ * the host unless stated otherwise.  A pool is not thread safe: calls on one
+ * pool must be serialised by the caller, and work on different streams must
+ * be ordered by the caller.
+ */
+#ifndef FASTCACHE_H
+#define FASTCACHE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct fc_pool fc_pool; /* opaque, owned by the library */
+
+enum { FC_OK = 0, FC_EINVAL = -1, FC_ENOMEM = -2, FC_EDEVICE = -3 };
+enum { FC_METHOD_NONE = 0, FC_METHOD_SNAPKV = 1, FC_METHOD_KNORM = 2 };
+enum { FC_DTYPE_F16 = 0 };
+
+#define FC_BLOCK_SIZE 16      /* tokens per pool block (the only supported value) */
+#define FC_MAX_WINDOW 64      /* largest observation window */
+#define FC_MAX_SEQ_LEN 32768  /* longest request the stage accepts */
+#define FC_MAX_POOL_KERNEL 63 /* largest max-pool kernel */
+
+/*
+ * Creates a pool over caller-owned device memory (Algorithm 1, "Initialize
+ * KVCachePool P").
+ *
+ * kv_base   dev, caller-owned for the lifetime of the pool, 256-byte aligned,
+ *           fp16, laid out as
+ *             kv[layer][block][kv: 0=K, 1=V][head][slot 0..15][head_dim]
+ *           so that (layer, block, kv, head) is one contiguous chunk of
+ *           16*head_dim halves.  The engine writes prefill K/V rows straight
+ *           into it; token j of a request lives in block table[j / 16],
+ *           slot j % 16, for every layer and head.
+ * kv_bytes  size of that memory; must be >= n_layers*n_blocks*2*n_heads*16*
+ *           head_dim*2.
+ * block_size must be 16, head_dim 64 or 128, dtype FC_DTYPE_F16.
+ *
+ * The free list is a LIFO stack of block ids held in device memory; a fresh
+ * pool holds stack[i] = n_blocks-1-i, top = n_blocks, so that the first
+ * block handed out is block 0.  Synchronous.
+ */
+int fc_pool_create(fc_pool** out, void* kv_base, size_t kv_bytes, int n_blocks,
+                   int block_size, int n_layers, int n_heads, int head_dim,
+                   int dtype);
+
+/* Releases the library's own device memory (free list, scratch).  Waits for
+ * the device first.  kv_base stays the caller's. */
+int fc_pool_destroy(fc_pool* pool);
+
+/*
+ * P.Store side of the pool: pops n_blocks ids off the free stack,
+ * dev_out_ids[i] = stack[top-1-i], then top -= n_blocks.
+ * dev_out_ids: dev, int32[n_blocks], caller-owned.
+ * FC_ENOMEM if fewer than n_blocks are free, FC_EINVAL if n_blocks < 0.
+ */
+int fc_pool_alloc(fc_pool* pool, int n_blocks, int32_t* dev_out_ids, void* stream);
+
+/*
+ * P.Release: pushes ids in array order, stack[top+i] = dev_ids[i], then
+ * top += n_blocks.  dev_ids: dev, int32[n_blocks].  The ids must have come
+ * from this pool and be owned by the caller (not checked on the device);
+ * FC_EINVAL if the push would exceed the pool size.
+ */
+int fc_pool_free(fc_pool* pool, const int32_t* dev_ids, int n_blocks, void* stream);
+
+/* Number of free blocks (exact host-side mirror of top), or a negative error. */
+int fc_pool_num_free(const fc_pool* pool);
+
+/*
+ * Copies the free stack to host_stack (host, int32[n_blocks]; entries
+ * [0, *top) are meaningful) after waiting for all device work.  Synchronous.
+ */
+int fc_pool_export_state(fc_pool* pool, int32_t* host_stack, int* top);
+
+/* Overwrites the free stack and top from the host (used to rewind metadata
+ * between benchmark repetitions).  0 <= top <= n_blocks.  Synchronous. */
+int fc_pool_import_state(fc_pool* pool, const int32_t* host_stack, int top);
+
+/*
+ * kv_c <- C(kv, lambda) for a whole batch (Algorithm 1, "Batch compression";
+ * Pipeline Optimization section: compression of many requests is issued as
+ * one grouped operation instead of one launch sequence per request).
+ *
+ * For every request r with method != FC_METHOD_NONE, every layer and head:
+ *   1. score the L_r cached tokens
+ *        FC_METHOD_SNAPKV: queries of the last `window` tokens attend (causal,
+ *          logits scale*q.k, row softmax) over the cached keys; per key, sum
+ *          over the window queries; max-pool (odd pool_kernel, stride 1, same
+ *          length) over the keys before the window; window tokens score +inf;
+ *        FC_METHOD_KNORM: score = -||k||_2;
+ *   2. keep the budget_r best scores (ties to the lower index), in ascending
+ *      token order;
+ *   3. pop ceil(budget_r/16) new blocks (all requests' new blocks are popped
+ *      first, in batch order), copy the kept K and V rows densely into them;
+ *   4. push the request's old blocks (batch order, table order) back on the
+ *      free stack, rewrite its block-table row (entries past the new count
+ *      become -1) and set host_seq_lens[r] = budget_r.
+ *
+ * dev_block_tables  dev, int32 [n_req][max_blocks_per_req], in/out.
+ * host_seq_lens     host, int32 [n_req], in/out (updated before returning).
+ * dev_q_window      dev, fp16 [n_req][n_layers][n_heads][window][head_dim],
+ *                   16-byte aligned; may be NULL if no request uses SNAPKV.
+ * host_method, host_budget  host, int32 [n_req].
+ * pool_kernel       odd, 1..FC_MAX_POOL_KERNEL.   scale <= 0 means
+ *                   1/sqrt(head_dim).
+ * dev_scores_out    dev or NULL: final fp32 scores packed as
+ *                   [r][layer][head][L_r] over the compressed requests in
+ *                   batch order (request r starts at the sum over earlier
+ *                   compressed requests of L*n_layers*n_heads).
+ * dev_kept_out      dev or NULL: kept indices, int32, packed the same way
+ *                   with budget_r in place of L_r.
+ *
+ * FC_EINVAL: unknown method; budget < 1 or > L; L > FC_MAX_SEQ_LEN; SNAPKV
+ * with window outside 1..FC_MAX_WINDOW, L < window or budget < window;
+ * ceil(L/16) > max_blocks_per_req; bad pool_kernel; NULL where a buffer is
+ * needed.  FC_ENOMEM: the sum of new blocks exceeds the free blocks (new
+ * blocks are taken before old ones are released because the copy reads the
+ * old blocks while it writes the new ones).  FC_EDEVICE: a HIP call failed.
+ */
+int fc_compress_batch(fc_pool* pool, int32_t* dev_block_tables, int max_blocks_per_req,
+                      int32_t* host_seq_lens, const void* dev_q_window, int window,
+                      const int32_t* host_method, const int32_t* host_budget, int n_req,
+                      int pool_kernel, float scale, float* dev_scores_out,
+                      int32_t* dev_kept_out, void* stream);
+
+/*
+ * Per-kernel timing for benchmarks.  With profiling enabled every kernel
+ * launched by fc_compress_batch is bracketed by HIP events on the call's
+ * stream.  fc_get_kernel_times waits for the last call and writes the elapsed
+ * milliseconds of each kernel of that call (0 if it was not launched) to
+ * host_ms[0..FC_N_KERNELS).  fc_kernel_name(i) names slot i.
+ */
+#define FC_N_KERNELS 6
+int fc_set_profiling(fc_pool* pool, int enable);
+int fc_get_kernel_times(fc_pool* pool, float* host_ms);
+const char* fc_kernel_name(int i);
+
+/* Text of the most recent error raised on the calling thread ("" if none). */
+const char* fc_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FASTCACHE_H */

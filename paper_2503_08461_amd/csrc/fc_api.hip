@@ -1,0 +1,383 @@
+// Host side of libfastcache: the C ABI declared in include/fastcache.h.
+// Validates a batch with what the host scheduler knows (lengths, methods,
+// budgets, free-block count), builds the per-request descriptors and issues
+// the stage's kernels on the caller's stream.  No device->host transfer and
+// no host wait happens inside fc_compress_batch once scratch is sized.
+
+#include "../../include/fastcache.h"
+#include "fc_internal.h"
+
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <numeric>
+#include <vector>
+
+using namespace fc;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define FC_HIP(call)                                                            \
+  do {                                                                          \
+    hipError_t e_ = (call);                                                     \
+    if (e_ != hipSuccess)                                                       \
+      return fail(FC_EDEVICE, "%s failed: %s", #call, hipGetErrorString(e_));   \
+  } while (0)
+
+const char* const kKernelNames[K_COUNT] = {"plan_alloc",   "snapkv_score", "knorm_score",
+                                           "select",       "gather",       "reclaim"};
+
+size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+}  // namespace
+
+struct fc_pool {
+  _Float16* kv = nullptr;
+  size_t kv_bytes = 0;
+  int n_blocks = 0, n_layers = 0, n_heads = 0, head_dim = 0;
+  int32_t* stack = nullptr;  // device
+  int top = 0;               // host mirror, exact
+
+  // scratch, grown on demand
+  float* raw_scores = nullptr;
+  size_t raw_cap = 0;  // floats
+  int32_t* kept = nullptr;
+  size_t kept_cap = 0;  // ints
+  int32_t* ids = nullptr;
+  size_t ids_cap = 0;  // ints (old ids then new ids)
+  char* dev_meta = nullptr;
+  char* host_meta = nullptr;  // pinned
+  size_t meta_cap = 0;
+  hipEvent_t meta_event = nullptr;
+  bool meta_pending = false;
+
+  bool profiling = false;
+  hipEvent_t ev[K_COUNT][2] = {};
+  bool timed[K_COUNT] = {};
+};
+
+namespace {
+
+template <typename T>
+int grow(T** buf, size_t* cap, size_t need) {
+  if (need <= *cap) return FC_OK;
+  // the old buffer may still be in use by queued work
+  FC_HIP(hipDeviceSynchronize());
+  if (*buf) FC_HIP(hipFree(*buf));
+  *buf = nullptr;
+  *cap = 0;
+  const size_t n = round_up(need + need / 8, 4096);
+  FC_HIP(hipMalloc(reinterpret_cast<void**>(buf), n * sizeof(T)));
+  *cap = n;
+  return FC_OK;
+}
+
+int grow_meta(fc_pool* p, size_t need) {
+  if (need <= p->meta_cap) return FC_OK;
+  FC_HIP(hipDeviceSynchronize());
+  if (p->dev_meta) FC_HIP(hipFree(p->dev_meta));
+  if (p->host_meta) FC_HIP(hipHostFree(p->host_meta));
+  p->dev_meta = nullptr;
+  p->host_meta = nullptr;
+  p->meta_cap = 0;
+  p->meta_pending = false;
+  const size_t n = round_up(need * 2, 4096);
+  FC_HIP(hipMalloc(reinterpret_cast<void**>(&p->dev_meta), n));
+  FC_HIP(hipHostMalloc(reinterpret_cast<void**>(&p->host_meta), n, hipHostMallocDefault));
+  p->meta_cap = n;
+  return FC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* fc_last_error(void) { return g_err; }
+
+const char* fc_kernel_name(int i) { return (i >= 0 && i < K_COUNT) ? kKernelNames[i] : ""; }
+
+int fc_pool_create(fc_pool** out, void* kv_base, size_t kv_bytes, int n_blocks, int block_size,
+                   int n_layers, int n_heads, int head_dim, int dtype) {
+  if (!out) return fail(FC_EINVAL, "out is NULL");
+  *out = nullptr;
+  if (!kv_base || (reinterpret_cast<uintptr_t>(kv_base) & 255))
+    return fail(FC_EINVAL, "kv_base must be a 256-byte aligned device pointer");
+  if (block_size != FC_BLOCK_SIZE) return fail(FC_EINVAL, "block_size must be 16");
+  if (dtype != FC_DTYPE_F16) return fail(FC_EINVAL, "dtype must be FC_DTYPE_F16");
+  if (head_dim != 64 && head_dim != 128) return fail(FC_EINVAL, "head_dim must be 64 or 128");
+  if (n_blocks < 1 || n_layers < 1 || n_heads < 1) return fail(FC_EINVAL, "bad pool geometry");
+  const size_t need = (size_t)n_layers * n_blocks * 2 * n_heads * FC_BLOCK_SIZE * head_dim * 2;
+  if (kv_bytes < need)
+    return fail(FC_EINVAL, "kv_bytes %zu is smaller than the pool geometry needs (%zu)", kv_bytes,
+                need);
+  FC_HIP(kernels_one_time_setup());
+  fc_pool* p = new fc_pool();
+  p->kv = static_cast<_Float16*>(kv_base);
+  p->kv_bytes = kv_bytes;
+  p->n_blocks = n_blocks;
+  p->n_layers = n_layers;
+  p->n_heads = n_heads;
+  p->head_dim = head_dim;
+  p->top = n_blocks;
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(&p->stack), (size_t)n_blocks * sizeof(int32_t));
+  if (e == hipSuccess) e = launch_stack_init(p->stack, n_blocks, nullptr);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&p->meta_event, hipEventDisableTiming);
+  for (int k = 0; k < K_COUNT && e == hipSuccess; ++k)
+    for (int j = 0; j < 2 && e == hipSuccess; ++j) e = hipEventCreate(&p->ev[k][j]);
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  if (e != hipSuccess) {
+    fc_pool_destroy(p);
+    return fail(FC_EDEVICE, "pool creation failed: %s", hipGetErrorString(e));
+  }
+  *out = p;
+  return FC_OK;
+}
+
+int fc_pool_destroy(fc_pool* p) {
+  if (!p) return FC_OK;
+  (void)hipDeviceSynchronize();
+  if (p->stack) (void)hipFree(p->stack);
+  if (p->raw_scores) (void)hipFree(p->raw_scores);
+  if (p->kept) (void)hipFree(p->kept);
+  if (p->ids) (void)hipFree(p->ids);
+  if (p->dev_meta) (void)hipFree(p->dev_meta);
+  if (p->host_meta) (void)hipHostFree(p->host_meta);
+  if (p->meta_event) (void)hipEventDestroy(p->meta_event);
+  for (int k = 0; k < K_COUNT; ++k)
+    for (int j = 0; j < 2; ++j)
+      if (p->ev[k][j]) (void)hipEventDestroy(p->ev[k][j]);
+  delete p;
+  return FC_OK;
+}
+
+int fc_pool_alloc(fc_pool* p, int n, int32_t* dev_out_ids, void* stream) {
+  if (!p) return fail(FC_EINVAL, "pool is NULL");
+  if (n < 0) return fail(FC_EINVAL, "n_blocks < 0");
+  if (n == 0) return FC_OK;
+  if (!dev_out_ids) return fail(FC_EINVAL, "dev_out_ids is NULL");
+  if (n > p->top) return fail(FC_ENOMEM, "asked for %d blocks, %d free", n, p->top);
+  FC_HIP(launch_pool_pop(p->stack, p->top, n, dev_out_ids, static_cast<hipStream_t>(stream)));
+  p->top -= n;
+  return FC_OK;
+}
+
+int fc_pool_free(fc_pool* p, const int32_t* dev_ids, int n, void* stream) {
+  if (!p) return fail(FC_EINVAL, "pool is NULL");
+  if (n < 0) return fail(FC_EINVAL, "n_blocks < 0");
+  if (n == 0) return FC_OK;
+  if (!dev_ids) return fail(FC_EINVAL, "dev_ids is NULL");
+  if (p->top + n > p->n_blocks)
+    return fail(FC_EINVAL, "freeing %d blocks with %d already free exceeds the pool (%d)", n,
+                p->top, p->n_blocks);
+  FC_HIP(launch_pool_push(p->stack, p->top, n, dev_ids, static_cast<hipStream_t>(stream)));
+  p->top += n;
+  return FC_OK;
+}
+
+int fc_pool_num_free(const fc_pool* p) { return p ? p->top : FC_EINVAL; }
+
+int fc_pool_export_state(fc_pool* p, int32_t* host_stack, int* top) {
+  if (!p || !host_stack || !top) return fail(FC_EINVAL, "NULL argument");
+  FC_HIP(hipDeviceSynchronize());
+  FC_HIP(hipMemcpy(host_stack, p->stack, (size_t)p->n_blocks * sizeof(int32_t),
+                   hipMemcpyDeviceToHost));
+  *top = p->top;
+  return FC_OK;
+}
+
+int fc_pool_import_state(fc_pool* p, const int32_t* host_stack, int top) {
+  if (!p || !host_stack) return fail(FC_EINVAL, "NULL argument");
+  if (top < 0 || top > p->n_blocks) return fail(FC_EINVAL, "top out of range");
+  FC_HIP(hipDeviceSynchronize());
+  FC_HIP(hipMemcpy(p->stack, host_stack, (size_t)p->n_blocks * sizeof(int32_t),
+                   hipMemcpyHostToDevice));
+  p->top = top;
+  return FC_OK;
+}
+
+int fc_set_profiling(fc_pool* p, int enable) {
+  if (!p) return fail(FC_EINVAL, "pool is NULL");
+  p->profiling = enable != 0;
+  return FC_OK;
+}
+
+int fc_get_kernel_times(fc_pool* p, float* host_ms) {
+  if (!p || !host_ms) return fail(FC_EINVAL, "NULL argument");
+  for (int k = 0; k < K_COUNT; ++k) {
+    host_ms[k] = 0.f;
+    if (!p->timed[k]) continue;
+    FC_HIP(hipEventSynchronize(p->ev[k][1]));
+    FC_HIP(hipEventElapsedTime(&host_ms[k], p->ev[k][0], p->ev[k][1]));
+  }
+  return FC_OK;
+}
+
+int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_req,
+                      int32_t* host_seq_lens, const void* dev_q_window, int window,
+                      const int32_t* host_method, const int32_t* host_budget, int n_req,
+                      int pool_kernel, float scale, float* dev_scores_out, int32_t* dev_kept_out,
+                      void* stream_) {
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  if (!p) return fail(FC_EINVAL, "pool is NULL");
+  if (n_req < 0) return fail(FC_EINVAL, "n_req < 0");
+  if (n_req == 0) return FC_OK;
+  if (!dev_block_tables || !host_seq_lens || !host_method || !host_budget)
+    return fail(FC_EINVAL, "NULL argument");
+  if (max_blocks_per_req < 1) return fail(FC_EINVAL, "max_blocks_per_req < 1");
+  if (pool_kernel < 1 || pool_kernel > FC_MAX_POOL_KERNEL || (pool_kernel & 1) == 0)
+    return fail(FC_EINVAL, "pool_kernel must be odd and in 1..%d", FC_MAX_POOL_KERNEL);
+
+  // ---- validate with host-known quantities; nothing is touched on error ----
+  const size_t n_lh = (size_t)p->n_layers * p->n_heads;
+  std::vector<ReqDesc> descs;
+  descs.reserve(n_req);
+  int total_new = 0, total_old = 0, max_len = 0;
+  size_t score_off = 0, kept_off = 0;
+  for (int r = 0; r < n_req; ++r) {
+    const int m = host_method[r];
+    if (m == FC_METHOD_NONE) continue;
+    const int L = host_seq_lens[r], B = host_budget[r];
+    if (m != FC_METHOD_SNAPKV && m != FC_METHOD_KNORM)
+      return fail(FC_EINVAL, "request %d: unknown method %d", r, m);
+    if (L < 1 || L > FC_MAX_SEQ_LEN)
+      return fail(FC_EINVAL, "request %d: length %d outside 1..%d", r, L, FC_MAX_SEQ_LEN);
+    if (B < 1 || B > L) return fail(FC_EINVAL, "request %d: budget %d outside 1..%d", r, B, L);
+    if (m == FC_METHOD_SNAPKV) {
+      if (window < 1 || window > FC_MAX_WINDOW)
+        return fail(FC_EINVAL, "window %d outside 1..%d", window, FC_MAX_WINDOW);
+      if (L < window || B < window)
+        return fail(FC_EINVAL, "request %d: SnapKV needs length and budget >= window", r);
+      if (!dev_q_window || (reinterpret_cast<uintptr_t>(dev_q_window) & 15))
+        return fail(FC_EINVAL, "dev_q_window must be a 16-byte aligned device pointer");
+    }
+    ReqDesc d;
+    d.seq_len = L;
+    d.budget = B;
+    d.method = m;
+    d.table_row = r;
+    d.n_old = (L + FC_BLOCK_SIZE - 1) / FC_BLOCK_SIZE;
+    d.n_new = (B + FC_BLOCK_SIZE - 1) / FC_BLOCK_SIZE;
+    if (d.n_old > max_blocks_per_req)
+      return fail(FC_EINVAL, "request %d: %d blocks exceed max_blocks_per_req %d", r, d.n_old,
+                  max_blocks_per_req);
+    d.old_off = total_old;
+    d.new_off = total_new;
+    d.score_off = (int64_t)score_off;
+    d.kept_off = (int64_t)kept_off;
+    d.q_off = (int64_t)((size_t)r * n_lh * (size_t)std::max(window, 0) * p->head_dim);
+    total_old += d.n_old;
+    total_new += d.n_new;
+    score_off += n_lh * (size_t)L;
+    kept_off += n_lh * (size_t)B;
+    max_len = std::max(max_len, L);
+    descs.push_back(d);
+  }
+  const int n_comp = (int)descs.size();
+  if (n_comp == 0) return FC_OK;
+  if (total_new > p->top)
+    return fail(FC_ENOMEM, "batch needs %d new blocks, %d free", total_new, p->top);
+
+  // ---- scratch and descriptors --------------------------------------------
+  int rc;
+  if ((rc = grow(&p->raw_scores, &p->raw_cap, score_off)) != FC_OK) return rc;
+  if (!dev_kept_out && (rc = grow(&p->kept, &p->kept_cap, kept_off)) != FC_OK) return rc;
+  if ((rc = grow(&p->ids, &p->ids_cap, (size_t)total_old + total_new)) != FC_OK) return rc;
+  const size_t desc_bytes = round_up((size_t)n_comp * sizeof(ReqDesc), 16);
+  const size_t order_bytes = round_up((size_t)n_comp * sizeof(int32_t), 16);
+  const size_t meta_bytes = desc_bytes + 3 * order_bytes;
+  if ((rc = grow_meta(p, meta_bytes)) != FC_OK) return rc;
+  if (p->meta_pending) {
+    // the previous call's descriptor upload must have left the staging buffer
+    FC_HIP(hipEventSynchronize(p->meta_event));
+    p->meta_pending = false;
+  }
+  memcpy(p->host_meta, descs.data(), (size_t)n_comp * sizeof(ReqDesc));
+  int32_t* order_all = reinterpret_cast<int32_t*>(p->host_meta + desc_bytes);
+  int32_t* order_snap = reinterpret_cast<int32_t*>(p->host_meta + desc_bytes + order_bytes);
+  int32_t* order_knorm = reinterpret_cast<int32_t*>(p->host_meta + desc_bytes + 2 * order_bytes);
+  std::iota(order_all, order_all + n_comp, 0);
+  // longest first, so that the tail of each launch is made of short units
+  std::stable_sort(order_all, order_all + n_comp,
+                   [&](int a, int b) { return descs[a].seq_len > descs[b].seq_len; });
+  int ns = 0, nk = 0;
+  for (int i = 0; i < n_comp; ++i) {
+    const int di = order_all[i];
+    if (descs[di].method == FC_METHOD_SNAPKV)
+      order_snap[ns++] = di;
+    else
+      order_knorm[nk++] = di;
+  }
+  FC_HIP(hipMemcpyAsync(p->dev_meta, p->host_meta, meta_bytes, hipMemcpyHostToDevice, stream));
+  FC_HIP(hipEventRecord(p->meta_event, stream));
+  p->meta_pending = true;
+
+  BatchParams bp;
+  bp.kv = p->kv;
+  bp.n_blocks = p->n_blocks;
+  bp.n_layers = p->n_layers;
+  bp.n_heads = p->n_heads;
+  bp.head_dim = p->head_dim;
+  bp.stack = p->stack;
+  bp.top_before = p->top;
+  bp.total_new = total_new;
+  bp.total_old = total_old;
+  bp.descs = reinterpret_cast<const ReqDesc*>(p->dev_meta);
+  bp.order_all = reinterpret_cast<const int32_t*>(p->dev_meta + desc_bytes);
+  bp.order_snap = reinterpret_cast<const int32_t*>(p->dev_meta + desc_bytes + order_bytes);
+  bp.order_knorm = reinterpret_cast<const int32_t*>(p->dev_meta + desc_bytes + 2 * order_bytes);
+  bp.n_comp = n_comp;
+  bp.n_snap = ns;
+  bp.n_knorm = nk;
+  bp.block_tables = dev_block_tables;
+  bp.max_blocks = max_blocks_per_req;
+  bp.old_ids = p->ids;
+  bp.new_ids = p->ids + total_old;
+  bp.q_window = static_cast<const _Float16*>(dev_q_window);
+  bp.window = window;
+  bp.pool_kernel = pool_kernel;
+  const float sc = (scale > 0.f) ? scale : 1.0f / sqrtf((float)p->head_dim);
+  bp.scale_log2e = sc * 1.44269504088896340736f;
+  bp.raw_scores = p->raw_scores;
+  bp.scores_out = dev_scores_out;
+  bp.kept = dev_kept_out ? dev_kept_out : p->kept;
+
+  // ---- the stage ------------------------------------------------------------
+  for (int k = 0; k < K_COUNT; ++k) p->timed[k] = false;
+  auto run = [&](int slot, bool active, auto&& launch) -> hipError_t {
+    if (!active) return hipSuccess;
+    hipError_t e = hipSuccess;
+    if (p->profiling) e = hipEventRecord(p->ev[slot][0], stream);
+    if (e == hipSuccess) e = launch();
+    if (e == hipSuccess && p->profiling) {
+      e = hipEventRecord(p->ev[slot][1], stream);
+      p->timed[slot] = true;
+    }
+    return e;
+  };
+  FC_HIP(run(K_PLAN_ALLOC, true, [&] { return launch_plan_alloc(bp, stream); }));
+  FC_HIP(run(K_SNAPKV_SCORE, ns > 0, [&] { return launch_snapkv_score(bp, stream); }));
+  FC_HIP(run(K_KNORM_SCORE, nk > 0, [&] { return launch_knorm_score(bp, stream); }));
+  FC_HIP(run(K_SELECT, true, [&] { return launch_select(bp, max_len, stream); }));
+  FC_HIP(run(K_GATHER, true, [&] { return launch_gather(bp, stream); }));
+  FC_HIP(run(K_RECLAIM, true, [&] { return launch_reclaim(bp, stream); }));
+
+  // ---- host mirrors ------------------------------------------------------------
+  p->top = p->top - total_new + total_old;
+  for (const ReqDesc& d : descs) host_seq_lens[d.table_row] = d.budget;
+  return FC_OK;
+}
+
+}  // extern "C"

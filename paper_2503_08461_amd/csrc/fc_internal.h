@@ -1,0 +1,76 @@
+// Internal declarations shared by the host API and the kernel launchers of
+// libfastcache.  Not part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fc {
+
+// One compressed request of a batch (device-visible copy of what the host
+// scheduler knows).  Offsets are in elements of the buffer they index.
+struct ReqDesc {
+  int32_t seq_len;    // L_r on entry
+  int32_t budget;     // B_r
+  int32_t method;     // FC_METHOD_*
+  int32_t table_row;  // row of dev_block_tables
+  int32_t n_old;      // ceil(L_r / 16)
+  int32_t n_new;      // ceil(B_r / 16)
+  int32_t old_off;    // start of this request in the saved old-id list
+  int32_t new_off;    // start of this request in the new-id list
+  int64_t score_off;  // start of [layer][head][L_r] in the score buffers
+  int64_t kept_off;   // start of [layer][head][B_r] in the kept buffer
+  int64_t q_off;      // start of [layer][head][window][d] in q_window
+};
+
+// Everything a kernel of the stage needs.  Passed by value.
+struct BatchParams {
+  // pool geometry
+  _Float16* kv;        // kv[layer][block][2][head][16][d]
+  int32_t n_blocks, n_layers, n_heads, head_dim;
+  // free stack
+  int32_t* stack;
+  int32_t top_before;  // top on entry to the call
+  int32_t total_new;   // sum of n_new
+  int32_t total_old;   // sum of n_old
+  // batch
+  const ReqDesc* descs;        // [n_comp] in batch order
+  const int32_t* order_all;    // [n_comp] desc indices, longest first
+  const int32_t* order_snap;   // [n_snap]
+  const int32_t* order_knorm;  // [n_knorm]
+  int32_t n_comp, n_snap, n_knorm;
+  int32_t* block_tables;       // caller's [n_req][max_blocks]
+  int32_t max_blocks;
+  int32_t* old_ids;            // [total_old] saved pre-compression ids
+  int32_t* new_ids;            // [total_new]
+  const _Float16* q_window;
+  int32_t window, pool_kernel;
+  float scale_log2e;           // scale * log2(e)
+  float* raw_scores;           // un-pooled scores, packed like scores_out
+  float* scores_out;           // nullable
+  int32_t* kept;               // kept indices, packed
+};
+
+enum KernelSlot {
+  K_PLAN_ALLOC = 0,
+  K_SNAPKV_SCORE = 1,
+  K_KNORM_SCORE = 2,
+  K_SELECT = 3,
+  K_GATHER = 4,
+  K_RECLAIM = 5,
+  K_COUNT = 6
+};
+
+// Launchers (fc_kernels.hip).  Each returns the hipError_t of the launch.
+hipError_t launch_stack_init(int32_t* stack, int n_blocks, hipStream_t s);
+hipError_t launch_pool_pop(const int32_t* stack, int top, int n, int32_t* out, hipStream_t s);
+hipError_t launch_pool_push(int32_t* stack, int top, int n, const int32_t* ids, hipStream_t s);
+hipError_t launch_plan_alloc(const BatchParams& p, hipStream_t s);
+hipError_t launch_snapkv_score(const BatchParams& p, hipStream_t s);
+hipError_t launch_knorm_score(const BatchParams& p, hipStream_t s);
+hipError_t launch_select(const BatchParams& p, int max_seq_len, hipStream_t s);
+hipError_t launch_gather(const BatchParams& p, hipStream_t s);
+hipError_t launch_reclaim(const BatchParams& p, hipStream_t s);
+hipError_t kernels_one_time_setup();
+
+}  // namespace fc

@@ -1,0 +1,593 @@
+// HIP kernels of the batched KV-cache compression stage, written for gfx950
+// (CDNA4: 64-wide wavefronts, MFMA, 160 KB LDS per CU).
+//
+// Pool layout (fixed by the public ABI):
+//   kv[layer][block][0=K,1=V][head][slot 0..15][d]   fp16
+// so one (layer, block, kv, head) chunk is 16*d contiguous halves (4 KiB at
+// d = 128) and one token row is d contiguous halves.
+
+#include "fc_internal.h"
+
+#include <float.h>
+
+namespace fc {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+static constexpr int kThreads = 256;  // 4 wavefronts per workgroup
+static constexpr int kWaves = 4;
+
+__device__ __forceinline__ int clamp_block(int blk, int n_blocks) {
+  // Block ids come from caller-owned device memory; an id outside the pool
+  // must not turn into an out-of-bounds access.
+  return ((unsigned)blk < (unsigned)n_blocks) ? blk : 0;
+}
+
+__device__ __forceinline__ half8 load_half8(const _Float16* p) {
+  return *reinterpret_cast<const half8*>(p);
+}
+
+__device__ __forceinline__ void store_half8(_Float16* p, half8 v) {
+  *reinterpret_cast<half8*>(p) = v;
+}
+
+// ---------------------------------------------------------------------------
+// free stack
+// ---------------------------------------------------------------------------
+
+__global__ void stack_init_kernel(int32_t* stack, int n_blocks) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n_blocks) stack[i] = n_blocks - 1 - i;
+}
+
+__global__ void pool_pop_kernel(const int32_t* stack, int top, int n, int32_t* out) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = stack[top - 1 - i];
+}
+
+__global__ void pool_push_kernel(int32_t* stack, int top, int n, const int32_t* ids) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) stack[top + i] = ids[i];
+}
+
+// Pops the new blocks of every compressed request (batch order) and saves the
+// pre-compression ids.  One workgroup per request; offsets are exclusive
+// prefix sums computed by the host, which knows every count.
+__global__ __launch_bounds__(kThreads) void plan_alloc_kernel(BatchParams p) {
+  const ReqDesc rd = p.descs[blockIdx.x];
+  const int32_t* row = p.block_tables + (size_t)rd.table_row * p.max_blocks;
+  for (int i = threadIdx.x; i < rd.n_old; i += kThreads)
+    p.old_ids[rd.old_off + i] = row[i];
+  for (int i = threadIdx.x; i < rd.n_new; i += kThreads)
+    p.new_ids[rd.new_off + i] = p.stack[p.top_before - 1 - rd.new_off - i];
+}
+
+// Zombie reclaim: pushes the pre-compression blocks (batch order, table
+// order) above the stack top left by plan_alloc and rewrites the table rows.
+__global__ __launch_bounds__(kThreads) void reclaim_kernel(BatchParams p) {
+  const ReqDesc rd = p.descs[blockIdx.x];
+  const int base = p.top_before - p.total_new;
+  for (int i = threadIdx.x; i < rd.n_old; i += kThreads)
+    p.stack[base + rd.old_off + i] = p.old_ids[rd.old_off + i];
+  int32_t* row = p.block_tables + (size_t)rd.table_row * p.max_blocks;
+  for (int i = threadIdx.x; i < p.max_blocks; i += kThreads)
+    row[i] = (i < rd.n_new) ? p.new_ids[rd.new_off + i] : -1;
+}
+
+// ---------------------------------------------------------------------------
+// SnapKV-style observation-window score
+// ---------------------------------------------------------------------------
+//
+// One workgroup per (request, layer, head).  A wavefront takes pool blocks
+// (16 tokens) round-robin and feeds them to v_mfma_f32_16x16x32_f16 straight
+// from global memory: lane l holds 8 consecutive channels
+// [32*ks + 8*(l/16), +8) of token l%16, which is both the A-operand layout
+// (rows = tokens) and the B-operand layout (columns = tokens) of that
+// instruction, and 4 lanes cover 64 contiguous bytes of a token row.
+//
+// Pass 1 (A = keys, B = queries): the 16x16 result has the window query on the
+// lane (l%16) and 4 tokens in the lane's registers, so every lane keeps an
+// online (max, sum-of-exp) pair for its query with no cross-lane traffic.
+// Pass 2 (A = queries, B = keys): the result has the token on the lane and 4
+// queries in registers, so the sum over window queries is an in-lane add plus
+// two cross-lane adds.  Softmax uses exp2 with scale*log2(e) folded in.
+//
+// The un-pooled column sums of the prefix are written to raw_scores; pooling
+// and the forced window are applied by the select kernel.
+
+template <int D, int NT>
+__global__ __launch_bounds__(kThreads) void snapkv_score_kernel(BatchParams p) {
+  constexpr int KS = D / 32;
+  const int n_lh = p.n_layers * p.n_heads;
+  const int slot = blockIdx.x / n_lh;
+  const int lh = blockIdx.x - slot * n_lh;
+  const int layer = lh / p.n_heads;
+  const int head = lh - layer * p.n_heads;
+  const ReqDesc rd = p.descs[p.order_snap[slot]];
+  const int L = rd.seq_len;
+  const int W = p.window;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int c16 = lane & 15;
+  const int q4 = lane >> 4;
+  const int32_t* old_ids = p.old_ids + rd.old_off;
+
+  __shared__ float sm_m[kWaves][4][64];
+  __shared__ float sm_z[kWaves][4][64];
+  __shared__ float sm_final[64];
+
+  // window queries, resident in registers for both passes
+  const _Float16* qbase = p.q_window + rd.q_off + (size_t)lh * W * D;
+  half8 qreg[NT][KS];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const int row = nt * 16 + c16;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+      qreg[nt][ks] = (row < W) ? load_half8(qbase + (size_t)row * D + ks * 32 + q4 * 8) : z;
+    }
+  }
+
+  const size_t blk_stride = (size_t)2 * p.n_heads * 16 * D;
+  const _Float16* kbase = p.kv + (size_t)layer * p.n_blocks * blk_stride +
+                          (size_t)head * 16 * D + (size_t)c16 * D + q4 * 8;
+  const float c = p.scale_log2e;
+  const int nb = (L + 15) >> 4;
+  const int n_unmasked = (L - W) >> 4;  // blocks that lie wholly before the window
+
+  auto load_block = [&](int b, half8 (&k)[KS]) {
+    const int blk = clamp_block(old_ids[b], p.n_blocks);
+    const _Float16* kp = kbase + (size_t)blk * blk_stride;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) k[ks] = load_half8(kp + ks * 32);
+  };
+
+  // ---- pass 1: row maxima and normalisers --------------------------------
+  float m[NT], z[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    m[nt] = -3.0e38f;
+    z[nt] = 0.f;
+  }
+  {
+    half8 kc[KS], kn[KS];
+    int b = wave;
+    if (b < nb) load_block(b, kc);
+    for (; b < nb; b += kWaves) {
+      if (b + kWaves < nb) load_block(b + kWaves, kn);
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(kc[ks], qreg[nt][ks], acc, 0, 0, 0);
+        float t[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) t[r] = acc[r] * c;
+        if (b >= n_unmasked) {
+          // query i at position L-W+i sees tokens <= its own position
+          const int limit = L - W + nt * 16 + c16;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int tok = b * 16 + q4 * 4 + r;
+            if (tok > limit) t[r] = -INFINITY;
+          }
+        }
+        const float bm = fmaxf(fmaxf(t[0], t[1]), fmaxf(t[2], t[3]));
+        const float mn = fmaxf(m[nt], bm);
+        float zz = z[nt] * __builtin_amdgcn_exp2f(m[nt] - mn);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) zz += __builtin_amdgcn_exp2f(t[r] - mn);
+        z[nt] = zz;
+        m[nt] = mn;
+      }
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) kc[ks] = kn[ks];
+    }
+  }
+
+  // combine the 16 partial (max, sum) pairs of every query
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    sm_m[wave][q4][nt * 16 + c16] = m[nt];
+    sm_z[wave][q4][nt * 16 + c16] = z[nt];
+  }
+  __syncthreads();
+  if (threadIdx.x < 64) {
+    const int row = threadIdx.x;
+    float out = INFINITY;  // padded rows contribute exp2(-inf) = 0
+    if (row < W) {
+      float mm = -3.0e38f;
+      for (int w = 0; w < kWaves; ++w)
+        for (int q = 0; q < 4; ++q) mm = fmaxf(mm, sm_m[w][q][row]);
+      float zz = 0.f;
+      for (int w = 0; w < kWaves; ++w)
+        for (int q = 0; q < 4; ++q)
+          zz += sm_z[w][q][row] * __builtin_amdgcn_exp2f(sm_m[w][q][row] - mm);
+      out = mm + log2f(zz);
+    }
+    sm_final[row] = out;
+  }
+  __syncthreads();
+
+  // ---- pass 2: column sums of the soft-maxed rows over the prefix ---------
+  const int n_prefix = L - W;
+  const int nb2 = (n_prefix + 15) >> 4;
+  float mrow[NT][4];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) mrow[nt][r] = sm_final[nt * 16 + q4 * 4 + r];
+
+  float* raw = p.raw_scores + rd.score_off + (size_t)lh * L;
+  {
+    half8 kc[KS], kn[KS];
+    int b = wave;
+    if (b < nb2) load_block(b, kc);
+    for (; b < nb2; b += kWaves) {
+      if (b + kWaves < nb2) load_block(b + kWaves, kn);
+      float colsum = 0.f;
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qreg[nt][ks], kc[ks], acc, 0, 0, 0);
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          colsum += __builtin_amdgcn_exp2f(acc[r] * c - mrow[nt][r]);
+      }
+      colsum += __shfl_xor(colsum, 16);
+      colsum += __shfl_xor(colsum, 32);
+      const int tok = b * 16 + c16;
+      if (q4 == 0 && tok < n_prefix) raw[tok] = colsum;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) kc[ks] = kn[ks];
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// key-norm score: raw[j] = -||k_j||_2
+// ---------------------------------------------------------------------------
+//
+// One workgroup per (request, layer, head); a wavefront reads one 16-token
+// chunk with fully coalesced 128-bit loads (64 lanes x 16 B = 1 KiB per
+// instruction) and reduces the squares over the lanes that share a row.
+
+template <int D>
+__global__ __launch_bounds__(kThreads) void knorm_score_kernel(BatchParams p) {
+  constexpr int LPR = D / 8;     // lanes per token row
+  constexpr int RPI = 64 / LPR;  // rows per load instruction
+  constexpr int NI = 16 / RPI;   // load instructions per block
+  const int n_lh = p.n_layers * p.n_heads;
+  const int slot = blockIdx.x / n_lh;
+  const int lh = blockIdx.x - slot * n_lh;
+  const int layer = lh / p.n_heads;
+  const int head = lh - layer * p.n_heads;
+  const ReqDesc rd = p.descs[p.order_knorm[slot]];
+  const int L = rd.seq_len;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int32_t* old_ids = p.old_ids + rd.old_off;
+  const size_t blk_stride = (size_t)2 * p.n_heads * 16 * D;
+  const _Float16* kbase = p.kv + (size_t)layer * p.n_blocks * blk_stride +
+                          (size_t)head * 16 * D + lane * 8;
+  float* raw = p.raw_scores + rd.score_off + (size_t)lh * L;
+  const int nb = (L + 15) >> 4;
+  for (int b = wave; b < nb; b += kWaves) {
+    const int blk = clamp_block(old_ids[b], p.n_blocks);
+    const _Float16* kp = kbase + (size_t)blk * blk_stride;
+    half8 v[NI];
+#pragma unroll
+    for (int k = 0; k < NI; ++k) v[k] = load_half8(kp + k * 512);
+#pragma unroll
+    for (int k = 0; k < NI; ++k) {
+      float s = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float x = (float)v[k][e];
+        s += x * x;
+      }
+#pragma unroll
+      for (int o = 1; o < LPR; o <<= 1) s += __shfl_xor(s, o);
+      const int tok = b * 16 + k * RPI + lane / LPR;
+      if ((lane % LPR) == 0 && tok < L) raw[tok] = -sqrtf(s);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// per-head top-budget selection
+// ---------------------------------------------------------------------------
+//
+// One workgroup per (request, layer, head).  Scores become order-preserving
+// 32-bit keys held in LDS; the budget-th largest key is found by a 4 x 8-bit
+// most-significant-digit radix select (LDS histogram + suffix scan); the
+// kept indices are then emitted in ascending token order by a ballot /
+// popcount compaction in which keys equal to the threshold are admitted in
+// index order until the budget is met (ties go to the lower index).
+
+__device__ __forceinline__ uint32_t score_key(float s) {
+  s += 0.0f;  // -0 and +0 compare equal, give them one key
+  const uint32_t u = __float_as_uint(s);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__global__ __launch_bounds__(kThreads) void select_kernel(BatchParams p) {
+  extern __shared__ uint32_t keys[];
+  __shared__ int hist[256];
+  __shared__ int wsum[kWaves];
+  __shared__ int sel[2];
+  __shared__ int cnt[kWaves][2];
+
+  const int n_lh = p.n_layers * p.n_heads;
+  const int slot = blockIdx.x / n_lh;
+  const int lh = blockIdx.x - slot * n_lh;
+  const ReqDesc rd = p.descs[p.order_all[slot]];
+  const int L = rd.seq_len;
+  const int B = rd.budget;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const float* raw = p.raw_scores + rd.score_off + (size_t)lh * L;
+  float* out = p.scores_out ? p.scores_out + rd.score_off + (size_t)lh * L : nullptr;
+
+  // 1. final scores -> keys
+  if (rd.method == 1 /* FC_METHOD_SNAPKV */) {
+    const int n_prefix = L - p.window;
+    const int h = p.pool_kernel >> 1;
+    for (int j = tid; j < L; j += kThreads) {
+      float s = INFINITY;  // window tokens are always kept
+      if (j < n_prefix) {
+        const int lo = max(0, j - h), hi = min(n_prefix - 1, j + h);
+        s = raw[lo];
+        for (int t = lo + 1; t <= hi; ++t) s = fmaxf(s, raw[t]);
+      }
+      if (out) out[j] = s;
+      keys[j] = score_key(s);
+    }
+  } else {
+    for (int j = tid; j < L; j += kThreads) {
+      const float s = raw[j];
+      if (out) out[j] = s;
+      keys[j] = score_key(s);
+    }
+  }
+  __syncthreads();
+
+  // 2. radix select of the B-th largest key
+  uint32_t prefix = 0, mask = 0;
+  int remaining = B;
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    hist[tid] = 0;
+    __syncthreads();
+    for (int j = tid; j < L; j += kThreads) {
+      const uint32_t k = keys[j];
+      if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1);
+    }
+    __syncthreads();
+    const int cdig = hist[tid];
+    int v = cdig;  // inclusive scan over digits 0..tid
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int n = __shfl_up(v, o);
+      if (lane >= o) v += n;
+    }
+    if (lane == 63) wsum[wave] = v;
+    __syncthreads();
+    int base = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      if (w < wave) base += wsum[w];
+      total += wsum[w];
+    }
+    const int above = total - (v + base);  // candidates with a larger digit
+    if (above < remaining && above + cdig >= remaining) {
+      sel[0] = tid;
+      sel[1] = remaining - above;
+    }
+    __syncthreads();
+    prefix |= (uint32_t)sel[0] << shift;
+    mask |= 0xFFu << shift;
+    remaining = sel[1];
+    __syncthreads();
+  }
+  const uint32_t thr = prefix;  // B-th largest key
+  const int need_eq = remaining;  // how many keys equal to it are kept
+
+  // 3. ordered compaction; each wavefront owns a contiguous token segment
+  const int seg = (((L + kWaves - 1) / kWaves) + 63) & ~63;
+  const int j0 = wave * seg;
+  const int j1 = min(L, j0 + seg);
+  int n_gt = 0, n_eq = 0;
+  for (int jb = j0; jb < j1; jb += 64) {
+    const int j = jb + lane;
+    const bool in = j < j1;
+    const uint32_t k = in ? keys[j] : 0u;
+    n_gt += __popcll(__ballot(in && k > thr));
+    n_eq += __popcll(__ballot(in && k == thr));
+  }
+  if (lane == 0) {
+    cnt[wave][0] = n_gt;
+    cnt[wave][1] = n_eq;
+  }
+  __syncthreads();
+  int gt_before = 0, eq_before = 0;
+  for (int w = 0; w < wave; ++w) {
+    gt_before += cnt[w][0];
+    eq_before += cnt[w][1];
+  }
+  int eq_run = eq_before;
+  int kept_run = gt_before + min(eq_before, need_eq);
+  int32_t* kept = p.kept + rd.kept_off + (size_t)lh * B;
+  const uint64_t lt_mask = (1ull << lane) - 1ull;
+  for (int jb = j0; jb < j1; jb += 64) {
+    const int j = jb + lane;
+    const bool in = j < j1;
+    const uint32_t k = in ? keys[j] : 0u;
+    const bool is_gt = in && k > thr;
+    const bool is_eq = in && k == thr;
+    const uint64_t eq_ballot = __ballot(is_eq);
+    const int eq_rank = eq_run + __popcll(eq_ballot & lt_mask);
+    const bool keep = is_gt || (is_eq && eq_rank < need_eq);
+    const uint64_t keep_ballot = __ballot(keep);
+    if (keep) kept[kept_run + __popcll(keep_ballot & lt_mask)] = j;
+    eq_run += __popcll(eq_ballot);
+    kept_run += __popcll(keep_ballot);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// gather / compact
+// ---------------------------------------------------------------------------
+//
+// One workgroup per (request, layer, head); a wavefront fills one new block
+// (16 output slots) at a time for K and V.  D/8 lanes move one row with
+// 128-bit accesses, so a wavefront instruction moves 64/(D/8) rows; the
+// destination chunk is contiguous.
+
+template <int D>
+__global__ __launch_bounds__(kThreads) void gather_kernel(BatchParams p) {
+  constexpr int LPR = D / 8;
+  constexpr int RPI = 64 / LPR;
+  constexpr int NI = 16 / RPI;
+  const int n_lh = p.n_layers * p.n_heads;
+  const int slot = blockIdx.x / n_lh;
+  const int lh = blockIdx.x - slot * n_lh;
+  const int layer = lh / p.n_heads;
+  const int head = lh - layer * p.n_heads;
+  const ReqDesc rd = p.descs[p.order_all[slot]];
+  const int B = rd.budget;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int32_t* old_ids = p.old_ids + rd.old_off;
+  const int32_t* new_ids = p.new_ids + rd.new_off;
+  const int32_t* kept = p.kept + rd.kept_off + (size_t)lh * B;
+  const size_t chunk = (size_t)16 * D;               // one (block, kv, head)
+  const size_t v_off = (size_t)p.n_heads * chunk;    // K chunk -> V chunk of a block
+  const size_t blk_stride = 2 * v_off;
+  _Float16* base = p.kv + (size_t)layer * p.n_blocks * blk_stride + (size_t)head * chunk +
+                   (lane % LPR) * 8;
+  const int row_in_instr = lane / LPR;
+  for (int nbk = wave; nbk < rd.n_new; nbk += kWaves) {
+    const int dblk = clamp_block(new_ids[nbk], p.n_blocks);
+    _Float16* dst = base + (size_t)dblk * blk_stride;
+    half8 kk[NI], vv[NI];
+    bool ok[NI];
+#pragma unroll
+    for (int k = 0; k < NI; ++k) {
+      const int row = k * RPI + row_in_instr;
+      const int t = nbk * 16 + row;
+      ok[k] = t < B;
+      if (ok[k]) {
+        const int idx = min(max(kept[t], 0), rd.seq_len - 1);
+        const int sblk = clamp_block(old_ids[idx >> 4], p.n_blocks);
+        const _Float16* src = base + (size_t)sblk * blk_stride + (size_t)(idx & 15) * D;
+        kk[k] = load_half8(src);
+        vv[k] = load_half8(src + v_off);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < NI; ++k) {
+      if (ok[k]) {
+        const int row = k * RPI + row_in_instr;
+        store_half8(dst + (size_t)row * D, kk[k]);
+        store_half8(dst + (size_t)row * D + v_off, vv[k]);
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------
+
+hipError_t kernels_one_time_setup() {
+  // the select kernel may need more than the default 64 KiB of dynamic LDS
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, 32768 * 4);
+}
+
+hipError_t launch_stack_init(int32_t* stack, int n_blocks, hipStream_t s) {
+  if (n_blocks <= 0) return hipSuccess;
+  stack_init_kernel<<<(n_blocks + 255) / 256, 256, 0, s>>>(stack, n_blocks);
+  return hipGetLastError();
+}
+
+hipError_t launch_pool_pop(const int32_t* stack, int top, int n, int32_t* out, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  pool_pop_kernel<<<(n + 255) / 256, 256, 0, s>>>(stack, top, n, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_pool_push(int32_t* stack, int top, int n, const int32_t* ids, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  pool_push_kernel<<<(n + 255) / 256, 256, 0, s>>>(stack, top, n, ids);
+  return hipGetLastError();
+}
+
+hipError_t launch_plan_alloc(const BatchParams& p, hipStream_t s) {
+  plan_alloc_kernel<<<p.n_comp, kThreads, 0, s>>>(p);
+  return hipGetLastError();
+}
+
+hipError_t launch_reclaim(const BatchParams& p, hipStream_t s) {
+  reclaim_kernel<<<p.n_comp, kThreads, 0, s>>>(p);
+  return hipGetLastError();
+}
+
+template <int D>
+static hipError_t launch_snapkv_d(const BatchParams& p, hipStream_t s) {
+  const unsigned grid = (unsigned)p.n_snap * p.n_layers * p.n_heads;
+  const int nt = (p.window + 15) / 16;
+  switch (nt) {
+    case 1: snapkv_score_kernel<D, 1><<<grid, kThreads, 0, s>>>(p); break;
+    case 2: snapkv_score_kernel<D, 2><<<grid, kThreads, 0, s>>>(p); break;
+    case 3: snapkv_score_kernel<D, 3><<<grid, kThreads, 0, s>>>(p); break;
+    case 4: snapkv_score_kernel<D, 4><<<grid, kThreads, 0, s>>>(p); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_snapkv_score(const BatchParams& p, hipStream_t s) {
+  if (p.n_snap == 0) return hipSuccess;
+  if (p.head_dim == 128) return launch_snapkv_d<128>(p, s);
+  if (p.head_dim == 64) return launch_snapkv_d<64>(p, s);
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_knorm_score(const BatchParams& p, hipStream_t s) {
+  if (p.n_knorm == 0) return hipSuccess;
+  const unsigned grid = (unsigned)p.n_knorm * p.n_layers * p.n_heads;
+  if (p.head_dim == 128)
+    knorm_score_kernel<128><<<grid, kThreads, 0, s>>>(p);
+  else if (p.head_dim == 64)
+    knorm_score_kernel<64><<<grid, kThreads, 0, s>>>(p);
+  else
+    return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+hipError_t launch_select(const BatchParams& p, int max_seq_len, hipStream_t s) {
+  const unsigned grid = (unsigned)p.n_comp * p.n_layers * p.n_heads;
+  const size_t lds = (size_t)max_seq_len * sizeof(uint32_t);
+  select_kernel<<<grid, kThreads, lds, s>>>(p);
+  return hipGetLastError();
+}
+
+hipError_t launch_gather(const BatchParams& p, hipStream_t s) {
+  const unsigned grid = (unsigned)p.n_comp * p.n_layers * p.n_heads;
+  if (p.head_dim == 128)
+    gather_kernel<128><<<grid, kThreads, 0, s>>>(p);
+  else if (p.head_dim == 64)
+    gather_kernel<64><<<grid, kThreads, 0, s>>>(p);
+  else
+    return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+}  // namespace fc

@@ -1,0 +1,224 @@
+"""ctypes binding over libfastcache.so (the C ABI of include/fastcache.h).
+
+Argument marshalling only: torch tensors supply device pointers, numpy arrays
+supply host arrays, and every step of the stage runs in the library's HIP
+kernels.  There is no fallback: if the library has not been built, or no GPU
+is present, the calls raise.
+"""
+
+import ctypes
+import os
+
+import numpy as np
+
+FC_OK, FC_EINVAL, FC_ENOMEM, FC_EDEVICE = 0, -1, -2, -3
+FC_METHOD_NONE, FC_METHOD_SNAPKV, FC_METHOD_KNORM = 0, 1, 2
+FC_DTYPE_F16 = 0
+FC_BLOCK_SIZE = 16
+FC_N_KERNELS = 6
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libfastcache.so")
+
+EXPORTS = [
+    "fc_pool_create", "fc_pool_destroy", "fc_pool_alloc", "fc_pool_free",
+    "fc_pool_num_free", "fc_pool_export_state", "fc_pool_import_state",
+    "fc_compress_batch", "fc_set_profiling", "fc_get_kernel_times",
+    "fc_kernel_name", "fc_last_error",
+]
+
+_lib = None
+
+
+class FastCacheError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("libfastcache error %d: %s" % (code, text))
+        self.code = code
+
+
+def _hip_runtimes_loaded():
+    paths = set()
+    with open("/proc/self/maps") as f:
+        for line in f:
+            if "libamdhip64" in line:
+                paths.add(line.split()[-1])
+    return sorted(paths)
+
+
+def load_library():
+    """Loads libfastcache.so once.  torch is imported first so that the HIP
+    runtime torch ships is the one the library binds to (same soname)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            "%s is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'`"
+            % LIB_PATH)
+    import torch  # noqa: F401  (loads libamdhip64 before the library asks for it)
+    lib = ctypes.CDLL(LIB_PATH)
+    runtimes = _hip_runtimes_loaded()
+    if len(runtimes) > 1:
+        raise RuntimeError("two HIP runtimes in one process: %s" % runtimes)
+    vp, i32p, i = ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32), ctypes.c_int
+    lib.fc_pool_create.argtypes = [ctypes.POINTER(vp), vp, ctypes.c_size_t, i, i, i, i, i, i]
+    lib.fc_pool_destroy.argtypes = [vp]
+    lib.fc_pool_alloc.argtypes = [vp, i, vp, vp]
+    lib.fc_pool_free.argtypes = [vp, vp, i, vp]
+    lib.fc_pool_num_free.argtypes = [vp]
+    lib.fc_pool_export_state.argtypes = [vp, i32p, ctypes.POINTER(i)]
+    lib.fc_pool_import_state.argtypes = [vp, i32p, i]
+    lib.fc_compress_batch.argtypes = [vp, vp, i, i32p, vp, i, i32p, i32p, i, i,
+                                      ctypes.c_float, vp, vp, vp]
+    lib.fc_set_profiling.argtypes = [vp, i]
+    lib.fc_get_kernel_times.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
+    lib.fc_kernel_name.argtypes = [i]
+    lib.fc_kernel_name.restype = ctypes.c_char_p
+    lib.fc_last_error.restype = ctypes.c_char_p
+    for name in EXPORTS:
+        if name not in ("fc_kernel_name", "fc_last_error"):
+            getattr(lib, name).restype = i
+    _lib = lib
+    return lib
+
+
+def _check(rc):
+    if rc < 0:
+        raise FastCacheError(rc, _lib.fc_last_error().decode())
+    return rc
+
+
+def _dev_ptr(t, dtype=None):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError("expected dtype %s, got %s" % (dtype, t.dtype))
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _host_i32(a):
+    if not (isinstance(a, np.ndarray) and a.dtype == np.int32 and a.flags.c_contiguous):
+        raise ValueError("expected a contiguous int32 numpy array")
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+class PoolHandle:
+    """Opaque fc_pool* plus the geometry it was created with (for marshalling)."""
+
+    def __init__(self, ptr, kv, n_blocks, n_layers, n_heads, head_dim):
+        self.ptr = ptr
+        self.kv = kv  # keeps the caller's tensor alive
+        self.n_blocks, self.n_layers, self.n_heads, self.head_dim = \
+            n_blocks, n_layers, n_heads, head_dim
+
+
+def fc_pool_create(kv, n_blocks, n_layers, n_heads, head_dim, block_size=FC_BLOCK_SIZE):
+    """kv: torch fp16 device tensor holding kv[layer][block][2][head][16][head_dim]."""
+    import torch
+    lib = load_library()
+    out = ctypes.c_void_p()
+    _check(lib.fc_pool_create(ctypes.byref(out), _dev_ptr(kv, torch.float16),
+                              kv.numel() * kv.element_size(), n_blocks, block_size,
+                              n_layers, n_heads, head_dim, FC_DTYPE_F16))
+    return PoolHandle(out, kv, n_blocks, n_layers, n_heads, head_dim)
+
+
+def fc_pool_destroy(pool):
+    lib = load_library()
+    if pool.ptr:
+        _check(lib.fc_pool_destroy(pool.ptr))
+        pool.ptr = None
+
+
+def fc_pool_alloc(pool, n_blocks, out_ids=None, stream=None):
+    """Pops n_blocks ids into out_ids (int32 device tensor; created if None)."""
+    import torch
+    lib = load_library()
+    if out_ids is None:
+        out_ids = torch.empty(max(n_blocks, 0), dtype=torch.int32, device=pool.kv.device)
+    if out_ids.numel() < n_blocks:
+        raise ValueError("out_ids too small")
+    _check(lib.fc_pool_alloc(pool.ptr, n_blocks, _dev_ptr(out_ids, torch.int32),
+                             _stream_ptr(stream)))
+    return out_ids
+
+
+def fc_pool_free(pool, ids, stream=None):
+    import torch
+    lib = load_library()
+    _check(lib.fc_pool_free(pool.ptr, _dev_ptr(ids, torch.int32), ids.numel(),
+                            _stream_ptr(stream)))
+
+
+def fc_pool_num_free(pool):
+    return _check(load_library().fc_pool_num_free(pool.ptr))
+
+
+def fc_pool_export_state(pool):
+    """Returns (stack int32[n_blocks] numpy, top)."""
+    lib = load_library()
+    stack = np.empty(pool.n_blocks, dtype=np.int32)
+    top = ctypes.c_int()
+    _check(lib.fc_pool_export_state(pool.ptr, _host_i32(stack), ctypes.byref(top)))
+    return stack, top.value
+
+
+def fc_pool_import_state(pool, stack, top):
+    lib = load_library()
+    if stack.shape[0] != pool.n_blocks:
+        raise ValueError("stack must have n_blocks entries")
+    _check(lib.fc_pool_import_state(pool.ptr, _host_i32(stack), int(top)))
+
+
+def fc_compress_batch(pool, block_tables, seq_lens, q_window, window, method, budget,
+                      pool_kernel=7, scale=0.0, scores_out=None, kept_out=None, stream=None):
+    """block_tables: int32 device tensor [n_req][max_blocks] (in/out);
+    seq_lens, method, budget: int32 numpy arrays [n_req] (seq_lens in/out);
+    q_window: fp16 device tensor [n_req][n_layers][n_heads][window][head_dim] or None;
+    scores_out / kept_out: optional fp32 / int32 device tensors (packed)."""
+    import torch
+    lib = load_library()
+    n_req = int(seq_lens.shape[0])
+    if block_tables.dim() != 2 or block_tables.shape[0] != n_req:
+        raise ValueError("block_tables must be [n_req][max_blocks]")
+    if method.shape[0] != n_req or budget.shape[0] != n_req:
+        raise ValueError("method / budget must have n_req entries")
+    if q_window is not None:
+        want = (n_req, pool.n_layers, pool.n_heads, window, pool.head_dim)
+        if tuple(q_window.shape) != want:
+            raise ValueError("q_window must have shape %s" % (want,))
+    comp = method != FC_METHOD_NONE
+    if scores_out is not None:
+        need = int((seq_lens[comp].astype(np.int64)).sum()) * pool.n_layers * pool.n_heads
+        if scores_out.numel() < need:
+            raise ValueError("scores_out too small")
+    if kept_out is not None:
+        need = int((budget[comp].astype(np.int64)).sum()) * pool.n_layers * pool.n_heads
+        if kept_out.numel() < need:
+            raise ValueError("kept_out too small")
+    _check(lib.fc_compress_batch(
+        pool.ptr, _dev_ptr(block_tables, torch.int32), int(block_tables.shape[1]),
+        _host_i32(seq_lens), _dev_ptr(q_window, torch.float16), int(window),
+        _host_i32(method), _host_i32(budget), n_req, int(pool_kernel), float(scale),
+        _dev_ptr(scores_out, torch.float32), _dev_ptr(kept_out, torch.int32),
+        _stream_ptr(stream)))
+
+
+def fc_set_profiling(pool, enable):
+    _check(load_library().fc_set_profiling(pool.ptr, 1 if enable else 0))
+
+
+def fc_get_kernel_times(pool):
+    """{kernel name: milliseconds} of the last fc_compress_batch (profiling on)."""
+    lib = load_library()
+    ms = (ctypes.c_float * FC_N_KERNELS)()
+    _check(lib.fc_get_kernel_times(pool.ptr, ms))
+    return {lib.fc_kernel_name(k).decode(): float(ms[k]) for k in range(FC_N_KERNELS)}

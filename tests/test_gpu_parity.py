@@ -1,0 +1,203 @@
+"""GPU parity tests: HIP library (through the C ABI) vs the CPU oracle on the
+same seeded inputs.  Run with `-m gpu` on an MI355X."""
+
+import numpy as np
+import pytest
+
+from oracle import fastcache_oracle as fo
+from paper_2503_08461_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _sbs(wl, **kw):
+    from parity_util import SideBySide
+    return SideBySide(wl, **kw)
+
+
+def _run(wl, **kw):
+    s = _sbs(wl)
+    try:
+        stats = s.compress_and_compare(**kw)
+    finally:
+        s.close()
+    print(wl.name, stats, flush=True)
+    assert stats["max_rel_err"] < 2e-3
+    return stats
+
+
+def test_config1_tiny_snapkv():
+    stats = _run(synth.make_workload(1))
+    assert stats["units"] == 4
+
+
+def test_config2_shape_reduced_heads():
+    # LLaVA-1.5-7B per-head shape, 640 tokens = 40 full blocks, window 32
+    _run(synth.make_workload(2, n_layers=2, n_heads=3))
+
+
+def test_config3_mixed_methods_permuted_tables():
+    # ragged lengths in [600, 1200], SnapKV and key-norm in one batch
+    _run(synth.make_workload(3, n_layers=1, n_heads=2, n_req=6))
+
+
+def test_config4_window64_long():
+    # several thousand tokens per head, window 64
+    _run(synth.make_workload(4, n_layers=1, n_heads=2, n_req=3))
+
+
+def test_config5_lengths_reduced():
+    _run(synth.make_workload(5, n_layers=1, n_heads=2, n_req=4, max_len=5000))
+
+
+def _custom(L, B, method, W=16, d=64, n_heads=2, n_layers=1, seed=11, n_blocks=None):
+    lens = np.array(L, dtype=np.int32)
+    nb = n_blocks or int(sum(synth.blocks_for(int(x)) for x in lens) * 2 + 8)
+    return synth.Workload("custom", n_layers, n_heads, d, nb, W, 7, lens,
+                          np.array(method, dtype=np.int32), np.array(B, dtype=np.int32),
+                          seed, False, True)
+
+
+@pytest.mark.parametrize("W", [1, 5, 16, 17, 33, 48, 64])
+def test_window_sizes(W):
+    _run(_custom([200, 131], [max(W, 40), max(W, 70)], [fo.METHOD_SNAPKV] * 2, W=W, d=128))
+
+
+@pytest.mark.parametrize("pool_kernel", [1, 3, 15])
+def test_pool_kernels(pool_kernel):
+    _run(_custom([150], [60], [fo.METHOD_SNAPKV]), pool_kernel=pool_kernel)
+
+
+def test_degenerate_budgets():
+    # B == L (identity), B == W (window only), L == W == B, single token
+    wl = _custom([97, 80, 16, 1, 33], [97, 16, 16, 1, 33],
+                 [fo.METHOD_KNORM, fo.METHOD_SNAPKV, fo.METHOD_SNAPKV, fo.METHOD_KNORM,
+                  fo.METHOD_SNAPKV])
+    _run(wl)
+
+
+def test_none_requests_pass_through():
+    wl = _custom([100, 64, 50], [30, 1, 20], [fo.METHOD_SNAPKV, fo.METHOD_NONE, fo.METHOD_KNORM])
+    _run(wl)
+
+
+def test_custom_scale():
+    _run(_custom([300], [100], [fo.METHOD_SNAPKV], d=128), scale=0.05)
+
+
+def test_all_ties_go_to_lower_index():
+    """All-zero queries: every prefix token has the same score, so the kept
+    prefix must be the lowest indices (no tolerance band can hide this: the
+    self-consistency check compares against the GPU's own scores)."""
+    import torch  # noqa: F401
+    from parity_util import SideBySide
+    wl = _custom([256, 77], [64, 40], [fo.METHOD_SNAPKV] * 2, W=16)
+    q = np.zeros((2, 1, 2, 16, 64), dtype=np.float16)
+    s = SideBySide(wl, q_host=q)
+    try:
+        s.compress_and_compare()
+        kept_prefix0 = 64 - 16
+        # request 0: prefix kept == 0..47 means the first 48 rows are unchanged
+        kv = s.kv_dev.cpu().numpy()
+        b0 = s.bt_host[0, 0]
+        assert (kv[:, b0].view(np.uint16) == s.kv_host[:, b0].view(np.uint16)).all()
+        assert kept_prefix0 == 48
+    finally:
+        s.close()
+
+
+def test_zero_keys_knorm_ties():
+    """Identical (zero) keys: -0.0 scores everywhere, lowest indices win."""
+    from parity_util import SideBySide
+    wl = _custom([100], [37], [fo.METHOD_KNORM])
+    kv = synth.fill_pool_host(wl)
+    kv[:, :, 0] = 0
+    s = SideBySide(wl, kv_host=kv)
+    try:
+        s.compress_and_compare()
+    finally:
+        s.close()
+
+
+def test_errors_leave_everything_untouched():
+    import torch
+    from paper_2503_08461_amd import fastcache as fc
+    from parity_util import SideBySide
+    wl = _custom([200], [100], [fo.METHOD_SNAPKV], n_blocks=16)   # 13 live, 3 free, needs 7
+    s = SideBySide(wl)
+    try:
+        before_kv = s.kv_dev.clone()
+        before_bt = s.bt_dev.clone()
+        stack0, top0 = fc.fc_pool_export_state(s.pool)
+
+        def expect(code, **kw):
+            args = dict(methods=wl.methods, budgets=wl.budgets, window=wl.window, pool_kernel=7)
+            args.update(kw)
+            lens = s.lens_g.copy()
+            with pytest.raises(fc.FastCacheError) as ei:
+                fc.fc_compress_batch(s.pool, s.bt_dev, lens, s.q_dev, args["window"],
+                                     args["methods"], args["budgets"], args["pool_kernel"])
+            assert ei.value.code == code
+            torch.cuda.synchronize()
+            assert (lens == s.lens_g).all()
+            assert torch.equal(before_kv, s.kv_dev) and torch.equal(before_bt, s.bt_dev)
+            st, top = fc.fc_pool_export_state(s.pool)
+            assert top == top0 and (st == stack0).all()
+
+        expect(fc.FC_ENOMEM)
+        expect(fc.FC_EINVAL, budgets=np.array([0], np.int32))
+        expect(fc.FC_EINVAL, budgets=np.array([201], np.int32))
+        expect(fc.FC_EINVAL, budgets=np.array([8], np.int32))            # below the window
+        expect(fc.FC_EINVAL, methods=np.array([9], np.int32))
+        expect(fc.FC_EINVAL, pool_kernel=4)
+        expect(fc.FC_EINVAL, window=65)
+        with pytest.raises(fc.FastCacheError) as ei:
+            fc.fc_pool_alloc(s.pool, 4)
+        assert ei.value.code == fc.FC_ENOMEM
+        with pytest.raises(fc.FastCacheError) as ei:
+            fc.fc_pool_free(s.pool, torch.zeros(14, dtype=torch.int32, device=s.dev))
+        assert ei.value.code == fc.FC_EINVAL
+        # and a request that fits still works afterwards
+        s.compress_and_compare(budgets=np.array([40], np.int32))
+    finally:
+        s.close()
+
+
+def test_alloc_free_are_lifo_and_match_the_oracle():
+    import torch
+    from paper_2503_08461_amd import fastcache as fc
+    kv = torch.zeros((1, 32, 2, 1, 16, 64), dtype=torch.float16, device="cuda:0")
+    pool = fc.fc_pool_create(kv, 32, 1, 1, 64)
+    st = fo.FreeStack(32)
+    try:
+        a = fc.fc_pool_alloc(pool, 5)
+        assert a.cpu().tolist() == st.alloc(5).tolist() == [0, 1, 2, 3, 4]
+        b = fc.fc_pool_alloc(pool, 3)
+        assert b.cpu().tolist() == st.alloc(3).tolist()
+        fc.fc_pool_free(pool, a)
+        st.free(np.arange(5, dtype=np.int32))
+        c = fc.fc_pool_alloc(pool, 7)
+        assert c.cpu().tolist() == st.alloc(7).tolist()
+        sg, tg = fc.fc_pool_export_state(pool)
+        assert tg == st.top and (sg[:tg] == st.stack[:tg]).all()
+        # rewind
+        fresh = fo.FreeStack(32)
+        fc.fc_pool_import_state(pool, fresh.stack.copy(), fresh.top)
+        assert fc.fc_pool_num_free(pool) == 32
+        assert fc.fc_pool_alloc(pool, 2).cpu().tolist() == [0, 1]
+    finally:
+        fc.fc_pool_destroy(pool)
+
+
+def test_repeated_compression_of_the_same_requests():
+    """Compress, then compress the compressed caches again (lengths shrink,
+    tables are the library's own output)."""
+    from parity_util import SideBySide
+    wl = _custom([500, 333], [200, 150], [fo.METHOD_SNAPKV, fo.METHOD_KNORM], d=128)
+    s = SideBySide(wl)
+    try:
+        s.compress_and_compare()
+        s.compress_and_compare(budgets=np.array([64, 20], np.int32))
+        s.compress_and_compare(budgets=np.array([16, 20], np.int32))
+    finally:
+        s.close()
