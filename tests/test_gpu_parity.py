@@ -47,7 +47,33 @@ def test_config4_window64_long():
 
 
 def test_config5_lengths_reduced():
-    _run(synth.make_workload(5, n_layers=1, n_heads=2, n_req=4, max_len=5000))
+    """Pool at 90% occupancy: the batch is trimmed to what fits (new blocks are
+    taken before old ones come back), the rest rides along as METHOD_NONE and
+    is compressed by the following calls."""
+    from paper_2503_08461_amd import fastcache as fc
+    wl = synth.make_workload(5, n_layers=1, n_heads=2, n_req=6, max_len=5000)
+    s = _sbs(wl)
+    try:
+        todo = list(range(wl.n_req))
+        calls = 0
+        while todo:
+            free = fc.fc_pool_num_free(s.pool)
+            methods = np.zeros(wl.n_req, dtype=np.int32)
+            picked = []
+            for r in todo:
+                need = synth.blocks_for(int(wl.budgets[r]))
+                if need <= free:
+                    free -= need
+                    methods[r] = wl.methods[r]
+                    picked.append(r)
+            assert picked, "nothing fits"
+            stats = s.compress_and_compare(methods=methods)
+            print("config5 sub-batch", picked, stats, flush=True)
+            todo = [r for r in todo if r not in picked]
+            calls += 1
+        assert calls >= 2
+    finally:
+        s.close()
 
 
 def _custom(L, B, method, W=16, d=64, n_heads=2, n_layers=1, seed=11, n_blocks=None):
@@ -134,8 +160,11 @@ def test_errors_leave_everything_untouched():
             args = dict(methods=wl.methods, budgets=wl.budgets, window=wl.window, pool_kernel=7)
             args.update(kw)
             lens = s.lens_g.copy()
+            q = s.q_dev
+            if args["window"] != wl.window:
+                q = torch.zeros((1, 1, 2, args["window"], 64), dtype=torch.float16, device=s.dev)
             with pytest.raises(fc.FastCacheError) as ei:
-                fc.fc_compress_batch(s.pool, s.bt_dev, lens, s.q_dev, args["window"],
+                fc.fc_compress_batch(s.pool, s.bt_dev, lens, q, args["window"],
                                      args["methods"], args["budgets"], args["pool_kernel"])
             assert ei.value.code == code
             torch.cuda.synchronize()
