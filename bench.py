@@ -1,0 +1,177 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched KV-cache compression stage on one MI355X.
+
+A step is one fc_compress_batch over the whole batch (score -> select ->
+allocate -> gather -> reclaim) with every input already resident in HBM.
+Between steps only the pool metadata (free stack, block tables, lengths) is
+rewound; that happens outside the timed region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload config4|config3|config2]
+"""
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
+
+
+def cpu_baseline(dw, seconds=15.0, seed=0):
+    """The CPU oracle, as it stands, timed on a bounded random sample of
+    (request, layer, head) units of the same workload (bytes downloaded from
+    the device pool; the download is not timed).  One thread."""
+    import numpy as np
+    import torch
+    from threadpoolctl import threadpool_limits
+    from oracle import fastcache_oracle as fo
+    wl = dw.wl
+    rng = np.random.Generator(np.random.PCG64(seed))
+    n_lh = wl.n_layers * wl.n_heads
+    bt0 = dw.bt0.cpu().numpy()
+    spent, token_heads, units = 0.0, 0, 0
+    with threadpool_limits(limits=1):
+        while spent < seconds and units < 4096:
+            r = int(rng.integers(wl.n_req))
+            l = int(rng.integers(wl.n_layers))
+            h = int(rng.integers(wl.n_heads))
+            if wl.methods[r] == fo.METHOD_NONE:
+                continue
+            L, B = int(wl.seq_lens[r]), int(wl.budgets[r])
+            n_old, n_new = fo.blocks_for(L, wl.block_size), fo.blocks_for(B, wl.block_size)
+            ids = torch.from_numpy(bt0[r, :n_old].astype(np.int64)).to(dw.dev)
+            mini = np.zeros((1, n_old + n_new, 2, 1, wl.block_size, wl.head_dim), np.float16)
+            mini[0, :n_old, :, 0] = dw.kv[l, ids, :, h].cpu().numpy()
+            q = dw.q[r:r + 1, l:l + 1, h:h + 1].cpu().numpy()
+            st = fo.FreeStack(n_old + n_new)
+            bt = st.alloc(n_old)[None, :].copy()
+            lens = np.array([L], dtype=np.int32)
+            t0 = time.perf_counter()
+            status, _, _ = fo.compress_batch(mini, st, bt, lens, q, wl.window,
+                                             wl.methods[r:r + 1], wl.budgets[r:r + 1],
+                                             wl.pool_kernel)
+            spent += time.perf_counter() - t0
+            assert status is None
+            token_heads += L
+            units += 1
+    return {
+        "value": token_heads / n_lh / spent,
+        "unit": "tokens/s",
+        "cores": 1,
+        "kind": "oracle",
+        "sample": "%d random (request, layer, head) units of %s = %d token-heads in %.1f s, "
+                  "scaled by 1/%d layer-heads per token" % (units, wl.name, token_heads, spent,
+                                                            n_lh),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="config4", choices=["config2", "config3", "config4"])
+    ap.add_argument("--cpu-seconds", type=float, default=15.0,
+                    help="CPU time budget of the oracle baseline (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the stage has no collectives); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2503_08461_amd import synth, fastcache as fc
+    from paper_2503_08461_amd.device_setup import DeviceWorkload
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    fc.load_library()
+    wl = synth.make_workload(int(args.workload[-1]))
+    need = wl.pool_bytes() + (8 << 30)
+    total = torch.cuda.get_device_properties(0).total_memory
+    if need > total:
+        print("bench.py: %s needs %.0f GiB, device has %.0f GiB" % (
+            wl.name, need / 2**30, total / 2**30), file=sys.stderr)
+        sys.exit(2)
+
+    dw = DeviceWorkload(wl, verbose=True)
+    fc.fc_set_profiling(dw.pool, True)
+    for _ in range(args.warmup):
+        dw.rewind()
+        dw.compress()
+    torch.cuda.synchronize()
+
+    wall = []
+    ktimes = {}
+    for _ in range(args.steps):
+        dw.rewind()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        dw.compress()
+        torch.cuda.synchronize()
+        wall.append(time.perf_counter() - t0)
+        for name, ms in fc.fc_get_kernel_times(dw.pool).items():
+            ktimes.setdefault(name, []).append(ms)
+    sec_per_step = sum(wall) / len(wall)
+    kavg = {k: sum(v) / len(v) for k, v in ktimes.items()}
+
+    comp = wl.methods != synth.METHOD_NONE
+    tokens = int(wl.seq_lens[comp].astype(np.int64).sum())
+    path_bytes = dw.algorithmic_bytes()
+    kbytes = dw.kernel_algorithmic_bytes()
+    # dominant kernel = the one with the largest average duration
+    dom = max(("snapkv_score", "knorm_score", "gather"), key=lambda k: kavg.get(k, 0.0))
+    dom_gbps = kbytes[dom] / (kavg[dom] * 1e-3) / 1e9
+
+    out = {
+        "metric": "KV tokens compressed/sec (all layers x heads), batched",
+        "value": tokens / sec_per_step,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": sec_per_step * 1e3,
+        "ms_per_step_min": min(wall) * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16 in, f32 accumulate/softmax",
+        "data": "synthetic",
+        "config": {
+            "workload": wl.name,
+            "n_req": wl.n_req, "tokens": tokens, "n_layers": wl.n_layers,
+            "n_heads": wl.n_heads, "head_dim": wl.head_dim, "window": wl.window,
+            "pool_blocks": wl.n_blocks, "pool_GiB": round(wl.pool_bytes() / 2**30, 1),
+            "kept_fraction": round(float(wl.budgets[comp].sum()) / tokens, 4),
+        },
+        "path": {
+            "algorithmic_bytes": path_bytes,
+            "achieved_GBps": path_bytes / sec_per_step / 1e9,
+            "frac_of_hbm_peak": path_bytes / sec_per_step / 1e9 / HBM_PEAK_GBPS,
+        },
+        "kernel_ms": {k: round(v, 4) for k, v in kavg.items()},
+        "roofline": {
+            "kernel": dom,
+            "bound": "hbm",
+            "achieved": dom_gbps,
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": dom_gbps / HBM_PEAK_GBPS,
+            "traffic": None,
+        },
+    }
+    if args.cpu_seconds > 0:
+        out["cpu_baseline"] = cpu_baseline(dw, args.cpu_seconds)
+    dw.close()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,77 @@
+"""Harness plumbing shared by bench.py and the full-size GPU tests: puts a
+synthetic workload into HBM (pool memory, window queries, block tables built
+through the library's own alloc/free calls).  No arithmetic of the stage."""
+
+import numpy as np
+
+from . import fastcache as fc
+from . import synth
+
+
+class DeviceWorkload:
+    def __init__(self, wl, device="cuda:0", verbose=False):
+        import torch
+        self.torch, self.wl = torch, wl
+        self.dev = torch.device(device)
+        if verbose:
+            print("[setup] %s: pool %.1f GiB, %d requests, %d tokens" % (
+                wl.name, wl.pool_bytes() / 2**30, wl.n_req, wl.total_tokens), flush=True)
+        self.kv = torch.empty(wl.pool_shape(), dtype=torch.float16, device=self.dev)
+        synth.fill_pool_device(wl, self.kv)
+        self.q = synth.fill_q_window_device(wl, self.dev)
+        self.pool = fc.fc_pool_create(self.kv, wl.n_blocks, wl.n_layers, wl.n_heads, wl.head_dim)
+        rows = synth.build_block_tables(
+            wl, lambda n: fc.fc_pool_alloc(self.pool, n),
+            lambda ids: fc.fc_pool_free(self.pool, ids),
+            lambda ids, ix: ids[torch.from_numpy(ix).to(self.dev)].contiguous())
+        self.bt = torch.full((wl.n_req, wl.max_blocks), -1, dtype=torch.int32, device=self.dev)
+        for r in range(wl.n_req):
+            self.bt[r, :rows[r].shape[0]] = rows[r]
+        self.lens = wl.seq_lens.copy()
+        torch.cuda.synchronize()
+        # snapshot of the metadata so a benchmark can rewind between repetitions
+        # (data blocks need no rewind: compaction writes only into free blocks)
+        self.bt0 = self.bt.clone()
+        self.stack0, self.top0 = fc.fc_pool_export_state(self.pool)
+        if verbose:
+            print("[setup] done", flush=True)
+
+    def rewind(self):
+        fc.fc_pool_import_state(self.pool, self.stack0, self.top0)
+        self.bt.copy_(self.bt0)
+        self.lens[:] = self.wl.seq_lens
+
+    def compress(self, scores_out=None, kept_out=None):
+        wl = self.wl
+        fc.fc_compress_batch(self.pool, self.bt, self.lens, self.q, wl.window, wl.methods,
+                             wl.budgets, wl.pool_kernel, 0.0, scores_out, kept_out)
+
+    def close(self):
+        fc.fc_pool_destroy(self.pool)
+        self.kv = None
+
+    # ---- accounting (algorithmic bytes, stated per token per (layer, head)) ----
+
+    def algorithmic_bytes(self):
+        """Whole path: read K once to score (2*d bytes per token-head), re-read
+        and write the kept K and V rows (2 * 2 * 2*d bytes per kept token-head)."""
+        wl = self.wl
+        n_lh = wl.n_layers * wl.n_heads
+        row = 2 * wl.head_dim
+        comp = wl.methods != synth.METHOD_NONE
+        tokens = int(wl.seq_lens[comp].astype(np.int64).sum())
+        kept = int(wl.budgets[comp].astype(np.int64).sum())
+        return n_lh * (tokens * row + kept * 4 * row)
+
+    def kernel_algorithmic_bytes(self):
+        wl = self.wl
+        n_lh = wl.n_layers * wl.n_heads
+        row = 2 * wl.head_dim
+        snap = wl.methods == synth.METHOD_SNAPKV
+        kn = wl.methods == synth.METHOD_KNORM
+        comp = wl.methods != synth.METHOD_NONE
+        return {
+            "snapkv_score": n_lh * int(wl.seq_lens[snap].astype(np.int64).sum()) * row,
+            "knorm_score": n_lh * int(wl.seq_lens[kn].astype(np.int64).sum()) * row,
+            "gather": n_lh * int(wl.budgets[comp].astype(np.int64).sum()) * 4 * row,
+        }
