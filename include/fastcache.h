@@ -89,6 +89,8 @@ int fc_pool_num_free(const fc_pool* pool);
 /*
  * Copies the free stack to host_stack (host, int32[n_blocks]; entries
  * [0, *top) are meaningful) after waiting for all device work.  Synchronous.
+ * Also reports, as FC_EDEVICE, a bounded wait between workgroups that ran
+ * out inside an earlier fc_compress_batch (its scores are then invalid).
  */
 int fc_pool_export_state(fc_pool* pool, int32_t* host_stack, int* top);
 
@@ -142,6 +144,18 @@ int fc_compress_batch(fc_pool* pool, int32_t* dev_block_tables, int max_blocks_p
                       const int32_t* host_method, const int32_t* host_budget, int n_req,
                       int pool_kernel, float scale, float* dev_scores_out,
                       int32_t* dev_kept_out, void* stream);
+
+/*
+ * Which SnapKV score kernel fc_compress_batch uses.  FC_SCORE_AUTO (default):
+ * the one-pass kernel (K read once, logits kept in registers, workgroups of a
+ * long head cooperate) whenever the device can hold its grid and every head
+ * of the batch fits, else the two-pass kernel (K read twice, no cooperation
+ * between workgroups, any length).  The other two values force one of them;
+ * forcing one-pass makes fc_compress_batch return FC_EINVAL when it cannot
+ * be used.  Both produce the same scores up to fp32 rounding.
+ */
+enum { FC_SCORE_AUTO = 0, FC_SCORE_TWO_PASS = 1, FC_SCORE_ONE_PASS = 2 };
+int fc_set_score_mode(fc_pool* pool, int mode);
 
 /*
  * Per-kernel timing for benchmarks.  With profiling enabled every kernel

@@ -64,6 +64,15 @@ struct fc_pool {
   hipEvent_t meta_event = nullptr;
   bool meta_pending = false;
 
+  // one-pass SnapKV score kernel
+  int32_t* team_counters = nullptr;
+  size_t team_counters_cap = 0;
+  float* team_stats = nullptr;
+  size_t team_stats_cap = 0;
+  int32_t* error_flag = nullptr;  // device, one int, zero unless a bounded wait ran out
+  int score_mode = FC_SCORE_AUTO;
+  int team_grid[FC_MAX_WINDOW / 16 + 1] = {};  // co-resident grid per query-tile count, -1 = none
+
   bool profiling = false;
   hipEvent_t ev[K_COUNT][2] = {};
   bool timed[K_COUNT] = {};
@@ -134,6 +143,8 @@ int fc_pool_create(fc_pool** out, void* kv_base, size_t kv_bytes, int n_blocks, 
   p->top = n_blocks;
   hipError_t e = hipMalloc(reinterpret_cast<void**>(&p->stack), (size_t)n_blocks * sizeof(int32_t));
   if (e == hipSuccess) e = launch_stack_init(p->stack, n_blocks, nullptr);
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->error_flag), sizeof(int32_t));
+  if (e == hipSuccess) e = launch_zero_ints(p->error_flag, 1, nullptr);
   if (e == hipSuccess) e = hipEventCreateWithFlags(&p->meta_event, hipEventDisableTiming);
   for (int k = 0; k < K_COUNT && e == hipSuccess; ++k)
     for (int j = 0; j < 2 && e == hipSuccess; ++j) e = hipEventCreate(&p->ev[k][j]);
@@ -153,6 +164,9 @@ int fc_pool_destroy(fc_pool* p) {
   if (p->raw_scores) (void)hipFree(p->raw_scores);
   if (p->kept) (void)hipFree(p->kept);
   if (p->ids) (void)hipFree(p->ids);
+  if (p->team_counters) (void)hipFree(p->team_counters);
+  if (p->team_stats) (void)hipFree(p->team_stats);
+  if (p->error_flag) (void)hipFree(p->error_flag);
   if (p->dev_meta) (void)hipFree(p->dev_meta);
   if (p->host_meta) (void)hipHostFree(p->host_meta);
   if (p->meta_event) (void)hipEventDestroy(p->meta_event);
@@ -192,6 +206,9 @@ int fc_pool_num_free(const fc_pool* p) { return p ? p->top : FC_EINVAL; }
 int fc_pool_export_state(fc_pool* p, int32_t* host_stack, int* top) {
   if (!p || !host_stack || !top) return fail(FC_EINVAL, "NULL argument");
   FC_HIP(hipDeviceSynchronize());
+  int32_t flag = 0;
+  FC_HIP(hipMemcpy(&flag, p->error_flag, sizeof(flag), hipMemcpyDeviceToHost));
+  if (flag) return fail(FC_EDEVICE, "a bounded wait between workgroups ran out in an earlier call");
   FC_HIP(hipMemcpy(host_stack, p->stack, (size_t)p->n_blocks * sizeof(int32_t),
                    hipMemcpyDeviceToHost));
   *top = p->top;
@@ -205,6 +222,14 @@ int fc_pool_import_state(fc_pool* p, const int32_t* host_stack, int top) {
   FC_HIP(hipMemcpy(p->stack, host_stack, (size_t)p->n_blocks * sizeof(int32_t),
                    hipMemcpyHostToDevice));
   p->top = top;
+  return FC_OK;
+}
+
+int fc_set_score_mode(fc_pool* p, int mode) {
+  if (!p) return fail(FC_EINVAL, "pool is NULL");
+  if (mode != FC_SCORE_AUTO && mode != FC_SCORE_TWO_PASS && mode != FC_SCORE_ONE_PASS)
+    return fail(FC_EINVAL, "unknown score mode %d", mode);
+  p->score_mode = mode;
   return FC_OK;
 }
 
@@ -290,8 +315,45 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
   if (total_new > p->top)
     return fail(FC_ENOMEM, "batch needs %d new blocks, %d free", total_new, p->top);
 
-  // ---- scratch and descriptors --------------------------------------------
+  // ---- one-pass SnapKV scoring: team sizes, if the device can hold the grid --
   int rc;
+  int team_grid = 0;
+  size_t n_team_counters = 0, n_team_stats = 0;
+  bool any_snap = false;
+  for (const ReqDesc& d : descs) any_snap |= d.method == FC_METHOD_SNAPKV;
+  if (any_snap && p->score_mode != FC_SCORE_TWO_PASS) {
+    const int nt = (window + 15) / 16;
+    if (p->team_grid[nt] == 0) {
+      const int gsz = team_grid_size(p->head_dim, window);
+      p->team_grid[nt] = gsz > 0 ? gsz : -1;
+    }
+    team_grid = std::max(p->team_grid[nt], 0);
+    const int cap_blocks = team_capacity_tokens(window) / FC_BLOCK_SIZE;
+    for (ReqDesc& d : descs) {
+      d.team_size = 1;
+      d.team_counter = 0;
+      d.team_stats = 0;
+      if (d.method != FC_METHOD_SNAPKV || team_grid == 0) continue;
+      d.team_size = (d.n_old + cap_blocks - 1) / cap_blocks;
+      if (d.team_size > team_grid) {
+        team_grid = 0;  // some head does not fit the co-resident grid
+        continue;
+      }
+      const int n_teams = team_grid / d.team_size;
+      d.team_counter = (int32_t)n_team_counters;
+      d.team_stats = (int64_t)n_team_stats;
+      n_team_counters += n_teams;
+      n_team_stats += (size_t)n_teams * 2 * d.team_size * 128;
+    }
+    if (team_grid == 0 && p->score_mode == FC_SCORE_ONE_PASS)
+      return fail(FC_EINVAL, "one-pass scoring is not possible for this batch on this device");
+  }
+  if (team_grid > 0) {
+    if ((rc = grow(&p->team_counters, &p->team_counters_cap, n_team_counters)) != FC_OK) return rc;
+    if ((rc = grow(&p->team_stats, &p->team_stats_cap, n_team_stats)) != FC_OK) return rc;
+  }
+
+  // ---- scratch and descriptors --------------------------------------------
   if ((rc = grow(&p->raw_scores, &p->raw_cap, score_off)) != FC_OK) return rc;
   if (!dev_kept_out && (rc = grow(&p->kept, &p->kept_cap, kept_off)) != FC_OK) return rc;
   if ((rc = grow(&p->ids, &p->ids_cap, (size_t)total_old + total_new)) != FC_OK) return rc;
@@ -353,6 +415,9 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
   bp.raw_scores = p->raw_scores;
   bp.scores_out = dev_scores_out;
   bp.kept = dev_kept_out ? dev_kept_out : p->kept;
+  bp.team_counters = p->team_counters;
+  bp.team_stats = p->team_stats;
+  bp.error_flag = p->error_flag;
 
   // ---- the stage ------------------------------------------------------------
   for (int k = 0; k < K_COUNT; ++k) p->timed[k] = false;
@@ -368,7 +433,12 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
     return e;
   };
   FC_HIP(run(K_PLAN_ALLOC, true, [&] { return launch_plan_alloc(bp, stream); }));
-  FC_HIP(run(K_SNAPKV_SCORE, ns > 0, [&] { return launch_snapkv_score(bp, stream); }));
+  if (ns > 0 && team_grid > 0)
+    FC_HIP(launch_zero_ints(p->team_counters, (int)n_team_counters, stream));
+  FC_HIP(run(K_SNAPKV_SCORE, ns > 0, [&] {
+    return team_grid > 0 ? launch_snapkv_score_team(bp, team_grid, stream)
+                         : launch_snapkv_score(bp, stream);
+  }));
   FC_HIP(run(K_KNORM_SCORE, nk > 0, [&] { return launch_knorm_score(bp, stream); }));
   FC_HIP(run(K_SELECT, true, [&] { return launch_select(bp, max_len, stream); }));
   FC_HIP(run(K_GATHER, true, [&] { return launch_gather(bp, stream); }));

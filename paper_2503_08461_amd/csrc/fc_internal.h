@@ -21,6 +21,10 @@ struct ReqDesc {
   int64_t score_off;  // start of [layer][head][L_r] in the score buffers
   int64_t kept_off;   // start of [layer][head][B_r] in the kept buffer
   int64_t q_off;      // start of [layer][head][window][d] in q_window
+  // one-pass SnapKV score kernel: workgroups that share one (layer, head)
+  int32_t team_size;     // g_r
+  int32_t team_counter;  // first of this request's n_wg/g_r team counters
+  int64_t team_stats;    // first float of this request's exchange buffers
 };
 
 // Everything a kernel of the stage needs.  Passed by value.
@@ -49,6 +53,10 @@ struct BatchParams {
   float* raw_scores;           // un-pooled scores, packed like scores_out
   float* scores_out;           // nullable
   int32_t* kept;               // kept indices, packed
+  // one-pass SnapKV score kernel (persistent, co-resident grid)
+  int32_t* team_counters;      // zeroed before the launch
+  float* team_stats;           // (max, sum) exchange between team members
+  int32_t* error_flag;         // set if a bounded wait ran out
 };
 
 enum KernelSlot {
@@ -67,6 +75,13 @@ hipError_t launch_pool_pop(const int32_t* stack, int top, int n, int32_t* out, h
 hipError_t launch_pool_push(int32_t* stack, int top, int n, const int32_t* ids, hipStream_t s);
 hipError_t launch_plan_alloc(const BatchParams& p, hipStream_t s);
 hipError_t launch_snapkv_score(const BatchParams& p, hipStream_t s);
+// One-pass variant.  team_capacity_tokens(head_dim, window) is how many tokens
+// one workgroup can hold; team_grid_size() is the co-resident grid (0 if the
+// device cannot run it); launch_zero_ints clears the team counters.
+int team_capacity_tokens(int window);
+int team_grid_size(int head_dim, int window);
+hipError_t launch_zero_ints(int32_t* p, int n, hipStream_t s);
+hipError_t launch_snapkv_score_team(const BatchParams& p, int grid, hipStream_t s);
 hipError_t launch_knorm_score(const BatchParams& p, hipStream_t s);
 hipError_t launch_select(const BatchParams& p, int max_seq_len, hipStream_t s);
 hipError_t launch_gather(const BatchParams& p, hipStream_t s);

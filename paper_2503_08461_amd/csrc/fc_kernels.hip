@@ -6,31 +6,11 @@
 // so one (layer, block, kv, head) chunk is 16*d contiguous halves (4 KiB at
 // d = 128) and one token row is d contiguous halves.
 
-#include "fc_internal.h"
+#include "fc_device.h"
 
 #include <float.h>
 
 namespace fc {
-
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-
-static constexpr int kThreads = 256;  // 4 wavefronts per workgroup
-static constexpr int kWaves = 4;
-
-__device__ __forceinline__ int clamp_block(int blk, int n_blocks) {
-  // Block ids come from caller-owned device memory; an id outside the pool
-  // must not turn into an out-of-bounds access.
-  return ((unsigned)blk < (unsigned)n_blocks) ? blk : 0;
-}
-
-__device__ __forceinline__ half8 load_half8(const _Float16* p) {
-  return *reinterpret_cast<const half8*>(p);
-}
-
-__device__ __forceinline__ void store_half8(_Float16* p, half8 v) {
-  *reinterpret_cast<half8*>(p) = v;
-}
 
 // ---------------------------------------------------------------------------
 // free stack

@@ -61,7 +61,7 @@ def check_kept(gk, g_scores, ok, o_scores, budget, where=""):
 class SideBySide:
     """Small workloads only: the whole pool lives on the host too."""
 
-    def __init__(self, wl, device="cuda:0", kv_host=None, q_host=None):
+    def __init__(self, wl, device="cuda:0", kv_host=None, q_host=None, score_mode=None):
         import torch
         from paper_2503_08461_amd import fastcache as fc
         self.torch, self.fc, self.wl = torch, fc, wl
@@ -72,6 +72,8 @@ class SideBySide:
         self.q_dev = torch.from_numpy(self.q_host.copy()).to(self.dev)
         self.pool = fc.fc_pool_create(self.kv_dev, wl.n_blocks, wl.n_layers, wl.n_heads,
                                       wl.head_dim)
+        if score_mode is not None:
+            fc.fc_set_score_mode(self.pool, score_mode)
         self.stack = fo.FreeStack(wl.n_blocks)
         # block tables through the public calls of each pool
         rows_o = synth.build_block_tables(wl, self.stack.alloc, self.stack.free,

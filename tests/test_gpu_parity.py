@@ -10,13 +10,20 @@ from paper_2503_08461_amd import synth
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(params=[1, 2], ids=["two_pass", "one_pass"])
+def score_mode(request):
+    """Both SnapKV score kernels must meet the same bar (FC_SCORE_TWO_PASS = 1,
+    FC_SCORE_ONE_PASS = 2)."""
+    return request.param
+
+
 def _sbs(wl, **kw):
     from parity_util import SideBySide
     return SideBySide(wl, **kw)
 
 
-def _run(wl, **kw):
-    s = _sbs(wl)
+def _run(wl, score_mode=None, **kw):
+    s = _sbs(wl, score_mode=score_mode)
     try:
         stats = s.compress_and_compare(**kw)
     finally:
@@ -26,33 +33,33 @@ def _run(wl, **kw):
     return stats
 
 
-def test_config1_tiny_snapkv():
-    stats = _run(synth.make_workload(1))
+def test_config1_tiny_snapkv(score_mode):
+    stats = _run(synth.make_workload(1), score_mode)
     assert stats["units"] == 4
 
 
-def test_config2_shape_reduced_heads():
+def test_config2_shape_reduced_heads(score_mode):
     # LLaVA-1.5-7B per-head shape, 640 tokens = 40 full blocks, window 32
-    _run(synth.make_workload(2, n_layers=2, n_heads=3))
+    _run(synth.make_workload(2, n_layers=2, n_heads=3), score_mode)
 
 
-def test_config3_mixed_methods_permuted_tables():
+def test_config3_mixed_methods_permuted_tables(score_mode):
     # ragged lengths in [600, 1200], SnapKV and key-norm in one batch
-    _run(synth.make_workload(3, n_layers=1, n_heads=2, n_req=6))
+    _run(synth.make_workload(3, n_layers=1, n_heads=2, n_req=6), score_mode)
 
 
-def test_config4_window64_long():
+def test_config4_window64_long(score_mode):
     # several thousand tokens per head, window 64
-    _run(synth.make_workload(4, n_layers=1, n_heads=2, n_req=3))
+    _run(synth.make_workload(4, n_layers=1, n_heads=2, n_req=3), score_mode)
 
 
-def test_config5_lengths_reduced():
+def test_config5_lengths_reduced(score_mode):
     """Pool at 90% occupancy: the batch is trimmed to what fits (new blocks are
     taken before old ones come back), the rest rides along as METHOD_NONE and
     is compressed by the following calls."""
     from paper_2503_08461_amd import fastcache as fc
     wl = synth.make_workload(5, n_layers=1, n_heads=2, n_req=6, max_len=5000)
-    s = _sbs(wl)
+    s = _sbs(wl, score_mode=score_mode)
     try:
         todo = list(range(wl.n_req))
         calls = 0
@@ -85,33 +92,33 @@ def _custom(L, B, method, W=16, d=64, n_heads=2, n_layers=1, seed=11, n_blocks=N
 
 
 @pytest.mark.parametrize("W", [1, 5, 16, 17, 33, 48, 64])
-def test_window_sizes(W):
-    _run(_custom([200, 131], [max(W, 40), max(W, 70)], [fo.METHOD_SNAPKV] * 2, W=W, d=128))
+def test_window_sizes(W, score_mode):
+    _run(_custom([200, 131], [max(W, 40), max(W, 70)], [fo.METHOD_SNAPKV] * 2, W=W, d=128), score_mode)
 
 
 @pytest.mark.parametrize("pool_kernel", [1, 3, 15])
-def test_pool_kernels(pool_kernel):
-    _run(_custom([150], [60], [fo.METHOD_SNAPKV]), pool_kernel=pool_kernel)
+def test_pool_kernels(pool_kernel, score_mode):
+    _run(_custom([150], [60], [fo.METHOD_SNAPKV]), score_mode, pool_kernel=pool_kernel)
 
 
-def test_degenerate_budgets():
+def test_degenerate_budgets(score_mode):
     # B == L (identity), B == W (window only), L == W == B, single token
     wl = _custom([97, 80, 16, 1, 33], [97, 16, 16, 1, 33],
                  [fo.METHOD_KNORM, fo.METHOD_SNAPKV, fo.METHOD_SNAPKV, fo.METHOD_KNORM,
                   fo.METHOD_SNAPKV])
-    _run(wl)
+    _run(wl, score_mode)
 
 
-def test_none_requests_pass_through():
+def test_none_requests_pass_through(score_mode):
     wl = _custom([100, 64, 50], [30, 1, 20], [fo.METHOD_SNAPKV, fo.METHOD_NONE, fo.METHOD_KNORM])
-    _run(wl)
+    _run(wl, score_mode)
 
 
-def test_custom_scale():
-    _run(_custom([300], [100], [fo.METHOD_SNAPKV], d=128), scale=0.05)
+def test_custom_scale(score_mode):
+    _run(_custom([300], [100], [fo.METHOD_SNAPKV], d=128), score_mode, scale=0.05)
 
 
-def test_all_ties_go_to_lower_index():
+def test_all_ties_go_to_lower_index(score_mode):
     """All-zero queries: every prefix token has the same score, so the kept
     prefix must be the lowest indices (no tolerance band can hide this: the
     self-consistency check compares against the GPU's own scores)."""
@@ -119,7 +126,7 @@ def test_all_ties_go_to_lower_index():
     from parity_util import SideBySide
     wl = _custom([256, 77], [64, 40], [fo.METHOD_SNAPKV] * 2, W=16)
     q = np.zeros((2, 1, 2, 16, 64), dtype=np.float16)
-    s = SideBySide(wl, q_host=q)
+    s = SideBySide(wl, q_host=q, score_mode=score_mode)
     try:
         s.compress_and_compare()
         kept_prefix0 = 64 - 16
@@ -218,15 +225,27 @@ def test_alloc_free_are_lifo_and_match_the_oracle():
         fc.fc_pool_destroy(pool)
 
 
-def test_repeated_compression_of_the_same_requests():
+def test_repeated_compression_of_the_same_requests(score_mode):
     """Compress, then compress the compressed caches again (lengths shrink,
     tables are the library's own output)."""
     from parity_util import SideBySide
     wl = _custom([500, 333], [200, 150], [fo.METHOD_SNAPKV, fo.METHOD_KNORM], d=128)
-    s = SideBySide(wl)
+    s = SideBySide(wl, score_mode=score_mode)
     try:
         s.compress_and_compare()
         s.compress_and_compare(budgets=np.array([64, 20], np.int32))
         s.compress_and_compare(budgets=np.array([16, 20], np.int32))
     finally:
         s.close()
+
+
+@pytest.mark.parametrize("L,W", [(513, 64), (2049, 64), (1500, 33), (3000, 16), (5000, 48)])
+def test_one_pass_teams_of_several_workgroups(L, W):
+    """Heads longer than one workgroup's register capacity are shared by a team
+    (here 2..10 workgroups, ragged block split, members with few or no blocks)."""
+    _run(_custom([L, L // 2 + 7], [max(W, L // 5), max(W, L // 4)], [fo.METHOD_SNAPKV] * 2,
+                 W=W, d=128, n_heads=3), 2)
+
+
+def test_auto_mode_is_default_and_green():
+    _run(synth.make_workload(4, n_layers=1, n_heads=4, n_req=2))
