@@ -146,13 +146,16 @@ int fc_compress_batch(fc_pool* pool, int32_t* dev_block_tables, int max_blocks_p
                       int32_t* dev_kept_out, void* stream);
 
 /*
- * Which SnapKV score kernel fc_compress_batch uses.  FC_SCORE_AUTO (default):
- * the one-pass kernel (K read once, logits kept in registers, workgroups of a
- * long head cooperate) whenever the device can hold its grid and every head
- * of the batch fits, else the two-pass kernel (K read twice, no cooperation
- * between workgroups, any length).  The other two values force one of them;
- * forcing one-pass makes fc_compress_batch return FC_EINVAL when it cannot
- * be used.  Both produce the same scores up to fp32 rounding.
+ * Which SnapKV score kernel fc_compress_batch uses.
+ *   FC_SCORE_TWO_PASS: K is streamed twice (row statistics, then column sums);
+ *     workgroups never wait for each other; any length up to FC_MAX_SEQ_LEN.
+ *   FC_SCORE_ONE_PASS: K is streamed once; the logits stay in registers and
+ *     the workgroups that share a long head exchange row statistics.  Needs a
+ *     device that can hold the kernel's grid co-resident; fc_compress_batch
+ *     returns FC_EINVAL if that is not possible for the batch.
+ *   FC_SCORE_AUTO (default): the faster of the two as measured on MI355X
+ *     (at present the two-pass kernel).
+ * Both produce the same scores up to fp32 rounding.
  */
 enum { FC_SCORE_AUTO = 0, FC_SCORE_TWO_PASS = 1, FC_SCORE_ONE_PASS = 2 };
 int fc_set_score_mode(fc_pool* pool, int mode);

@@ -321,7 +321,8 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
   size_t n_team_counters = 0, n_team_stats = 0;
   bool any_snap = false;
   for (const ReqDesc& d : descs) any_snap |= d.method == FC_METHOD_SNAPKV;
-  if (any_snap && p->score_mode != FC_SCORE_TWO_PASS) {
+  // AUTO currently means two-pass: measured faster on MI355X for every benchmark shape
+  if (any_snap && p->score_mode == FC_SCORE_ONE_PASS) {
     const int nt = (window + 15) / 16;
     if (p->team_grid[nt] == 0) {
       const int gsz = team_grid_size(p->head_dim, window);
