@@ -186,3 +186,37 @@ class SideBySide:
             live += bt_g[r, :fo.blocks_for(int(self.lens_g[r]), bs)].tolist()
         stack_g, top_g = self.fc.fc_pool_export_state(self.pool)
         assert sorted(stack_g[:top_g].tolist() + live) == list(range(wl.n_blocks))
+
+
+def check_unit_on_device(kv_dev, q_unit, old_ids, new_ids, layer, head, L, B, method, window,
+                         pool_kernel, scores_g, kept_g, where=""):
+    """Full-size workloads: checks ONE (request, layer, head) unit of a finished
+    fc_compress_batch against the oracle.  The unit's old blocks are downloaded
+    (they are intact after the call: compaction writes only into blocks that
+    were free), the oracle scores / selects / copies on a private mini pool,
+    and the new blocks are downloaded for the byte comparison.
+
+    kv_dev: device pool tensor; q_unit: [window][d] fp16 numpy (or None);
+    old_ids / new_ids: int numpy arrays; scores_g fp32 [L], kept_g int32 [B].
+    Returns (max relative score error, kept lists identical?)."""
+    import torch
+    bs, d = kv_dev.shape[4], kv_dev.shape[5]
+    n_old, n_new = len(old_ids), len(new_ids)
+    dev = kv_dev.device
+    mini = np.zeros((1, n_old + n_new, 2, 1, bs, d), dtype=np.float16)
+    oi = torch.from_numpy(np.asarray(old_ids, dtype=np.int64)).to(dev)
+    ni = torch.from_numpy(np.asarray(new_ids, dtype=np.int64)).to(dev)
+    mini[0, :n_old, :, 0] = kv_dev[layer, oi, :, head].cpu().numpy()
+    table = np.arange(n_old)
+    s_o = fo.unit_scores(mini, 0, table, 0, L, method, q_unit, None, pool_kernel)
+    k_o = fo.select_topk(s_o, B)
+    err = check_scores(scores_g, s_o, where)
+    same = check_kept(kept_g, scores_g, k_o, s_o, B, where)
+    fo.copy_rows(mini, 0, 0, table, n_old + np.arange(n_new), kept_g)
+    got = kv_dev[layer, ni, :, head].cpu().numpy()            # [n_new][2][bs][d]
+    for i in range(n_new):
+        valid = min(bs, B - i * bs)
+        a = got[i, :, :valid].view(np.uint16)
+        e = mini[0, n_old + i, :, 0, :valid].view(np.uint16)
+        assert (a == e).all(), "gathered K/V bytes differ %s new block %d" % (where, i)
+    return err, same

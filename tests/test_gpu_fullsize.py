@@ -1,0 +1,109 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py
+times: the whole batch goes through one fc_compress_batch; pool state is
+compared bit-exactly with the oracle (it depends on counts only), structural
+properties are checked on every unit, and sampled units are checked element by
+element against the oracle."""
+
+import numpy as np
+import pytest
+
+from oracle import fastcache_oracle as fo
+from paper_2503_08461_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _oracle_pool_replay(wl):
+    """The oracle's pool bookkeeping for the whole workload.  A pool array with
+    zero layers makes compress_batch skip all scoring and copying and run
+    only its allocation / reclaim steps, which depend on counts alone."""
+    st = fo.FreeStack(wl.n_blocks)
+    rows = synth.build_block_tables(wl, st.alloc, st.free, lambda ids, ix: ids[ix])
+    bt = np.full((wl.n_req, wl.max_blocks), -1, dtype=np.int32)
+    for r in range(wl.n_req):
+        bt[r, :rows[r].shape[0]] = rows[r]
+    bt0 = bt.copy()
+    lens = wl.seq_lens.copy()
+    skeleton = np.zeros((0, wl.n_blocks, 2, wl.n_heads, wl.block_size, wl.head_dim), np.float16)
+    status, _, _ = fo.compress_batch(skeleton, st, bt, lens, None, wl.window, wl.methods,
+                                     wl.budgets, wl.pool_kernel)
+    assert status is None
+    return st, bt0, bt, lens
+
+
+@pytest.mark.parametrize("config,n_samples", [(2, 48), (3, 40), (4, 24)])
+def test_fullsize_batch(config, n_samples):
+    import torch
+    from paper_2503_08461_amd import fastcache as fc
+    from paper_2503_08461_amd.device_setup import DeviceWorkload
+    from parity_util import check_unit_on_device
+    wl = synth.make_workload(config)
+    total = torch.cuda.get_device_properties(0).total_memory
+    if wl.pool_bytes() + (10 << 30) > total:
+        pytest.skip("pool does not fit this device")
+    print("full-size", wl.name, "pool GiB %.1f" % (wl.pool_bytes() / 2**30), flush=True)
+    dw = DeviceWorkload(wl)
+    try:
+        n_lh = wl.n_layers * wl.n_heads
+        n_scores = int(wl.seq_lens.astype(np.int64).sum()) * n_lh
+        n_kept = int(wl.budgets.astype(np.int64).sum()) * n_lh
+        scores = torch.empty(n_scores, dtype=torch.float32, device=dw.dev)
+        kept = torch.empty(n_kept, dtype=torch.int32, device=dw.dev)
+        dw.compress(scores, kept)
+        torch.cuda.synchronize()
+        print("compressed", flush=True)
+
+        # pool state: bit-exact with the oracle's bookkeeping
+        st, bt0_o, bt_o, lens_o = _oracle_pool_replay(wl)
+        assert (dw.bt0.cpu().numpy() == bt0_o).all()
+        stack_g, top_g = fc.fc_pool_export_state(dw.pool)
+        assert top_g == st.top and (stack_g[:top_g] == st.stack[:top_g]).all()
+        assert (dw.lens == lens_o).all()
+        bt_g = dw.bt.cpu().numpy()
+        for r in range(wl.n_req):
+            n = fo.blocks_for(int(lens_o[r]), wl.block_size)
+            assert (bt_g[r, :n] == bt_o[r, :n]).all()
+
+        # structure of every unit's kept list, checked on the device
+        so = ko = 0
+        offs = []
+        for r in range(wl.n_req):
+            L, B = int(wl.seq_lens[r]), int(wl.budgets[r])
+            k = kept[ko:ko + n_lh * B].view(n_lh, B)
+            assert bool((k[:, 1:] > k[:, :-1]).all()), "kept not ascending (request %d)" % r
+            assert int(k.min()) >= 0 and int(k.max()) < L
+            if wl.methods[r] == fo.METHOD_SNAPKV:
+                W = wl.window
+                want = torch.arange(L - W, L, device=dw.dev, dtype=torch.int32)
+                assert bool((k[:, B - W:] == want).all()), "window not kept (request %d)" % r
+                s = scores[so:so + n_lh * L].view(n_lh, L)
+                assert bool(torch.isposinf(s[:, L - W:]).all())
+                assert bool(torch.isfinite(s[:, :L - W]).all())
+            offs.append((so, ko))
+            so += n_lh * L
+            ko += n_lh * B
+
+        # sampled units against the oracle, longest and shortest requests included
+        rng = np.random.Generator(np.random.PCG64(100 + config))
+        reqs = [int(np.argmax(wl.seq_lens)), int(np.argmin(wl.seq_lens))]
+        worst, same_cnt = 0.0, 0
+        for i in range(n_samples):
+            r = reqs[i] if i < len(reqs) else int(rng.integers(wl.n_req))
+            l, h = int(rng.integers(wl.n_layers)), int(rng.integers(wl.n_heads))
+            L, B = int(wl.seq_lens[r]), int(wl.budgets[r])
+            lh = l * wl.n_heads + h
+            so, ko = offs[r]
+            sg = scores[so + lh * L: so + (lh + 1) * L].cpu().numpy()
+            kg = kept[ko + lh * B: ko + (lh + 1) * B].cpu().numpy()
+            q = dw.q[r, l, h].cpu().numpy() if wl.methods[r] == fo.METHOD_SNAPKV else None
+            n_old, n_new = fo.blocks_for(L, 16), fo.blocks_for(B, 16)
+            err, same = check_unit_on_device(
+                dw.kv, q, bt0_o[r, :n_old], bt_o[r, :n_new], l, h, L, B, int(wl.methods[r]),
+                wl.window, wl.pool_kernel, sg, kg, "(%s req %d layer %d head %d)" % (wl.name, r, l, h))
+            worst = max(worst, err)
+            same_cnt += int(same)
+        print("sampled units: %d, kept identical: %d, max rel score err %.2e" % (
+            n_samples, same_cnt, worst), flush=True)
+        assert worst < 2e-3
+    finally:
+        dw.close()
