@@ -98,6 +98,10 @@ int fc_pool_export_state(fc_pool* pool, int32_t* host_stack, int* top);
  * between benchmark repetitions).  0 <= top <= n_blocks.  Synchronous. */
 int fc_pool_import_state(fc_pool* pool, const int32_t* host_stack, int top);
 
+/* Same from a device copy of the stack (dev, int32[n_blocks]), asynchronously
+ * on `stream`, so that a benchmark can rewind without idling the GPU. */
+int fc_pool_import_state_dev(fc_pool* pool, const int32_t* dev_stack, int top, void* stream);
+
 /*
  * kv_c <- C(kv, lambda) for a whole batch (Algorithm 1, "Batch compression";
  * Pipeline Optimization section: compression of many requests is issued as
@@ -163,9 +167,12 @@ int fc_set_score_mode(fc_pool* pool, int mode);
 /*
  * Per-kernel timing for benchmarks.  With profiling enabled every kernel
  * launched by fc_compress_batch is bracketed by HIP events on the call's
- * stream.  fc_get_kernel_times waits for the last call and writes the elapsed
- * milliseconds of each kernel of that call (0 if it was not launched) to
- * host_ms[0..FC_N_KERNELS).  fc_kernel_name(i) names slot i.
+ * stream; the events of the last 32 calls are kept.  fc_get_kernel_times
+ * waits for those calls and writes, for each kernel, its elapsed milliseconds
+ * averaged over the calls made since profiling was switched on (at most the
+ * last 32; 0 if it was never launched) to host_ms[0..FC_N_KERNELS).
+ * fc_kernel_name(i) names slot i.  fc_set_profiling(pool, 1) restarts the
+ * average.
  */
 #define FC_N_KERNELS 6
 int fc_set_profiling(fc_pool* pool, int enable);

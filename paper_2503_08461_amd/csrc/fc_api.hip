@@ -42,6 +42,8 @@ const char* const kKernelNames[K_COUNT] = {"plan_alloc",   "snapkv_score", "knor
 
 size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+constexpr int kProfRing = 32;
+
 }  // namespace
 
 struct fc_pool {
@@ -74,8 +76,10 @@ struct fc_pool {
   int team_grid[FC_MAX_WINDOW / 16 + 1] = {};  // co-resident grid per query-tile count, -1 = none
 
   bool profiling = false;
-  hipEvent_t ev[K_COUNT][2] = {};
-  bool timed[K_COUNT] = {};
+  // event ring: the last kProfRing profiled calls, [call][kernel][start, stop]
+  hipEvent_t ev[kProfRing][K_COUNT][2] = {};
+  bool timed[kProfRing][K_COUNT] = {};
+  int prof_calls = 0;  // profiled calls since profiling was last switched on
 };
 
 namespace {
@@ -146,8 +150,9 @@ int fc_pool_create(fc_pool** out, void* kv_base, size_t kv_bytes, int n_blocks, 
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->error_flag), sizeof(int32_t));
   if (e == hipSuccess) e = launch_zero_ints(p->error_flag, 1, nullptr);
   if (e == hipSuccess) e = hipEventCreateWithFlags(&p->meta_event, hipEventDisableTiming);
-  for (int k = 0; k < K_COUNT && e == hipSuccess; ++k)
-    for (int j = 0; j < 2 && e == hipSuccess; ++j) e = hipEventCreate(&p->ev[k][j]);
+  for (int c = 0; c < kProfRing && e == hipSuccess; ++c)
+    for (int k = 0; k < K_COUNT && e == hipSuccess; ++k)
+      for (int j = 0; j < 2 && e == hipSuccess; ++j) e = hipEventCreate(&p->ev[c][k][j]);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
     fc_pool_destroy(p);
@@ -170,9 +175,10 @@ int fc_pool_destroy(fc_pool* p) {
   if (p->dev_meta) (void)hipFree(p->dev_meta);
   if (p->host_meta) (void)hipHostFree(p->host_meta);
   if (p->meta_event) (void)hipEventDestroy(p->meta_event);
-  for (int k = 0; k < K_COUNT; ++k)
-    for (int j = 0; j < 2; ++j)
-      if (p->ev[k][j]) (void)hipEventDestroy(p->ev[k][j]);
+  for (int c = 0; c < kProfRing; ++c)
+    for (int k = 0; k < K_COUNT; ++k)
+      for (int j = 0; j < 2; ++j)
+        if (p->ev[c][k][j]) (void)hipEventDestroy(p->ev[c][k][j]);
   delete p;
   return FC_OK;
 }
@@ -236,17 +242,34 @@ int fc_set_score_mode(fc_pool* p, int mode) {
 int fc_set_profiling(fc_pool* p, int enable) {
   if (!p) return fail(FC_EINVAL, "pool is NULL");
   p->profiling = enable != 0;
+  p->prof_calls = 0;
   return FC_OK;
 }
 
 int fc_get_kernel_times(fc_pool* p, float* host_ms) {
   if (!p || !host_ms) return fail(FC_EINVAL, "NULL argument");
+  const int n = std::min(p->prof_calls, kProfRing);
   for (int k = 0; k < K_COUNT; ++k) {
-    host_ms[k] = 0.f;
-    if (!p->timed[k]) continue;
-    FC_HIP(hipEventSynchronize(p->ev[k][1]));
-    FC_HIP(hipEventElapsedTime(&host_ms[k], p->ev[k][0], p->ev[k][1]));
+    double sum = 0.0;
+    int cnt = 0;
+    for (int c = 0; c < n; ++c) {
+      if (!p->timed[c][k]) continue;
+      float ms = 0.f;
+      FC_HIP(hipEventSynchronize(p->ev[c][k][1]));
+      FC_HIP(hipEventElapsedTime(&ms, p->ev[c][k][0], p->ev[c][k][1]));
+      sum += ms;
+      ++cnt;
+    }
+    host_ms[k] = cnt ? (float)(sum / cnt) : 0.f;
   }
+  return FC_OK;
+}
+
+int fc_pool_import_state_dev(fc_pool* p, const int32_t* dev_stack, int top, void* stream) {
+  if (!p || !dev_stack) return fail(FC_EINVAL, "NULL argument");
+  if (top < 0 || top > p->n_blocks) return fail(FC_EINVAL, "top out of range");
+  FC_HIP(launch_pool_push(p->stack, 0, p->n_blocks, dev_stack, static_cast<hipStream_t>(stream)));
+  p->top = top;
   return FC_OK;
 }
 
@@ -421,15 +444,19 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
   bp.error_flag = p->error_flag;
 
   // ---- the stage ------------------------------------------------------------
-  for (int k = 0; k < K_COUNT; ++k) p->timed[k] = false;
+  const int ring = p->prof_calls % kProfRing;
+  if (p->profiling) {
+    for (int k = 0; k < K_COUNT; ++k) p->timed[ring][k] = false;
+    ++p->prof_calls;
+  }
   auto run = [&](int slot, bool active, auto&& launch) -> hipError_t {
     if (!active) return hipSuccess;
     hipError_t e = hipSuccess;
-    if (p->profiling) e = hipEventRecord(p->ev[slot][0], stream);
+    if (p->profiling) e = hipEventRecord(p->ev[ring][slot][0], stream);
     if (e == hipSuccess) e = launch();
     if (e == hipSuccess && p->profiling) {
-      e = hipEventRecord(p->ev[slot][1], stream);
-      p->timed[slot] = true;
+      e = hipEventRecord(p->ev[ring][slot][1], stream);
+      p->timed[ring][slot] = true;
     }
     return e;
   };

@@ -33,11 +33,18 @@ class DeviceWorkload:
         # (data blocks need no rewind: compaction writes only into free blocks)
         self.bt0 = self.bt.clone()
         self.stack0, self.top0 = fc.fc_pool_export_state(self.pool)
+        self.stack0_dev = torch.from_numpy(self.stack0).to(self.dev)
         if verbose:
             print("[setup] done", flush=True)
 
     def rewind(self):
         fc.fc_pool_import_state(self.pool, self.stack0, self.top0)
+        self.bt.copy_(self.bt0)
+        self.lens[:] = self.wl.seq_lens
+
+    def rewind_async(self):
+        """Rewind without a host wait (device-to-device copies on the stream)."""
+        fc.fc_pool_import_state_dev(self.pool, self.stack0_dev, self.top0)
         self.bt.copy_(self.bt0)
         self.lens[:] = self.wl.seq_lens
 

@@ -23,6 +23,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libfastcach
 EXPORTS = [
     "fc_pool_create", "fc_pool_destroy", "fc_pool_alloc", "fc_pool_free",
     "fc_pool_num_free", "fc_pool_export_state", "fc_pool_import_state",
+    "fc_pool_import_state_dev",
     "fc_compress_batch", "fc_set_score_mode", "fc_set_profiling", "fc_get_kernel_times",
     "fc_kernel_name", "fc_last_error",
 ]
@@ -68,6 +69,7 @@ def load_library():
     lib.fc_pool_num_free.argtypes = [vp]
     lib.fc_pool_export_state.argtypes = [vp, i32p, ctypes.POINTER(i)]
     lib.fc_pool_import_state.argtypes = [vp, i32p, i]
+    lib.fc_pool_import_state_dev.argtypes = [vp, vp, i, vp]
     lib.fc_compress_batch.argtypes = [vp, vp, i, i32p, vp, i, i32p, i32p, i, i,
                                       ctypes.c_float, vp, vp, vp]
     lib.fc_set_score_mode.argtypes = [vp, i]
@@ -180,6 +182,16 @@ def fc_pool_import_state(pool, stack, top):
     _check(lib.fc_pool_import_state(pool.ptr, _host_i32(stack), int(top)))
 
 
+def fc_pool_import_state_dev(pool, dev_stack, top, stream=None):
+    """dev_stack: int32 device tensor [n_blocks]; asynchronous on the stream."""
+    import torch
+    lib = load_library()
+    if dev_stack.numel() != pool.n_blocks:
+        raise ValueError("stack must have n_blocks entries")
+    _check(lib.fc_pool_import_state_dev(pool.ptr, _dev_ptr(dev_stack, torch.int32), int(top),
+                                        _stream_ptr(stream)))
+
+
 def fc_compress_batch(pool, block_tables, seq_lens, q_window, window, method, budget,
                       pool_kernel=7, scale=0.0, scores_out=None, kept_out=None, stream=None):
     """block_tables: int32 device tensor [n_req][max_blocks] (in/out);
@@ -223,7 +235,8 @@ def fc_set_profiling(pool, enable):
 
 
 def fc_get_kernel_times(pool):
-    """{kernel name: milliseconds} of the last fc_compress_batch (profiling on)."""
+    """{kernel name: mean milliseconds} over the profiled fc_compress_batch calls
+    since profiling was switched on (at most the last 32)."""
     lib = load_library()
     ms = (ctypes.c_float * FC_N_KERNELS)()
     _check(lib.fc_get_kernel_times(pool.ptr, ms))
