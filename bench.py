@@ -78,6 +78,8 @@ def main():
     ap.add_argument("--workload", default="config4", choices=["config2", "config3", "config4"])
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="CPU time budget of the oracle baseline (0 = skip)")
+    ap.add_argument("--score-mode", default="auto", choices=["auto", "two_pass", "one_pass"],
+                    help="which SnapKV score kernel the library uses")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of known size (reference for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -115,6 +117,7 @@ def main():
         sys.exit(2)
 
     dw = DeviceWorkload(wl, verbose=True)
+    fc.fc_set_score_mode(dw.pool, {"auto": 0, "two_pass": 1, "one_pass": 2}[args.score_mode])
     fc.fc_set_profiling(dw.pool, True)
     for _ in range(args.warmup):
         dw.rewind()
@@ -162,6 +165,7 @@ def main():
             "n_heads": wl.n_heads, "head_dim": wl.head_dim, "window": wl.window,
             "pool_blocks": wl.n_blocks, "pool_GiB": round(wl.pool_bytes() / 2**30, 1),
             "kept_fraction": round(float(wl.budgets[comp].sum()) / tokens, 4),
+            "score_mode": args.score_mode,
         },
         "path": {
             "algorithmic_bytes": path_bytes,

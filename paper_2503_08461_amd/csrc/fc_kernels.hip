@@ -283,12 +283,22 @@ __global__ __launch_bounds__(kThreads) void knorm_score_kernel(BatchParams p) {
 // per-head top-budget selection
 // ---------------------------------------------------------------------------
 //
-// One workgroup per (request, layer, head).  Scores become order-preserving
-// 32-bit keys held in LDS; the budget-th largest key is found by a 4 x 8-bit
-// most-significant-digit radix select (LDS histogram + suffix scan); the
-// kept indices are then emitted in ascending token order by a ballot /
-// popcount compaction in which keys equal to the threshold are admitted in
-// index order until the budget is met (ties go to the lower index).
+// One workgroup per (request, layer, head).  Only the tokens before the
+// observation window compete (window tokens are always kept), so the kernel
+// selects the budget-minus-window best of the prefix and appends the window.
+//
+//   1. the un-pooled scores are staged in LDS, max-pooled from LDS and turned
+//      in place into order-preserving 32-bit keys; min and max key are reduced
+//      on the way;
+//   2. the threshold (the k-th largest key) is found by a bucket select: 2048
+//      linear buckets over [min, max] (so the histogram is spread even when
+//      every score shares its exponent), then the keys of the one bucket that
+//      holds the threshold are compacted to a short candidate list, which is
+//      refined with 2048 buckets per pass until a bucket is a single key
+//      (at most 3 passes for 32 bits);
+//   3. the kept indices are emitted in ascending token order by a ballot /
+//      popcount compaction in which keys equal to the threshold are admitted
+//      in index order until the budget is met (ties go to the lower index).
 
 __device__ __forceinline__ uint32_t score_key(float s) {
   s += 0.0f;  // -0 and +0 compare equal, give them one key
@@ -296,11 +306,71 @@ __device__ __forceinline__ uint32_t score_key(float s) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+static constexpr int kBuckets = 2048;
+static constexpr int kBucketBits = 11;
+static constexpr int kMaxCand = 2048;
+static constexpr int kStagePerThread = 32;  // staging path handles up to 32*256 tokens
+
+// Finds, among the `n` keys produced by get(j) that lie in [lo, lo + width)
+// (width == 0: all of them do, no check), the bucket (key - lo) >> shift that
+// holds the `remaining`-th largest.  Returns the bucket in sel[0] and the rank
+// inside it in sel[1].  All threads must call.
+template <typename Get>
+__device__ __forceinline__ void bucket_pass(int n, uint32_t lo, int shift, uint32_t width,
+                                            int remaining, int* hist, int* wsum, int* sel,
+                                            Get get) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+  for (int i = 0; i < kBuckets / kThreads; ++i) hist[tid + i * kThreads] = 0;
+  __syncthreads();
+  for (int j = tid; j < n; j += kThreads) {
+    const uint32_t k = get(j);
+    const uint32_t d = k - lo;
+    if (width == 0u || (k >= lo && d < width)) atomicAdd(&hist[d >> shift], 1);
+  }
+  __syncthreads();
+  // thread t owns buckets [8t, 8t+8)
+  int own[kBuckets / kThreads];
+  int s = 0;
+#pragma unroll
+  for (int i = 0; i < kBuckets / kThreads; ++i) {
+    own[i] = hist[tid * (kBuckets / kThreads) + i];
+    s += own[i];
+  }
+  int v = s;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int t = __shfl_up(v, o);
+    if (lane >= o) v += t;
+  }
+  if (lane == 63) wsum[wave] = v;
+  __syncthreads();
+  int base = 0, total = 0;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) {
+    if (w < wave) base += wsum[w];
+    total += wsum[w];
+  }
+  int above = total - (v + base);  // keys in buckets above this thread's
+#pragma unroll
+  for (int i = kBuckets / kThreads - 1; i >= 0; --i) {
+    if (above < remaining && above + own[i] >= remaining) {
+      sel[0] = tid * (kBuckets / kThreads) + i;
+      sel[1] = remaining - above;
+    }
+    above += own[i];
+  }
+  __syncthreads();
+}
+
 __global__ __launch_bounds__(kThreads) void select_kernel(BatchParams p) {
   extern __shared__ uint32_t keys[];
-  __shared__ int hist[256];
+  __shared__ int hist[kBuckets];
+  __shared__ uint32_t cand[kMaxCand];
   __shared__ int wsum[kWaves];
+  __shared__ uint32_t wmin[kWaves], wmax[kWaves];
   __shared__ int sel[2];
+  __shared__ int n_cand;
   __shared__ int cnt[kWaves][2];
 
   const int n_lh = p.n_layers * p.n_heads;
@@ -312,76 +382,136 @@ __global__ __launch_bounds__(kThreads) void select_kernel(BatchParams p) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
+  const bool snap = rd.method == 1 /* FC_METHOD_SNAPKV */;
+  const int n_sel = snap ? L - p.window : L;  // tokens that compete
+  const int k_sel = snap ? B - p.window : B;  // how many of them are kept
   const float* raw = p.raw_scores + rd.score_off + (size_t)lh * L;
   float* out = p.scores_out ? p.scores_out + rd.score_off + (size_t)lh * L : nullptr;
+  int32_t* kept = p.kept + rd.kept_off + (size_t)lh * B;
 
-  // 1. final scores -> keys
-  if (rd.method == 1 /* FC_METHOD_SNAPKV */) {
-    const int n_prefix = L - p.window;
+  // ---- 1. final scores -> keys, min / max -------------------------------------
+  uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
+  if (snap && n_sel <= kStagePerThread * kThreads) {
+    float* stage = reinterpret_cast<float*>(keys);
+    for (int j = tid; j < n_sel; j += kThreads) stage[j] = raw[j];
+    __syncthreads();
     const int h = p.pool_kernel >> 1;
-    for (int j = tid; j < L; j += kThreads) {
-      float s = INFINITY;  // window tokens are always kept
-      if (j < n_prefix) {
-        const int lo = max(0, j - h), hi = min(n_prefix - 1, j + h);
-        s = raw[lo];
-        for (int t = lo + 1; t <= hi; ++t) s = fmaxf(s, raw[t]);
+    float pv[kStagePerThread];
+#pragma unroll
+    for (int i = 0; i < kStagePerThread; ++i) {
+      const int j = tid + i * kThreads;
+      float s = 0.f;
+      if (j < n_sel) {
+        const int lo = max(0, j - h), hi = min(n_sel - 1, j + h);
+        s = stage[lo];
+        for (int t = lo + 1; t <= hi; ++t) s = fmaxf(s, stage[t]);
       }
+      pv[i] = s;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kStagePerThread; ++i) {
+      const int j = tid + i * kThreads;
+      if (j < n_sel) {
+        const uint32_t k = score_key(pv[i]);
+        keys[j] = k;
+        kmin = min(kmin, k);
+        kmax = max(kmax, k);
+        if (out) out[j] = pv[i];
+      }
+    }
+  } else if (snap) {
+    const int h = p.pool_kernel >> 1;
+    for (int j = tid; j < n_sel; j += kThreads) {
+      const int lo = max(0, j - h), hi = min(n_sel - 1, j + h);
+      float s = raw[lo];
+      for (int t = lo + 1; t <= hi; ++t) s = fmaxf(s, raw[t]);
+      const uint32_t k = score_key(s);
+      keys[j] = k;
+      kmin = min(kmin, k);
+      kmax = max(kmax, k);
       if (out) out[j] = s;
-      keys[j] = score_key(s);
     }
   } else {
-    for (int j = tid; j < L; j += kThreads) {
+    for (int j = tid; j < n_sel; j += kThreads) {
       const float s = raw[j];
+      const uint32_t k = score_key(s);
+      keys[j] = k;
+      kmin = min(kmin, k);
+      kmax = max(kmax, k);
       if (out) out[j] = s;
-      keys[j] = score_key(s);
     }
   }
+  if (snap) {
+    if (out)
+      for (int j = n_sel + tid; j < L; j += kThreads) out[j] = INFINITY;
+    for (int j = tid; j < p.window; j += kThreads) kept[k_sel + j] = n_sel + j;  // forced window
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o));
+    kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o));
+  }
+  if (lane == 0) {
+    wmin[wave] = kmin;
+    wmax[wave] = kmax;
+  }
+  if (tid == 0) n_cand = 0;
   __syncthreads();
-
-  // 2. radix select of the B-th largest key
-  uint32_t prefix = 0, mask = 0;
-  int remaining = B;
-  for (int shift = 24; shift >= 0; shift -= 8) {
-    hist[tid] = 0;
-    __syncthreads();
-    for (int j = tid; j < L; j += kThreads) {
-      const uint32_t k = keys[j];
-      if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1);
-    }
-    __syncthreads();
-    const int cdig = hist[tid];
-    int v = cdig;  // inclusive scan over digits 0..tid
+  if (k_sel == 0) return;  // only the window is kept (uniform across the workgroup)
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const int n = __shfl_up(v, o);
-      if (lane >= o) v += n;
-    }
-    if (lane == 63) wsum[wave] = v;
-    __syncthreads();
-    int base = 0, total = 0;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-      if (w < wave) base += wsum[w];
-      total += wsum[w];
-    }
-    const int above = total - (v + base);  // candidates with a larger digit
-    if (above < remaining && above + cdig >= remaining) {
-      sel[0] = tid;
-      sel[1] = remaining - above;
-    }
-    __syncthreads();
-    prefix |= (uint32_t)sel[0] << shift;
-    mask |= 0xFFu << shift;
-    remaining = sel[1];
-    __syncthreads();
+  for (int w = 0; w < kWaves; ++w) {
+    kmin = min(kmin, wmin[w]);
+    kmax = max(kmax, wmax[w]);
   }
-  const uint32_t thr = prefix;  // B-th largest key
-  const int need_eq = remaining;  // how many keys equal to it are kept
 
-  // 3. ordered compaction; each wavefront owns a contiguous token segment
-  const int seg = (((L + kWaves - 1) / kWaves) + 63) & ~63;
+  // ---- 2. threshold = k_sel-th largest key ---------------------------------------
+  uint32_t thr;
+  int need_eq;
+  if (kmin == kmax) {
+    thr = kmin;
+    need_eq = k_sel;
+  } else {
+    uint32_t lo = kmin;
+    const uint32_t range = kmax - kmin;
+    int shift = max(0, 32 - __clz(range) - kBucketBits);
+    bucket_pass(n_sel, lo, shift, 0u, k_sel, hist, wsum, sel, [&](int j) { return keys[j]; });
+    int remaining = sel[1];
+    uint32_t bkt = (uint32_t)sel[0];
+    if (shift > 0) {
+      // candidates: the keys of that one bucket
+      for (int j = tid; j < n_sel; j += kThreads) {
+        const uint32_t k = keys[j];
+        if (((k - lo) >> shift) == bkt) {
+          const int pos = atomicAdd(&n_cand, 1);
+          if (pos < kMaxCand) cand[pos] = k;
+        }
+      }
+      __syncthreads();
+      const int nc = n_cand;
+      const bool listed = nc <= kMaxCand;  // else refine over all keys with a range check
+      while (shift > 0) {
+        lo += bkt << shift;
+        const uint32_t width = 1u << shift;  // the chosen bucket spans [lo, lo + width)
+        shift = max(0, shift - kBucketBits);
+        if (listed)
+          bucket_pass(nc, lo, shift, width, remaining, hist, wsum, sel,
+                      [&](int j) { return cand[j]; });
+        else
+          bucket_pass(n_sel, lo, shift, width, remaining, hist, wsum, sel,
+                      [&](int j) { return keys[j]; });
+        remaining = sel[1];
+        bkt = (uint32_t)sel[0];
+      }
+    }
+    thr = lo + bkt;
+    need_eq = remaining;
+  }
+
+  // ---- 3. ordered compaction; each wavefront owns a contiguous token segment ----
+  const int seg = (((n_sel + kWaves - 1) / kWaves) + 63) & ~63;
   const int j0 = wave * seg;
-  const int j1 = min(L, j0 + seg);
+  const int j1 = min(n_sel, j0 + seg);
   int n_gt = 0, n_eq = 0;
   for (int jb = j0; jb < j1; jb += 64) {
     const int j = jb + lane;
@@ -402,7 +532,6 @@ __global__ __launch_bounds__(kThreads) void select_kernel(BatchParams p) {
   }
   int eq_run = eq_before;
   int kept_run = gt_before + min(eq_before, need_eq);
-  int32_t* kept = p.kept + rd.kept_off + (size_t)lh * B;
   const uint64_t lt_mask = (1ull << lane) - 1ull;
   for (int jb = j0; jb < j1; jb += 64) {
     const int j = jb + lane;

@@ -249,3 +249,33 @@ def test_one_pass_teams_of_several_workgroups(L, W):
 
 def test_auto_mode_is_default_and_green():
     _run(synth.make_workload(4, n_layers=1, n_heads=4, n_req=2))
+
+
+def test_select_with_massive_ties_and_clustered_scores():
+    """Many identical keys (more than the candidate list holds) and scores that
+    differ only in their lowest mantissa bits: the threshold search must fall
+    back to refining over all keys and still break ties by index."""
+    from parity_util import SideBySide
+    wl = _custom([6000, 4097], [2500, 1], [fo.METHOD_KNORM] * 2, d=64, n_heads=2)
+    kv = synth.fill_pool_host(wl)
+    rng = np.random.default_rng(5)
+    # keys take only 3 distinct norms, so thousands tie at the threshold
+    vals = np.array([0.5, 1.0, 2.0], dtype=np.float16)
+    kv[:, :, 0] = 0
+    kv[:, :, 0, :, :, 0] = vals[rng.integers(0, 3, size=kv[:, :, 0, :, :, 0].shape)]
+    s = SideBySide(wl, kv_host=kv)
+    try:
+        st = s.compress_and_compare()
+        assert st["units_kept_identical"] == st["units"]
+    finally:
+        s.close()
+    # clustered: norms equal up to one fp16 ulp in a single channel
+    kv2 = synth.fill_pool_host(wl)
+    kv2[:, :, 0] = 1.0
+    kv2[:, :, 0, :, :, 0] = (1.0 + rng.integers(0, 2, size=kv2[:, :, 0, :, :, 0].shape) / 1024.0
+                             ).astype(np.float16)
+    s = SideBySide(wl, kv_host=kv2)
+    try:
+        s.compress_and_compare()
+    finally:
+        s.close()
