@@ -141,9 +141,9 @@ def main():
     comp = wl.methods != synth.METHOD_NONE
     tokens = int(wl.seq_lens[comp].astype(np.int64).sum())
     path_bytes = dw.algorithmic_bytes()
-    kbytes = dw.kernel_algorithmic_bytes()
+    kbytes = dw.kernel_algorithmic_bytes(8192 if args.score_mode == "auto" else 0)
     # dominant kernel = the one with the largest average duration
-    dom = max(("snapkv_score", "knorm_score", "gather"), key=lambda k: kavg.get(k, 0.0))
+    dom = max(kbytes, key=lambda k: kavg.get(k, 0.0))
     dom_gbps = kbytes[dom] / (kavg[dom] * 1e-3) / 1e9
 
     out = {

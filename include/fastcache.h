@@ -150,16 +150,21 @@ int fc_compress_batch(fc_pool* pool, int32_t* dev_block_tables, int max_blocks_p
                       int32_t* dev_kept_out, void* stream);
 
 /*
- * Which SnapKV score kernel fc_compress_batch uses.
- *   FC_SCORE_TWO_PASS: K is streamed twice (row statistics, then column sums);
- *     workgroups never wait for each other; any length up to FC_MAX_SEQ_LEN.
- *   FC_SCORE_ONE_PASS: K is streamed once; the logits stay in registers and
- *     the workgroups that share a long head exchange row statistics.  Needs a
- *     device that can hold the kernel's grid co-resident; fc_compress_batch
- *     returns FC_EINVAL if that is not possible for the batch.
- *   FC_SCORE_AUTO (default): the faster of the two as measured on MI355X
- *     (at present the two-pass kernel).
- * Both produce the same scores up to fp32 rounding.
+ * How fc_compress_batch schedules the scoring.
+ *   FC_SCORE_AUTO (default): every (request, layer, head) of at most 8192
+ *     tokens is handled by one fused kernel (two-pass score -> select ->
+ *     gather inside the workgroup that owns the head; scores stay in LDS);
+ *     longer heads go through the separate two-pass score, select and gather
+ *     kernels.
+ *   FC_SCORE_TWO_PASS: separate kernels for everything; SnapKV scoring streams
+ *     K twice (row statistics, then column sums); workgroups never wait for
+ *     each other; any length up to FC_MAX_SEQ_LEN.
+ *   FC_SCORE_ONE_PASS: separate kernels; SnapKV scoring streams K once, the
+ *     logits stay in registers and the workgroups that share a long head
+ *     exchange row statistics.  Needs a device that can hold the kernel's grid
+ *     co-resident; fc_compress_batch returns FC_EINVAL if that is not
+ *     possible for the batch.  Slower than two-pass on MI355X as measured.
+ * All three produce the same scores up to fp32 rounding.
  */
 enum { FC_SCORE_AUTO = 0, FC_SCORE_TWO_PASS = 1, FC_SCORE_ONE_PASS = 2 };
 int fc_set_score_mode(fc_pool* pool, int mode);
@@ -174,7 +179,7 @@ int fc_set_score_mode(fc_pool* pool, int mode);
  * fc_kernel_name(i) names slot i.  fc_set_profiling(pool, 1) restarts the
  * average.
  */
-#define FC_N_KERNELS 6
+#define FC_N_KERNELS 7
 int fc_set_profiling(fc_pool* pool, int enable);
 int fc_get_kernel_times(fc_pool* pool, float* host_ms);
 const char* fc_kernel_name(int i);

@@ -37,8 +37,9 @@ int fail(int code, const char* fmt, ...) {
       return fail(FC_EDEVICE, "%s failed: %s", #call, hipGetErrorString(e_));   \
   } while (0)
 
-const char* const kKernelNames[K_COUNT] = {"plan_alloc",   "snapkv_score", "knorm_score",
-                                           "select",       "gather",       "reclaim"};
+const char* const kKernelNames[K_COUNT] = {"plan_alloc", "snapkv_score", "knorm_score",
+                                           "select",     "gather",       "reclaim",
+                                           "fused_unit"};
 
 size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -383,7 +384,7 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
   if ((rc = grow(&p->ids, &p->ids_cap, (size_t)total_old + total_new)) != FC_OK) return rc;
   const size_t desc_bytes = round_up((size_t)n_comp * sizeof(ReqDesc), 16);
   const size_t order_bytes = round_up((size_t)n_comp * sizeof(int32_t), 16);
-  const size_t meta_bytes = desc_bytes + 3 * order_bytes;
+  const size_t meta_bytes = desc_bytes + 4 * order_bytes;
   if ((rc = grow_meta(p, meta_bytes)) != FC_OK) return rc;
   if (p->meta_pending) {
     // the previous call's descriptor upload must have left the staging buffer
@@ -391,21 +392,41 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
     p->meta_pending = false;
   }
   memcpy(p->host_meta, descs.data(), (size_t)n_comp * sizeof(ReqDesc));
-  int32_t* order_all = reinterpret_cast<int32_t*>(p->host_meta + desc_bytes);
-  int32_t* order_snap = reinterpret_cast<int32_t*>(p->host_meta + desc_bytes + order_bytes);
-  int32_t* order_knorm = reinterpret_cast<int32_t*>(p->host_meta + desc_bytes + 2 * order_bytes);
-  std::iota(order_all, order_all + n_comp, 0);
-  // longest first, so that the tail of each launch is made of short units
-  std::stable_sort(order_all, order_all + n_comp,
-                   [&](int a, int b) { return descs[a].seq_len > descs[b].seq_len; });
-  int ns = 0, nk = 0;
-  for (int i = 0; i < n_comp; ++i) {
-    const int di = order_all[i];
-    if (descs[di].method == FC_METHOD_SNAPKV)
-      order_snap[ns++] = di;
-    else
-      order_knorm[nk++] = di;
+  // Work lists (descriptor indices, longest first so that the tail of each
+  // launch is made of short units).  Heads short enough for the fused kernel
+  // (score -> select -> gather in one workgroup) share one list; the rest go
+  // through the separate kernels, listed per method.
+  enum { LIST_FUSED = 0, LIST_SNAP, LIST_KNORM, LIST_ALL, N_LISTS };
+  int32_t* lists[N_LISTS];
+  size_t list_off[N_LISTS];
+  int n_list[N_LISTS] = {};
+  int max_len_list[N_LISTS] = {};
+  for (int i = 0; i < N_LISTS; ++i) {
+    list_off[i] = desc_bytes + (size_t)i * order_bytes;
+    lists[i] = reinterpret_cast<int32_t*>(p->host_meta + list_off[i]);
   }
+  std::vector<int> sorted(n_comp);
+  std::iota(sorted.begin(), sorted.end(), 0);
+  std::stable_sort(sorted.begin(), sorted.end(),
+                   [&](int a, int b) { return descs[a].seq_len > descs[b].seq_len; });
+  const bool allow_fused = p->score_mode == FC_SCORE_AUTO;
+  bool fused_has_snap = false;
+  for (int di : sorted) {
+    const ReqDesc& d = descs[di];
+    const bool snap = d.method == FC_METHOD_SNAPKV;
+    int li;
+    if (allow_fused && d.seq_len <= kFusedMaxLen) {
+      li = LIST_FUSED;
+      fused_has_snap |= snap;
+    } else {
+      li = snap ? LIST_SNAP : LIST_KNORM;
+      lists[LIST_ALL][n_list[LIST_ALL]++] = di;
+      max_len_list[LIST_ALL] = std::max(max_len_list[LIST_ALL], d.seq_len);
+    }
+    lists[li][n_list[li]++] = di;
+    max_len_list[li] = std::max(max_len_list[li], d.seq_len);
+  }
+  const int ns = n_list[LIST_SNAP], nk = n_list[LIST_KNORM];
   FC_HIP(hipMemcpyAsync(p->dev_meta, p->host_meta, meta_bytes, hipMemcpyHostToDevice, stream));
   FC_HIP(hipEventRecord(p->meta_event, stream));
   p->meta_pending = true;
@@ -421,12 +442,16 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
   bp.total_new = total_new;
   bp.total_old = total_old;
   bp.descs = reinterpret_cast<const ReqDesc*>(p->dev_meta);
-  bp.order_all = reinterpret_cast<const int32_t*>(p->dev_meta + desc_bytes);
-  bp.order_snap = reinterpret_cast<const int32_t*>(p->dev_meta + desc_bytes + order_bytes);
-  bp.order_knorm = reinterpret_cast<const int32_t*>(p->dev_meta + desc_bytes + 2 * order_bytes);
-  bp.n_comp = n_comp;
+  auto dev_list = [&](int i) { return reinterpret_cast<const int32_t*>(p->dev_meta + list_off[i]); };
+  bp.order_all = dev_list(LIST_ALL);
+  bp.order_snap = dev_list(LIST_SNAP);
+  bp.order_knorm = dev_list(LIST_KNORM);
+  bp.n_comp = n_comp;  // plan_alloc / reclaim walk every descriptor
   bp.n_snap = ns;
   bp.n_knorm = nk;
+  bp.n_unfused = n_list[LIST_ALL];
+  bp.n_fused = n_list[LIST_FUSED];
+  bp.order_fused = dev_list(LIST_FUSED);
   bp.block_tables = dev_block_tables;
   bp.max_blocks = max_blocks_per_req;
   bp.old_ids = p->ids;
@@ -468,8 +493,12 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
                          : launch_snapkv_score(bp, stream);
   }));
   FC_HIP(run(K_KNORM_SCORE, nk > 0, [&] { return launch_knorm_score(bp, stream); }));
-  FC_HIP(run(K_SELECT, true, [&] { return launch_select(bp, max_len, stream); }));
-  FC_HIP(run(K_GATHER, true, [&] { return launch_gather(bp, stream); }));
+  FC_HIP(run(K_SELECT, bp.n_unfused > 0,
+             [&] { return launch_select(bp, max_len_list[LIST_ALL], stream); }));
+  FC_HIP(run(K_GATHER, bp.n_unfused > 0, [&] { return launch_gather(bp, stream); }));
+  FC_HIP(run(K_FUSED, bp.n_fused > 0, [&] {
+    return launch_fused(bp, fused_has_snap, max_len_list[LIST_FUSED], stream);
+  }));
   FC_HIP(run(K_RECLAIM, true, [&] { return launch_reclaim(bp, stream); }));
 
   // ---- host mirrors ------------------------------------------------------------

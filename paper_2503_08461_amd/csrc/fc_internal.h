@@ -42,7 +42,8 @@ struct BatchParams {
   const int32_t* order_all;    // [n_comp] desc indices, longest first
   const int32_t* order_snap;   // [n_snap]
   const int32_t* order_knorm;  // [n_knorm]
-  int32_t n_comp, n_snap, n_knorm;
+  const int32_t* order_fused;  // [n_fused] units handled by the fused kernel (both methods)
+  int32_t n_comp, n_snap, n_knorm, n_unfused, n_fused;
   int32_t* block_tables;       // caller's [n_req][max_blocks]
   int32_t max_blocks;
   int32_t* old_ids;            // [total_old] saved pre-compression ids
@@ -66,7 +67,8 @@ enum KernelSlot {
   K_SELECT = 3,
   K_GATHER = 4,
   K_RECLAIM = 5,
-  K_COUNT = 6
+  K_FUSED = 6,
+  K_COUNT = 7
 };
 
 // Launchers (fc_kernels.hip).  Each returns the hipError_t of the launch.
@@ -85,6 +87,10 @@ hipError_t launch_snapkv_score_team(const BatchParams& p, int grid, hipStream_t 
 hipError_t launch_knorm_score(const BatchParams& p, hipStream_t s);
 hipError_t launch_select(const BatchParams& p, int max_seq_len, hipStream_t s);
 hipError_t launch_gather(const BatchParams& p, hipStream_t s);
+// score -> select -> gather of every unit of order_fused in one launch; needs
+// max_seq_len <= kFusedMaxLen; any_snap: the list holds a SnapKV request
+hipError_t launch_fused(const BatchParams& p, bool any_snap, int max_seq_len, hipStream_t s);
+static constexpr int kFusedMaxLen = 8192;
 hipError_t launch_reclaim(const BatchParams& p, hipStream_t s);
 hipError_t kernels_one_time_setup();
 

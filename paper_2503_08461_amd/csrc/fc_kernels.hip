@@ -76,15 +76,20 @@ __global__ __launch_bounds__(kThreads) void reclaim_kernel(BatchParams p) {
 // The un-pooled column sums of the prefix are written to raw_scores; pooling
 // and the forced window are applied by the select kernel.
 
-template <int D, int NT>
-__global__ __launch_bounds__(kThreads) void snapkv_score_kernel(BatchParams p) {
+struct ScoreShared {
+  float m[kWaves][4][64];
+  float z[kWaves][4][64];
+  float fin[64];
+};
+
+// Scores one (request, layer, head); store(j, a_j) receives the un-pooled
+// column sum of every prefix token j.  All threads of the workgroup call.
+template <int D, int NT, typename Store>
+__device__ __forceinline__ void snapkv_unit(const BatchParams& p, const ReqDesc& rd, int lh,
+                                            ScoreShared& sh, Store store) {
   constexpr int KS = D / 32;
-  const int n_lh = p.n_layers * p.n_heads;
-  const int slot = blockIdx.x / n_lh;
-  const int lh = blockIdx.x - slot * n_lh;
   const int layer = lh / p.n_heads;
   const int head = lh - layer * p.n_heads;
-  const ReqDesc rd = p.descs[p.order_snap[slot]];
   const int L = rd.seq_len;
   const int W = p.window;
   const int lane = threadIdx.x & 63;
@@ -92,10 +97,6 @@ __global__ __launch_bounds__(kThreads) void snapkv_score_kernel(BatchParams p) {
   const int c16 = lane & 15;
   const int q4 = lane >> 4;
   const int32_t* old_ids = p.old_ids + rd.old_off;
-
-  __shared__ float sm_m[kWaves][4][64];
-  __shared__ float sm_z[kWaves][4][64];
-  __shared__ float sm_final[64];
 
   // window queries, resident in registers for both passes
   const _Float16* qbase = p.q_window + rd.q_off + (size_t)lh * W * D;
@@ -171,8 +172,8 @@ __global__ __launch_bounds__(kThreads) void snapkv_score_kernel(BatchParams p) {
   // combine the 16 partial (max, sum) pairs of every query
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
-    sm_m[wave][q4][nt * 16 + c16] = m[nt];
-    sm_z[wave][q4][nt * 16 + c16] = z[nt];
+    sh.m[wave][q4][nt * 16 + c16] = m[nt];
+    sh.z[wave][q4][nt * 16 + c16] = z[nt];
   }
   __syncthreads();
   if (threadIdx.x < 64) {
@@ -181,14 +182,14 @@ __global__ __launch_bounds__(kThreads) void snapkv_score_kernel(BatchParams p) {
     if (row < W) {
       float mm = -3.0e38f;
       for (int w = 0; w < kWaves; ++w)
-        for (int q = 0; q < 4; ++q) mm = fmaxf(mm, sm_m[w][q][row]);
+        for (int q = 0; q < 4; ++q) mm = fmaxf(mm, sh.m[w][q][row]);
       float zz = 0.f;
       for (int w = 0; w < kWaves; ++w)
         for (int q = 0; q < 4; ++q)
-          zz += sm_z[w][q][row] * __builtin_amdgcn_exp2f(sm_m[w][q][row] - mm);
+          zz += sh.z[w][q][row] * __builtin_amdgcn_exp2f(sh.m[w][q][row] - mm);
       out = mm + log2f(zz);
     }
-    sm_final[row] = out;
+    sh.fin[row] = out;
   }
   __syncthreads();
 
@@ -199,9 +200,8 @@ __global__ __launch_bounds__(kThreads) void snapkv_score_kernel(BatchParams p) {
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-    for (int r = 0; r < 4; ++r) mrow[nt][r] = sm_final[nt * 16 + q4 * 4 + r];
+    for (int r = 0; r < 4; ++r) mrow[nt][r] = sh.fin[nt * 16 + q4 * 4 + r];
 
-  float* raw = p.raw_scores + rd.score_off + (size_t)lh * L;
   {
     half8 kc[KS], kn[KS];
     int b = wave;
@@ -222,11 +222,22 @@ __global__ __launch_bounds__(kThreads) void snapkv_score_kernel(BatchParams p) {
       colsum += __shfl_xor(colsum, 16);
       colsum += __shfl_xor(colsum, 32);
       const int tok = b * 16 + c16;
-      if (q4 == 0 && tok < n_prefix) raw[tok] = colsum;
+      if (q4 == 0 && tok < n_prefix) store(tok, colsum);
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) kc[ks] = kn[ks];
     }
   }
+}
+
+template <int D, int NT>
+__global__ __launch_bounds__(kThreads) void snapkv_score_kernel(BatchParams p) {
+  __shared__ ScoreShared sh;
+  const int n_lh = p.n_layers * p.n_heads;
+  const int slot = blockIdx.x / n_lh;
+  const int lh = blockIdx.x - slot * n_lh;
+  const ReqDesc rd = p.descs[p.order_snap[slot]];
+  float* raw = p.raw_scores + rd.score_off + (size_t)lh * rd.seq_len;
+  snapkv_unit<D, NT>(p, rd, lh, sh, [&](int j, float v) { raw[j] = v; });
 }
 
 // ---------------------------------------------------------------------------
@@ -237,17 +248,14 @@ __global__ __launch_bounds__(kThreads) void snapkv_score_kernel(BatchParams p) {
 // chunk with fully coalesced 128-bit loads (64 lanes x 16 B = 1 KiB per
 // instruction) and reduces the squares over the lanes that share a row.
 
-template <int D>
-__global__ __launch_bounds__(kThreads) void knorm_score_kernel(BatchParams p) {
+template <int D, typename Store>
+__device__ __forceinline__ void knorm_unit(const BatchParams& p, const ReqDesc& rd, int lh,
+                                           Store store) {
   constexpr int LPR = D / 8;     // lanes per token row
   constexpr int RPI = 64 / LPR;  // rows per load instruction
   constexpr int NI = 16 / RPI;   // load instructions per block
-  const int n_lh = p.n_layers * p.n_heads;
-  const int slot = blockIdx.x / n_lh;
-  const int lh = blockIdx.x - slot * n_lh;
   const int layer = lh / p.n_heads;
   const int head = lh - layer * p.n_heads;
-  const ReqDesc rd = p.descs[p.order_knorm[slot]];
   const int L = rd.seq_len;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -255,7 +263,6 @@ __global__ __launch_bounds__(kThreads) void knorm_score_kernel(BatchParams p) {
   const size_t blk_stride = (size_t)2 * p.n_heads * 16 * D;
   const _Float16* kbase = p.kv + (size_t)layer * p.n_blocks * blk_stride +
                           (size_t)head * 16 * D + lane * 8;
-  float* raw = p.raw_scores + rd.score_off + (size_t)lh * L;
   const int nb = (L + 15) >> 4;
   for (int b = wave; b < nb; b += kWaves) {
     const int blk = clamp_block(old_ids[b], p.n_blocks);
@@ -274,9 +281,19 @@ __global__ __launch_bounds__(kThreads) void knorm_score_kernel(BatchParams p) {
 #pragma unroll
       for (int o = 1; o < LPR; o <<= 1) s += __shfl_xor(s, o);
       const int tok = b * 16 + k * RPI + lane / LPR;
-      if ((lane % LPR) == 0 && tok < L) raw[tok] = -sqrtf(s);
+      if ((lane % LPR) == 0 && tok < L) store(tok, -sqrtf(s));
     }
   }
+}
+
+template <int D>
+__global__ __launch_bounds__(kThreads) void knorm_score_kernel(BatchParams p) {
+  const int n_lh = p.n_layers * p.n_heads;
+  const int slot = blockIdx.x / n_lh;
+  const int lh = blockIdx.x - slot * n_lh;
+  const ReqDesc rd = p.descs[p.order_knorm[slot]];
+  float* raw = p.raw_scores + rd.score_off + (size_t)lh * rd.seq_len;
+  knorm_unit<D>(p, rd, lh, [&](int j, float v) { raw[j] = v; });
 }
 
 // ---------------------------------------------------------------------------
@@ -363,20 +380,32 @@ __device__ __forceinline__ void bucket_pass(int n, uint32_t lo, int shift, uint3
   __syncthreads();
 }
 
-__global__ __launch_bounds__(kThreads) void select_kernel(BatchParams p) {
-  extern __shared__ uint32_t keys[];
-  __shared__ int hist[kBuckets];
-  __shared__ uint32_t cand[kMaxCand];
-  __shared__ int wsum[kWaves];
-  __shared__ uint32_t wmin[kWaves], wmax[kWaves];
-  __shared__ int sel[2];
-  __shared__ int n_cand;
-  __shared__ int cnt[kWaves][2];
+struct SelectShared {
+  int hist[kBuckets];
+  uint32_t cand[kMaxCand];
+  int wsum[kWaves];
+  uint32_t wmin[kWaves], wmax[kWaves];
+  int sel[2];
+  int n_cand;
+  int cnt[kWaves][2];
+};
 
-  const int n_lh = p.n_layers * p.n_heads;
-  const int slot = blockIdx.x / n_lh;
-  const int lh = blockIdx.x - slot * n_lh;
-  const ReqDesc rd = p.descs[p.order_all[slot]];
+// Selects the kept tokens of one (request, layer, head) and writes them, in
+// ascending order, to the kept list.  `keys` is LDS room for seq_len words.
+// kRawInLds: the un-pooled scores already sit in keys[] (as floats, written
+// by this workgroup and made visible by a barrier); otherwise they are read
+// from raw_scores.  All threads of the workgroup call.
+template <bool kRawInLds>
+__device__ __forceinline__ void select_unit(const BatchParams& p, const ReqDesc& rd, int lh,
+                                            uint32_t* keys, SelectShared& sh) {
+  int* hist = sh.hist;
+  uint32_t* cand = sh.cand;
+  int* wsum = sh.wsum;
+  uint32_t* wmin = sh.wmin;
+  uint32_t* wmax = sh.wmax;
+  int* sel = sh.sel;
+  int& n_cand = sh.n_cand;
+  int (*cnt)[2] = sh.cnt;
   const int L = rd.seq_len;
   const int B = rd.budget;
   const int tid = threadIdx.x;
@@ -391,10 +420,12 @@ __global__ __launch_bounds__(kThreads) void select_kernel(BatchParams p) {
 
   // ---- 1. final scores -> keys, min / max -------------------------------------
   uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
-  if (snap && n_sel <= kStagePerThread * kThreads) {
+  if (snap && (kRawInLds || n_sel <= kStagePerThread * kThreads)) {
     float* stage = reinterpret_cast<float*>(keys);
-    for (int j = tid; j < n_sel; j += kThreads) stage[j] = raw[j];
-    __syncthreads();
+    if (!kRawInLds) {
+      for (int j = tid; j < n_sel; j += kThreads) stage[j] = raw[j];
+      __syncthreads();
+    }
     const int h = p.pool_kernel >> 1;
     float pv[kStagePerThread];
 #pragma unroll
@@ -434,7 +465,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(BatchParams p) {
     }
   } else {
     for (int j = tid; j < n_sel; j += kThreads) {
-      const float s = raw[j];
+      const float s = kRawInLds ? reinterpret_cast<float*>(keys)[j] : raw[j];
       const uint32_t k = score_key(s);
       keys[j] = k;
       kmin = min(kmin, k);
@@ -549,6 +580,16 @@ __global__ __launch_bounds__(kThreads) void select_kernel(BatchParams p) {
   }
 }
 
+__global__ __launch_bounds__(kThreads) void select_kernel(BatchParams p) {
+  extern __shared__ uint32_t keys[];
+  __shared__ SelectShared sh;
+  const int n_lh = p.n_layers * p.n_heads;
+  const int slot = blockIdx.x / n_lh;
+  const int lh = blockIdx.x - slot * n_lh;
+  const ReqDesc rd = p.descs[p.order_all[slot]];
+  select_unit<false>(p, rd, lh, keys, sh);
+}
+
 // ---------------------------------------------------------------------------
 // gather / compact
 // ---------------------------------------------------------------------------
@@ -559,16 +600,12 @@ __global__ __launch_bounds__(kThreads) void select_kernel(BatchParams p) {
 // destination chunk is contiguous.
 
 template <int D>
-__global__ __launch_bounds__(kThreads) void gather_kernel(BatchParams p) {
+__device__ __forceinline__ void gather_unit(const BatchParams& p, const ReqDesc& rd, int lh) {
   constexpr int LPR = D / 8;
   constexpr int RPI = 64 / LPR;
   constexpr int NI = 16 / RPI;
-  const int n_lh = p.n_layers * p.n_heads;
-  const int slot = blockIdx.x / n_lh;
-  const int lh = blockIdx.x - slot * n_lh;
   const int layer = lh / p.n_heads;
   const int head = lh - layer * p.n_heads;
-  const ReqDesc rd = p.descs[p.order_all[slot]];
   const int B = rd.budget;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -610,12 +647,61 @@ __global__ __launch_bounds__(kThreads) void gather_kernel(BatchParams p) {
   }
 }
 
+template <int D>
+__global__ __launch_bounds__(kThreads) void gather_kernel(BatchParams p) {
+  const int n_lh = p.n_layers * p.n_heads;
+  const int slot = blockIdx.x / n_lh;
+  const int lh = blockIdx.x - slot * n_lh;
+  const ReqDesc rd = p.descs[p.order_all[slot]];
+  gather_unit<D>(p, rd, lh);
+}
+
+// ---------------------------------------------------------------------------
+// fused per-unit kernel: score -> select -> gather in one workgroup
+// ---------------------------------------------------------------------------
+//
+// For heads whose scores fit the workgroup's LDS share the three steps run
+// back to back in the workgroup that owns the (request, layer, head): the
+// column sums (or key norms) go straight into LDS, the selection works on
+// them in place and the copy follows.  The scores never travel through HBM,
+// the stage is one launch per method, and the LDS/ALU-bound selection of one
+// workgroup overlaps the HBM-bound streaming of the others on the same CU.
+// One launch serves both methods (the unit's descriptor says which); NT =
+// ceil(window / 16), or 0 when the launch holds no SnapKV unit.
+
+template <int D, int NT>
+__global__ __launch_bounds__(kThreads) void fused_unit_kernel(BatchParams p) {
+  extern __shared__ uint32_t keys[];
+  __shared__ union {
+    ScoreShared score;
+    SelectShared select;
+  } sh;
+  const int n_lh = p.n_layers * p.n_heads;
+  const int slot = blockIdx.x / n_lh;
+  const int lh = blockIdx.x - slot * n_lh;
+  const ReqDesc rd = p.descs[p.order_fused[slot]];
+  float* stage = reinterpret_cast<float*>(keys);
+  bool snap = false;
+  if constexpr (NT > 0) snap = rd.method == 1 /* FC_METHOD_SNAPKV */;  // uniform per workgroup
+  if (snap) {
+    if constexpr (NT > 0)
+      snapkv_unit<D, NT>(p, rd, lh, sh.score, [&](int j, float v) { stage[j] = v; });
+  } else {
+    knorm_unit<D>(p, rd, lh, [&](int j, float v) { stage[j] = v; });
+  }
+  __syncthreads();
+  select_unit<true>(p, rd, lh, keys, sh.select);
+  __syncthreads();  // the kept list (global memory, this workgroup's own) is complete
+  gather_unit<D>(p, rd, lh);
+}
+
 // ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
 
 hipError_t kernels_one_time_setup() {
   // the select kernel may need more than the default 64 KiB of dynamic LDS
+  // (the fused kernel never does: kFusedMaxLen * 4 = 32 KiB)
   return hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel),
                              hipFuncAttributeMaxDynamicSharedMemorySize, 32768 * 4);
 }
@@ -682,14 +768,36 @@ hipError_t launch_knorm_score(const BatchParams& p, hipStream_t s) {
 }
 
 hipError_t launch_select(const BatchParams& p, int max_seq_len, hipStream_t s) {
-  const unsigned grid = (unsigned)p.n_comp * p.n_layers * p.n_heads;
+  const unsigned grid = (unsigned)p.n_unfused * p.n_layers * p.n_heads;
   const size_t lds = (size_t)max_seq_len * sizeof(uint32_t);
   select_kernel<<<grid, kThreads, lds, s>>>(p);
   return hipGetLastError();
 }
 
+template <int D>
+static hipError_t launch_fused_d(const BatchParams& p, bool any_snap, size_t lds, hipStream_t s) {
+  const unsigned grid = (unsigned)p.n_fused * p.n_layers * p.n_heads;
+  switch (any_snap ? (p.window + 15) / 16 : 0) {
+    case 0: fused_unit_kernel<D, 0><<<grid, kThreads, lds, s>>>(p); break;
+    case 1: fused_unit_kernel<D, 1><<<grid, kThreads, lds, s>>>(p); break;
+    case 2: fused_unit_kernel<D, 2><<<grid, kThreads, lds, s>>>(p); break;
+    case 3: fused_unit_kernel<D, 3><<<grid, kThreads, lds, s>>>(p); break;
+    case 4: fused_unit_kernel<D, 4><<<grid, kThreads, lds, s>>>(p); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_fused(const BatchParams& p, bool any_snap, int max_seq_len, hipStream_t s) {
+  if (p.n_fused == 0) return hipSuccess;
+  const size_t lds = (size_t)max_seq_len * sizeof(uint32_t);
+  if (p.head_dim == 128) return launch_fused_d<128>(p, any_snap, lds, s);
+  if (p.head_dim == 64) return launch_fused_d<64>(p, any_snap, lds, s);
+  return hipErrorInvalidValue;
+}
+
 hipError_t launch_gather(const BatchParams& p, hipStream_t s) {
-  const unsigned grid = (unsigned)p.n_comp * p.n_layers * p.n_heads;
+  const unsigned grid = (unsigned)p.n_unfused * p.n_layers * p.n_heads;
   if (p.head_dim == 128)
     gather_kernel<128><<<grid, kThreads, 0, s>>>(p);
   else if (p.head_dim == 64)

@@ -70,15 +70,24 @@ class DeviceWorkload:
         kept = int(wl.budgets[comp].astype(np.int64).sum())
         return n_lh * (tokens * row + kept * 4 * row)
 
-    def kernel_algorithmic_bytes(self):
+    def kernel_algorithmic_bytes(self, fused_max_len=8192):
+        """Algorithmic bytes per launch of each kernel that moves bulk data.
+        With the default scheduling, heads of at most `fused_max_len` tokens
+        run in the fused kernels (score + gather bytes), longer ones in the
+        separate kernels."""
         wl = self.wl
         n_lh = wl.n_layers * wl.n_heads
         row = 2 * wl.head_dim
+        L = wl.seq_lens.astype(np.int64)
+        B = wl.budgets.astype(np.int64)
         snap = wl.methods == synth.METHOD_SNAPKV
         kn = wl.methods == synth.METHOD_KNORM
-        comp = wl.methods != synth.METHOD_NONE
+        short = wl.seq_lens <= fused_max_len
+        long_ = ~short
         return {
-            "snapkv_score": n_lh * int(wl.seq_lens[snap].astype(np.int64).sum()) * row,
-            "knorm_score": n_lh * int(wl.seq_lens[kn].astype(np.int64).sum()) * row,
-            "gather": n_lh * int(wl.budgets[comp].astype(np.int64).sum()) * 4 * row,
+            "fused_unit": n_lh * int((L[(snap | kn) & short] * row
+                                      + B[(snap | kn) & short] * 4 * row).sum()),
+            "snapkv_score": n_lh * int(L[snap & long_].sum()) * row,
+            "knorm_score": n_lh * int(L[kn & long_].sum()) * row,
+            "gather": n_lh * int(B[(snap | kn) & long_].sum()) * 4 * row,
         }

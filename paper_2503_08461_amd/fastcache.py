@@ -15,7 +15,7 @@ FC_OK, FC_EINVAL, FC_ENOMEM, FC_EDEVICE = 0, -1, -2, -3
 FC_METHOD_NONE, FC_METHOD_SNAPKV, FC_METHOD_KNORM = 0, 1, 2
 FC_DTYPE_F16 = 0
 FC_BLOCK_SIZE = 16
-FC_N_KERNELS = 6
+FC_N_KERNELS = 7
 FC_SCORE_AUTO, FC_SCORE_TWO_PASS, FC_SCORE_ONE_PASS = 0, 1, 2
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libfastcache.so")

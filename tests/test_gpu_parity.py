@@ -10,10 +10,11 @@ from paper_2503_08461_amd import synth
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(params=[1, 2], ids=["two_pass", "one_pass"])
+@pytest.fixture(params=[0, 1, 2], ids=["auto_fused", "two_pass", "one_pass"])
 def score_mode(request):
-    """Both SnapKV score kernels must meet the same bar (FC_SCORE_TWO_PASS = 1,
-    FC_SCORE_ONE_PASS = 2)."""
+    """Every scheduling of the stage must meet the same bar (FC_SCORE_AUTO = 0:
+    fused score/select/gather kernel; FC_SCORE_TWO_PASS = 1 and
+    FC_SCORE_ONE_PASS = 2: separate kernels)."""
     return request.param
 
 
