@@ -84,9 +84,10 @@ struct ScoreShared {
 
 // Scores one (request, layer, head); store(j, a_j) receives the un-pooled
 // column sum of every prefix token j.  All threads of the workgroup call.
+// `old_ids` are the request's pre-compression block ids (global or LDS copy).
 template <int D, int NT, typename Store>
 __device__ __forceinline__ void snapkv_unit(const BatchParams& p, const ReqDesc& rd, int lh,
-                                            ScoreShared& sh, Store store) {
+                                            const int32_t* old_ids, ScoreShared& sh, Store store) {
   constexpr int KS = D / 32;
   const int layer = lh / p.n_heads;
   const int head = lh - layer * p.n_heads;
@@ -96,7 +97,6 @@ __device__ __forceinline__ void snapkv_unit(const BatchParams& p, const ReqDesc&
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int c16 = lane & 15;
   const int q4 = lane >> 4;
-  const int32_t* old_ids = p.old_ids + rd.old_off;
 
   // window queries, resident in registers for both passes
   const _Float16* qbase = p.q_window + rd.q_off + (size_t)lh * W * D;
@@ -237,7 +237,7 @@ __global__ __launch_bounds__(kThreads) void snapkv_score_kernel(BatchParams p) {
   const int lh = blockIdx.x - slot * n_lh;
   const ReqDesc rd = p.descs[p.order_snap[slot]];
   float* raw = p.raw_scores + rd.score_off + (size_t)lh * rd.seq_len;
-  snapkv_unit<D, NT>(p, rd, lh, sh, [&](int j, float v) { raw[j] = v; });
+  snapkv_unit<D, NT>(p, rd, lh, p.old_ids + rd.old_off, sh, [&](int j, float v) { raw[j] = v; });
 }
 
 // ---------------------------------------------------------------------------
@@ -250,7 +250,7 @@ __global__ __launch_bounds__(kThreads) void snapkv_score_kernel(BatchParams p) {
 
 template <int D, typename Store>
 __device__ __forceinline__ void knorm_unit(const BatchParams& p, const ReqDesc& rd, int lh,
-                                           Store store) {
+                                           const int32_t* old_ids, Store store) {
   constexpr int LPR = D / 8;     // lanes per token row
   constexpr int RPI = 64 / LPR;  // rows per load instruction
   constexpr int NI = 16 / RPI;   // load instructions per block
@@ -259,7 +259,6 @@ __device__ __forceinline__ void knorm_unit(const BatchParams& p, const ReqDesc& 
   const int L = rd.seq_len;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int32_t* old_ids = p.old_ids + rd.old_off;
   const size_t blk_stride = (size_t)2 * p.n_heads * 16 * D;
   const _Float16* kbase = p.kv + (size_t)layer * p.n_blocks * blk_stride +
                           (size_t)head * 16 * D + lane * 8;
@@ -293,7 +292,7 @@ __global__ __launch_bounds__(kThreads) void knorm_score_kernel(BatchParams p) {
   const int lh = blockIdx.x - slot * n_lh;
   const ReqDesc rd = p.descs[p.order_knorm[slot]];
   float* raw = p.raw_scores + rd.score_off + (size_t)lh * rd.seq_len;
-  knorm_unit<D>(p, rd, lh, [&](int j, float v) { raw[j] = v; });
+  knorm_unit<D>(p, rd, lh, p.old_ids + rd.old_off, [&](int j, float v) { raw[j] = v; });
 }
 
 // ---------------------------------------------------------------------------
@@ -600,7 +599,8 @@ __global__ __launch_bounds__(kThreads) void select_kernel(BatchParams p) {
 // destination chunk is contiguous.
 
 template <int D>
-__device__ __forceinline__ void gather_unit(const BatchParams& p, const ReqDesc& rd, int lh) {
+__device__ __forceinline__ void gather_unit(const BatchParams& p, const ReqDesc& rd, int lh,
+                                            const int32_t* old_ids) {
   constexpr int LPR = D / 8;
   constexpr int RPI = 64 / LPR;
   constexpr int NI = 16 / RPI;
@@ -609,7 +609,6 @@ __device__ __forceinline__ void gather_unit(const BatchParams& p, const ReqDesc&
   const int B = rd.budget;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int32_t* old_ids = p.old_ids + rd.old_off;
   const int32_t* new_ids = p.new_ids + rd.new_off;
   const int32_t* kept = p.kept + rd.kept_off + (size_t)lh * B;
   const size_t chunk = (size_t)16 * D;               // one (block, kv, head)
@@ -653,7 +652,7 @@ __global__ __launch_bounds__(kThreads) void gather_kernel(BatchParams p) {
   const int slot = blockIdx.x / n_lh;
   const int lh = blockIdx.x - slot * n_lh;
   const ReqDesc rd = p.descs[p.order_all[slot]];
-  gather_unit<D>(p, rd, lh);
+  gather_unit<D>(p, rd, lh, p.old_ids + rd.old_off);
 }
 
 // ---------------------------------------------------------------------------
@@ -681,18 +680,23 @@ __global__ __launch_bounds__(kThreads) void fused_unit_kernel(BatchParams p) {
   const int lh = blockIdx.x - slot * n_lh;
   const ReqDesc rd = p.descs[p.order_fused[slot]];
   float* stage = reinterpret_cast<float*>(keys);
+  // the request's block ids, read once per workgroup (every later use is an LDS read)
+  __shared__ int32_t sm_ids[kFusedMaxLen / 16];
+  for (int i = threadIdx.x; i < rd.n_old; i += kThreads)
+    sm_ids[i] = clamp_block(p.old_ids[rd.old_off + i], p.n_blocks);
+  __syncthreads();
   bool snap = false;
   if constexpr (NT > 0) snap = rd.method == 1 /* FC_METHOD_SNAPKV */;  // uniform per workgroup
   if (snap) {
     if constexpr (NT > 0)
-      snapkv_unit<D, NT>(p, rd, lh, sh.score, [&](int j, float v) { stage[j] = v; });
+      snapkv_unit<D, NT>(p, rd, lh, sm_ids, sh.score, [&](int j, float v) { stage[j] = v; });
   } else {
-    knorm_unit<D>(p, rd, lh, [&](int j, float v) { stage[j] = v; });
+    knorm_unit<D>(p, rd, lh, sm_ids, [&](int j, float v) { stage[j] = v; });
   }
   __syncthreads();
   select_unit<true>(p, rd, lh, keys, sh.select);
   __syncthreads();  // the kept list (global memory, this workgroup's own) is complete
-  gather_unit<D>(p, rd, lh);
+  gather_unit<D>(p, rd, lh, sm_ids);
 }
 
 // ---------------------------------------------------------------------------
