@@ -21,6 +21,15 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 
+# HBM bytes per launch of the dominant kernel, measured with rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE and scaled by what the same counters read for a plain
+# 4 GiB copy (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000 on this chip); summary and
+# commands in profiles/fused_unit_kernel_config2_config3_config4.md.
+MEASURED_TRAFFIC_BYTES = {
+    ("config3_batched_mixed", "fused_unit"): 25.95e9,
+    ("config4_multi_image", "fused_unit"): 214.57e9,
+}
+
 
 def cpu_baseline(dw, seconds=15.0, seed=0):
     """The CPU oracle, as it stands, timed on a bounded random sample of
@@ -180,7 +189,8 @@ def main():
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": dom_gbps / HBM_PEAK_GBPS,
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, dom)) if args.score_mode == "auto"
+            else None,
         },
     }
     if args.cpu_seconds > 0:
