@@ -166,7 +166,8 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f16 in, f32 accumulate/softmax",
+        "dtype": "f16",
+        "dtype_note": "fp16 K/V/Q and MFMA inputs, fp32 accumulation, softmax and scores",
         "data": "synthetic",
         "config": {
             "workload": wl.name,

@@ -325,6 +325,7 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
     d.old_off = total_old;
     d.new_off = total_new;
     d.score_off = (int64_t)score_off;
+    d.raw_off = 0;
     d.kept_off = (int64_t)kept_off;
     d.q_off = (int64_t)((size_t)r * n_lh * (size_t)std::max(window, 0) * p->head_dim);
     total_old += d.n_old;
@@ -379,7 +380,6 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
   }
 
   // ---- scratch and descriptors --------------------------------------------
-  if ((rc = grow(&p->raw_scores, &p->raw_cap, score_off)) != FC_OK) return rc;
   if (!dev_kept_out && (rc = grow(&p->kept, &p->kept_cap, kept_off)) != FC_OK) return rc;
   if ((rc = grow(&p->ids, &p->ids_cap, (size_t)total_old + total_new)) != FC_OK) return rc;
   const size_t desc_bytes = round_up((size_t)n_comp * sizeof(ReqDesc), 16);
@@ -411,6 +411,7 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
                    [&](int a, int b) { return descs[a].seq_len > descs[b].seq_len; });
   const bool allow_fused = p->score_mode == FC_SCORE_AUTO;
   bool fused_has_snap = false;
+  size_t raw_need = 0;
   for (int di : sorted) {
     const ReqDesc& d = descs[di];
     const bool snap = d.method == FC_METHOD_SNAPKV;
@@ -419,6 +420,9 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
       li = LIST_FUSED;
       fused_has_snap |= snap;
     } else {
+      // scores of these units travel through the library's scratch
+      reinterpret_cast<ReqDesc*>(p->host_meta)[di].raw_off = (int64_t)raw_need;
+      raw_need += n_lh * (size_t)d.seq_len;
       li = snap ? LIST_SNAP : LIST_KNORM;
       lists[LIST_ALL][n_list[LIST_ALL]++] = di;
       max_len_list[LIST_ALL] = std::max(max_len_list[LIST_ALL], d.seq_len);
@@ -427,6 +431,7 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
     max_len_list[li] = std::max(max_len_list[li], d.seq_len);
   }
   const int ns = n_list[LIST_SNAP], nk = n_list[LIST_KNORM];
+  if ((rc = grow(&p->raw_scores, &p->raw_cap, raw_need)) != FC_OK) return rc;
   FC_HIP(hipMemcpyAsync(p->dev_meta, p->host_meta, meta_bytes, hipMemcpyHostToDevice, stream));
   FC_HIP(hipEventRecord(p->meta_event, stream));
   p->meta_pending = true;

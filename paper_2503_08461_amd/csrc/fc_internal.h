@@ -18,7 +18,8 @@ struct ReqDesc {
   int32_t n_new;      // ceil(B_r / 16)
   int32_t old_off;    // start of this request in the saved old-id list
   int32_t new_off;    // start of this request in the new-id list
-  int64_t score_off;  // start of [layer][head][L_r] in the score buffers
+  int64_t score_off;  // start of [layer][head][L_r] in the caller's packed scores_out
+  int64_t raw_off;    // same in the library's un-pooled score scratch (separate kernels only)
   int64_t kept_off;   // start of [layer][head][B_r] in the kept buffer
   int64_t q_off;      // start of [layer][head][window][d] in q_window
   // one-pass SnapKV score kernel: workgroups that share one (layer, head)
@@ -51,7 +52,7 @@ struct BatchParams {
   const _Float16* q_window;
   int32_t window, pool_kernel;
   float scale_log2e;           // scale * log2(e)
-  float* raw_scores;           // un-pooled scores, packed like scores_out
+  float* raw_scores;           // un-pooled scores of the units that take the separate kernels
   float* scores_out;           // nullable
   int32_t* kept;               // kept indices, packed
   // one-pass SnapKV score kernel (persistent, co-resident grid)

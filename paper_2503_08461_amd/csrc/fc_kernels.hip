@@ -236,7 +236,7 @@ __global__ __launch_bounds__(kThreads) void snapkv_score_kernel(BatchParams p) {
   const int slot = blockIdx.x / n_lh;
   const int lh = blockIdx.x - slot * n_lh;
   const ReqDesc rd = p.descs[p.order_snap[slot]];
-  float* raw = p.raw_scores + rd.score_off + (size_t)lh * rd.seq_len;
+  float* raw = p.raw_scores + rd.raw_off + (size_t)lh * rd.seq_len;
   snapkv_unit<D, NT>(p, rd, lh, p.old_ids + rd.old_off, sh, [&](int j, float v) { raw[j] = v; });
 }
 
@@ -291,7 +291,7 @@ __global__ __launch_bounds__(kThreads) void knorm_score_kernel(BatchParams p) {
   const int slot = blockIdx.x / n_lh;
   const int lh = blockIdx.x - slot * n_lh;
   const ReqDesc rd = p.descs[p.order_knorm[slot]];
-  float* raw = p.raw_scores + rd.score_off + (size_t)lh * rd.seq_len;
+  float* raw = p.raw_scores + rd.raw_off + (size_t)lh * rd.seq_len;
   knorm_unit<D>(p, rd, lh, p.old_ids + rd.old_off, [&](int j, float v) { raw[j] = v; });
 }
 
@@ -413,7 +413,7 @@ __device__ __forceinline__ void select_unit(const BatchParams& p, const ReqDesc&
   const bool snap = rd.method == 1 /* FC_METHOD_SNAPKV */;
   const int n_sel = snap ? L - p.window : L;  // tokens that compete
   const int k_sel = snap ? B - p.window : B;  // how many of them are kept
-  const float* raw = p.raw_scores + rd.score_off + (size_t)lh * L;
+  const float* raw = p.raw_scores + rd.raw_off + (size_t)lh * L;
   float* out = p.scores_out ? p.scores_out + rd.score_off + (size_t)lh * L : nullptr;
   int32_t* kept = p.kept + rd.kept_off + (size_t)lh * B;
 

@@ -213,7 +213,7 @@ __global__ __launch_bounds__(kThreads, 2) void snapkv_score_team_kernel(BatchPar
       float mfin[NT];
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) mfin[nt] = sm_final[nt * 16 + c16];
-      float* raw = p.raw_scores + rd.score_off + (size_t)lh * L;
+      float* raw = p.raw_scores + rd.raw_off + (size_t)lh * L;
 #pragma unroll
       for (int k = 0; k < NBW; ++k) {
         const int b = b0 + k;

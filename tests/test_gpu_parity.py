@@ -280,3 +280,29 @@ def test_select_with_massive_ties_and_clustered_scores():
         s.compress_and_compare()
     finally:
         s.close()
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_workloads(seed):
+    """Seeded random batches: ragged lengths (1..3000), any window 1..64, both
+    head sizes, mixed methods and pass-through requests, random budgets and
+    pool kernels, all three schedulings."""
+    rng = np.random.Generator(np.random.PCG64(9000 + seed))
+    n_req = int(rng.integers(1, 6))
+    W = int(rng.integers(1, 65))
+    d = int(rng.choice([64, 128]))
+    lens, methods, budgets = [], [], []
+    for _ in range(n_req):
+        m = int(rng.choice([fo.METHOD_SNAPKV, fo.METHOD_KNORM, fo.METHOD_NONE], p=[0.5, 0.4, 0.1]))
+        lo = W if m == fo.METHOD_SNAPKV else 1
+        L = int(rng.integers(lo, 3001)) if rng.random() < 0.7 else int(rng.integers(lo, lo + 40))
+        b_lo = W if m == fo.METHOD_SNAPKV else 1
+        B = int(rng.integers(b_lo, L + 1))
+        lens.append(L); methods.append(m); budgets.append(B)
+    wl = _custom(lens, budgets, methods, W=W, d=d, n_heads=int(rng.integers(1, 4)),
+                 n_layers=int(rng.integers(1, 3)), seed=100 + seed)
+    mode = int(rng.integers(0, 3))
+    kernel = int(rng.choice([1, 3, 5, 7, 9, 15]))
+    print("seed", seed, "lens", lens, "budgets", budgets, "methods", methods, "W", W, "d", d,
+          "mode", mode, "pool", kernel, flush=True)
+    _run(wl, mode, pool_kernel=kernel)
