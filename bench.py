@@ -84,7 +84,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config4", choices=["config2", "config3", "config4"])
+    ap.add_argument("--workload", default="config4",
+                    choices=["config2", "config3", "config4", "config4_streaming"],
+                    help="config4_streaming: the config-4 batch with every request using the "
+                         "score-free sinks + recent rule (gather and pool work only)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="CPU time budget of the oracle baseline (0 = skip)")
     ap.add_argument("--score-mode", default="auto", choices=["auto", "two_pass", "one_pass"],
@@ -117,7 +120,10 @@ def main():
                           "bytes_written_per_copy": n, "copies": 5}), flush=True)
         return
     fc.load_library()
-    wl = synth.make_workload(int(args.workload[-1]))
+    wl = synth.make_workload(int(args.workload[6]))
+    if args.workload.endswith("_streaming"):
+        wl.methods[:] = synth.METHOD_STREAMING
+        wl.name += "_streaming"
     need = wl.pool_bytes() + (8 << 30)
     total = torch.cuda.get_device_properties(0).total_memory
     if need > total:

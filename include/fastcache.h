@@ -32,7 +32,7 @@ extern "C" {
 typedef struct fc_pool fc_pool; /* opaque, owned by the library */
 
 enum { FC_OK = 0, FC_EINVAL = -1, FC_ENOMEM = -2, FC_EDEVICE = -3 };
-enum { FC_METHOD_NONE = 0, FC_METHOD_SNAPKV = 1, FC_METHOD_KNORM = 2 };
+enum { FC_METHOD_NONE = 0, FC_METHOD_SNAPKV = 1, FC_METHOD_KNORM = 2, FC_METHOD_STREAMING = 3 };
 enum { FC_DTYPE_F16 = 0 };
 
 #define FC_BLOCK_SIZE 16      /* tokens per pool block (the only supported value) */
@@ -114,6 +114,10 @@ int fc_pool_import_state_dev(fc_pool* pool, const int32_t* dev_stack, int top, v
  *          over the window queries; max-pool (odd pool_kernel, stride 1, same
  *          length) over the keys before the window; window tokens score +inf;
  *        FC_METHOD_KNORM: score = -||k||_2;
+ *        FC_METHOD_STREAMING (StreamingLLM-style baseline of the paper's
+ *          evaluation): nothing is read; the first min(n_sink, budget_r)
+ *          tokens and the last budget_r - sinks tokens score +inf, the rest 0
+ *          (n_sink: fc_set_streaming_sinks, default 4);
  *   2. keep the budget_r best scores (ties to the lower index), in ascending
  *      token order;
  *   3. pop ceil(budget_r/16) new blocks (all requests' new blocks are popped
@@ -148,6 +152,10 @@ int fc_compress_batch(fc_pool* pool, int32_t* dev_block_tables, int max_blocks_p
                       const int32_t* host_method, const int32_t* host_budget, int n_req,
                       int pool_kernel, float scale, float* dev_scores_out,
                       int32_t* dev_kept_out, void* stream);
+
+/* Number of leading "attention sink" tokens that FC_METHOD_STREAMING requests
+ * keep (>= 0, default 4). */
+int fc_set_streaming_sinks(fc_pool* pool, int n_sink);
 
 /*
  * How fc_compress_batch schedules the scoring.

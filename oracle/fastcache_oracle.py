@@ -28,6 +28,11 @@ but prints none of their formulas; the readings taken here are:
     score +inf so they are always kept;
   * key-norm score: minus the Euclidean norm of the key, so that keeping the
     best scores keeps the lowest norms; no pooling, no forced tokens;
+  * streaming (StreamingLLM-style, one of the baselines the paper runs): no
+    scoring; the first min(n_sink, budget) tokens ("attention sinks") and the
+    most recent budget - sinks tokens are kept.  As a score: +inf on those
+    tokens and 0 elsewhere, which the common selection rule turns into exactly
+    that kept set;
   * selection: sort by (score descending, index ascending), keep the first
     `budget`, emit them in ascending index order;
   * pool: a LIFO stack of free block ids; a fresh pool holds
@@ -42,6 +47,7 @@ import numpy as np
 METHOD_NONE = 0
 METHOD_SNAPKV = 1
 METHOD_KNORM = 2
+METHOD_STREAMING = 3
 
 
 # --------------------------------------------------------------------------
@@ -101,9 +107,23 @@ def knorm_scores(keys):
     return -np.sqrt((keys * keys).sum(axis=1))
 
 
+def streaming_scores(n_tokens, budget, n_sink):
+    """Sinks-plus-recent rule written as a score: +inf on the first
+    min(n_sink, budget) tokens and on the last budget - sinks tokens, else 0."""
+    sinks = min(int(n_sink), int(budget))
+    recent = int(budget) - sinks
+    s = np.zeros(n_tokens, dtype=np.float64)
+    s[:sinks] = np.inf
+    if recent > 0:
+        s[n_tokens - recent:] = np.inf
+    return s
+
+
 def unit_scores(kv_pool, layer, table_row, head, n_tokens, method,
-                q_window_unit=None, scale=None, pool_kernel=7):
+                q_window_unit=None, scale=None, pool_kernel=7, budget=None, n_sink=4):
     """Scores of one (request, layer, head) unit read through its block table."""
+    if method == METHOD_STREAMING:
+        return streaming_scores(n_tokens, budget, n_sink)
     keys = fetch_rows(kv_pool, layer, table_row, 0, head, n_tokens)
     if method == METHOD_SNAPKV:
         d = keys.shape[1]
@@ -186,7 +206,7 @@ def validate_batch(stack, block_tables, seq_lens, window, method, budget,
         m, L, B = int(method[r]), int(seq_lens[r]), int(budget[r])
         if m == METHOD_NONE:
             continue
-        if m not in (METHOD_SNAPKV, METHOD_KNORM):
+        if m not in (METHOD_SNAPKV, METHOD_KNORM, METHOD_STREAMING):
             return "EINVAL"
         if B < 1 or B > L:
             return "EINVAL"
@@ -201,7 +221,7 @@ def validate_batch(stack, block_tables, seq_lens, window, method, budget,
 
 
 def compress_batch(kv_pool, stack, block_tables, seq_lens, q_window, window,
-                   method, budget, pool_kernel=7, scale=None, kept_override=None):
+                   method, budget, pool_kernel=7, scale=None, kept_override=None, n_sink=4):
     """The whole stage for one batch, in place.
 
     kv_pool      float16 [n_layers][n_blocks][2][n_heads][block_size][d]
@@ -211,6 +231,7 @@ def compress_batch(kv_pool, stack, block_tables, seq_lens, q_window, window,
     q_window     float16 [n_req][n_layers][n_heads][window][d] (may be None if
                  no request uses SnapKV)
     method, budget  int arrays [n_req]
+    n_sink       attention sinks kept by METHOD_STREAMING requests
     kept_override   optional list (per request) of int arrays
                  [n_layers][n_heads][B_r]: use these kept indices instead of
                  the oracle's own selection (used to check the copy step on
@@ -243,7 +264,7 @@ def compress_batch(kv_pool, stack, block_tables, seq_lens, q_window, window,
             for h in range(n_heads):
                 qw = q_window[r, l, h] if m == METHOD_SNAPKV else None
                 s = unit_scores(kv_pool, l, block_tables[r], h, L, m, qw, scale,
-                                pool_kernel)
+                                pool_kernel, B, n_sink)
                 scores[r][l, h] = s
                 if kept_override is not None:
                     kept[r][l, h] = kept_override[r][l, h]

@@ -74,6 +74,7 @@ struct fc_pool {
   size_t team_stats_cap = 0;
   int32_t* error_flag = nullptr;  // device, one int, zero unless a bounded wait ran out
   int score_mode = FC_SCORE_AUTO;
+  int n_sink = 4;
   int team_grid[FC_MAX_WINDOW / 16 + 1] = {};  // co-resident grid per query-tile count, -1 = none
 
   bool profiling = false;
@@ -232,6 +233,13 @@ int fc_pool_import_state(fc_pool* p, const int32_t* host_stack, int top) {
   return FC_OK;
 }
 
+int fc_set_streaming_sinks(fc_pool* p, int n_sink) {
+  if (!p) return fail(FC_EINVAL, "pool is NULL");
+  if (n_sink < 0) return fail(FC_EINVAL, "n_sink < 0");
+  p->n_sink = n_sink;
+  return FC_OK;
+}
+
 int fc_set_score_mode(fc_pool* p, int mode) {
   if (!p) return fail(FC_EINVAL, "pool is NULL");
   if (mode != FC_SCORE_AUTO && mode != FC_SCORE_TWO_PASS && mode != FC_SCORE_ONE_PASS)
@@ -299,7 +307,7 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
     const int m = host_method[r];
     if (m == FC_METHOD_NONE) continue;
     const int L = host_seq_lens[r], B = host_budget[r];
-    if (m != FC_METHOD_SNAPKV && m != FC_METHOD_KNORM)
+    if (m != FC_METHOD_SNAPKV && m != FC_METHOD_KNORM && m != FC_METHOD_STREAMING)
       return fail(FC_EINVAL, "request %d: unknown method %d", r, m);
     if (L < 1 || L > FC_MAX_SEQ_LEN)
       return fail(FC_EINVAL, "request %d: length %d outside 1..%d", r, L, FC_MAX_SEQ_LEN);
@@ -392,8 +400,8 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
     p->meta_pending = false;
   }
   memcpy(p->host_meta, descs.data(), (size_t)n_comp * sizeof(ReqDesc));
-  // Work lists (descriptor indices, longest first so that the tail of each
-  // launch is made of short units).  Heads short enough for the fused kernel
+  // Work lists (descriptor indices, heaviest first so that the tail of each
+  // launch is made of light units).  Heads short enough for the fused kernel
   // (score -> select -> gather in one workgroup) share one list; the rest go
   // through the separate kernels, listed per method.
   enum { LIST_FUSED = 0, LIST_SNAP, LIST_KNORM, LIST_ALL, N_LISTS };
@@ -407,8 +415,14 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
   }
   std::vector<int> sorted(n_comp);
   std::iota(sorted.begin(), sorted.end(), 0);
+  // heaviest first: bytes a unit moves (K once or twice, kept K/V read and written)
+  auto weight = [&](int i) {
+    const ReqDesc& d = descs[i];
+    const int passes = d.method == FC_METHOD_SNAPKV ? 2 : d.method == FC_METHOD_KNORM ? 1 : 0;
+    return (int64_t)d.seq_len * passes + (int64_t)d.budget * 4;
+  };
   std::stable_sort(sorted.begin(), sorted.end(),
-                   [&](int a, int b) { return descs[a].seq_len > descs[b].seq_len; });
+                   [&](int a, int b) { return weight(a) > weight(b); });
   const bool allow_fused = p->score_mode == FC_SCORE_AUTO;
   bool fused_has_snap = false;
   size_t raw_need = 0;
@@ -416,6 +430,11 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
     const ReqDesc& d = descs[di];
     const bool snap = d.method == FC_METHOD_SNAPKV;
     int li;
+    if (d.method == FC_METHOD_STREAMING) {
+      // no score, no LDS: always the fused kernel, whatever the length
+      lists[LIST_FUSED][n_list[LIST_FUSED]++] = di;
+      continue;
+    }
     if (allow_fused && d.seq_len <= kFusedMaxLen) {
       li = LIST_FUSED;
       fused_has_snap |= snap;
@@ -464,6 +483,7 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
   bp.q_window = static_cast<const _Float16*>(dev_q_window);
   bp.window = window;
   bp.pool_kernel = pool_kernel;
+  bp.n_sink = p->n_sink;
   const float sc = (scale > 0.f) ? scale : 1.0f / sqrtf((float)p->head_dim);
   bp.scale_log2e = sc * 1.44269504088896340736f;
   bp.raw_scores = p->raw_scores;

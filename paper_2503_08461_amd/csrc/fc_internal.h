@@ -51,6 +51,7 @@ struct BatchParams {
   int32_t* new_ids;            // [total_new]
   const _Float16* q_window;
   int32_t window, pool_kernel;
+  int32_t n_sink;              // leading tokens kept by streaming requests
   float scale_log2e;           // scale * log2(e)
   float* raw_scores;           // un-pooled scores of the units that take the separate kernels
   float* scores_out;           // nullable

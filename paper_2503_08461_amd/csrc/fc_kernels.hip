@@ -589,6 +589,23 @@ __global__ __launch_bounds__(kThreads) void select_kernel(BatchParams p) {
   select_unit<false>(p, rd, lh, keys, sh);
 }
 
+// Streaming requests need no score: the first min(n_sink, budget) tokens and
+// the most recent budget - sinks tokens are kept.
+__device__ __forceinline__ void streaming_unit(const BatchParams& p, const ReqDesc& rd, int lh) {
+  const int L = rd.seq_len;
+  const int B = rd.budget;
+  const int sinks = min(p.n_sink, B);
+  const int first_recent = L - (B - sinks);
+  int32_t* kept = p.kept + rd.kept_off + (size_t)lh * B;
+  for (int t = threadIdx.x; t < B; t += kThreads)
+    kept[t] = (t < sinks) ? t : first_recent + (t - sinks);
+  if (p.scores_out) {
+    float* out = p.scores_out + rd.score_off + (size_t)lh * L;
+    for (int j = threadIdx.x; j < L; j += kThreads)
+      out[j] = (j < sinks || j >= first_recent) ? INFINITY : 0.f;
+  }
+}
+
 // ---------------------------------------------------------------------------
 // gather / compact
 // ---------------------------------------------------------------------------
@@ -682,21 +699,27 @@ __global__ __launch_bounds__(kThreads) void fused_unit_kernel(BatchParams p) {
   float* stage = reinterpret_cast<float*>(keys);
   // the request's block ids, read once per workgroup (every later use is an LDS read)
   __shared__ int32_t sm_ids[kFusedMaxLen / 16];
-  for (int i = threadIdx.x; i < rd.n_old; i += kThreads)
-    sm_ids[i] = clamp_block(p.old_ids[rd.old_off + i], p.n_blocks);
+  const bool ids_in_lds = rd.n_old <= kFusedMaxLen / 16;  // streaming units may be longer
+  if (ids_in_lds)
+    for (int i = threadIdx.x; i < rd.n_old; i += kThreads)
+      sm_ids[i] = clamp_block(p.old_ids[rd.old_off + i], p.n_blocks);
   __syncthreads();
-  bool snap = false;
-  if constexpr (NT > 0) snap = rd.method == 1 /* FC_METHOD_SNAPKV */;  // uniform per workgroup
-  if (snap) {
-    if constexpr (NT > 0)
-      snapkv_unit<D, NT>(p, rd, lh, sm_ids, sh.score, [&](int j, float v) { stage[j] = v; });
+  if (rd.method == 3 /* FC_METHOD_STREAMING */) {  // uniform per workgroup
+    streaming_unit(p, rd, lh);
   } else {
-    knorm_unit<D>(p, rd, lh, sm_ids, [&](int j, float v) { stage[j] = v; });
+    bool snap = false;
+    if constexpr (NT > 0) snap = rd.method == 1 /* FC_METHOD_SNAPKV */;
+    if (snap) {
+      if constexpr (NT > 0)
+        snapkv_unit<D, NT>(p, rd, lh, sm_ids, sh.score, [&](int j, float v) { stage[j] = v; });
+    } else {
+      knorm_unit<D>(p, rd, lh, sm_ids, [&](int j, float v) { stage[j] = v; });
+    }
+    __syncthreads();
+    select_unit<true>(p, rd, lh, keys, sh.select);
   }
-  __syncthreads();
-  select_unit<true>(p, rd, lh, keys, sh.select);
   __syncthreads();  // the kept list (global memory, this workgroup's own) is complete
-  gather_unit<D>(p, rd, lh, sm_ids);
+  gather_unit<D>(p, rd, lh, ids_in_lds ? sm_ids : p.old_ids + rd.old_off);
 }
 
 // ---------------------------------------------------------------------------

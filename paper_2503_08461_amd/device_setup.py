@@ -60,13 +60,15 @@ class DeviceWorkload:
     # ---- accounting (algorithmic bytes, stated per token per (layer, head)) ----
 
     def algorithmic_bytes(self):
-        """Whole path: read K once to score (2*d bytes per token-head), re-read
-        and write the kept K and V rows (2 * 2 * 2*d bytes per kept token-head)."""
+        """Whole path: read K once to score (2*d bytes per token-head; nothing
+        for streaming requests, which are not scored), re-read and write the
+        kept K and V rows (2 * 2 * 2*d bytes per kept token-head)."""
         wl = self.wl
         n_lh = wl.n_layers * wl.n_heads
         row = 2 * wl.head_dim
         comp = wl.methods != synth.METHOD_NONE
-        tokens = int(wl.seq_lens[comp].astype(np.int64).sum())
+        scored = comp & (wl.methods != synth.METHOD_STREAMING)
+        tokens = int(wl.seq_lens[scored].astype(np.int64).sum())
         kept = int(wl.budgets[comp].astype(np.int64).sum())
         return n_lh * (tokens * row + kept * 4 * row)
 
@@ -82,11 +84,13 @@ class DeviceWorkload:
         B = wl.budgets.astype(np.int64)
         snap = wl.methods == synth.METHOD_SNAPKV
         kn = wl.methods == synth.METHOD_KNORM
+        stream = wl.methods == synth.METHOD_STREAMING
         short = wl.seq_lens <= fused_max_len
         long_ = ~short
         return {
             "fused_unit": n_lh * int((L[(snap | kn) & short] * row
-                                      + B[(snap | kn) & short] * 4 * row).sum()),
+                                      + B[(snap | kn) & short] * 4 * row).sum()
+                                     + (B[stream] * 4 * row).sum()),
             "snapkv_score": n_lh * int(L[snap & long_].sum()) * row,
             "knorm_score": n_lh * int(L[kn & long_].sum()) * row,
             "gather": n_lh * int(B[(snap | kn) & long_].sum()) * 4 * row,

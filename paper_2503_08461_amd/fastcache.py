@@ -12,7 +12,7 @@ import os
 import numpy as np
 
 FC_OK, FC_EINVAL, FC_ENOMEM, FC_EDEVICE = 0, -1, -2, -3
-FC_METHOD_NONE, FC_METHOD_SNAPKV, FC_METHOD_KNORM = 0, 1, 2
+FC_METHOD_NONE, FC_METHOD_SNAPKV, FC_METHOD_KNORM, FC_METHOD_STREAMING = 0, 1, 2, 3
 FC_DTYPE_F16 = 0
 FC_BLOCK_SIZE = 16
 FC_N_KERNELS = 7
@@ -24,7 +24,7 @@ EXPORTS = [
     "fc_pool_create", "fc_pool_destroy", "fc_pool_alloc", "fc_pool_free",
     "fc_pool_num_free", "fc_pool_export_state", "fc_pool_import_state",
     "fc_pool_import_state_dev",
-    "fc_compress_batch", "fc_set_score_mode", "fc_set_profiling", "fc_get_kernel_times",
+    "fc_compress_batch", "fc_set_streaming_sinks", "fc_set_score_mode", "fc_set_profiling", "fc_get_kernel_times",
     "fc_kernel_name", "fc_last_error",
 ]
 
@@ -73,6 +73,7 @@ def load_library():
     lib.fc_compress_batch.argtypes = [vp, vp, i, i32p, vp, i, i32p, i32p, i, i,
                                       ctypes.c_float, vp, vp, vp]
     lib.fc_set_score_mode.argtypes = [vp, i]
+    lib.fc_set_streaming_sinks.argtypes = [vp, i]
     lib.fc_set_profiling.argtypes = [vp, i]
     lib.fc_get_kernel_times.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
     lib.fc_kernel_name.argtypes = [i]
@@ -224,6 +225,10 @@ def fc_compress_batch(pool, block_tables, seq_lens, q_window, window, method, bu
         _host_i32(method), _host_i32(budget), n_req, int(pool_kernel), float(scale),
         _dev_ptr(scores_out, torch.float32), _dev_ptr(kept_out, torch.int32),
         _stream_ptr(stream)))
+
+
+def fc_set_streaming_sinks(pool, n_sink):
+    _check(load_library().fc_set_streaming_sinks(pool.ptr, int(n_sink)))
 
 
 def fc_set_score_mode(pool, mode):

@@ -17,6 +17,7 @@ import numpy as np
 METHOD_NONE = 0
 METHOD_SNAPKV = 1
 METHOD_KNORM = 2
+METHOD_STREAMING = 3
 
 BLOCK_SIZE = 16
 

@@ -101,7 +101,7 @@ class SideBySide:
         assert (stack_g[:top_g] == self.stack.stack[:top_g]).all(), "free stacks differ"
 
     def compress_and_compare(self, methods=None, budgets=None, window=None, pool_kernel=None,
-                             scale=0.0):
+                             scale=0.0, n_sink=4):
         """One fc_compress_batch on both sides + full comparison.  Returns stats."""
         torch, fc, wl = self.torch, self.fc, self.wl
         methods = wl.methods if methods is None else methods
@@ -116,6 +116,7 @@ class SideBySide:
         scores_dev = torch.full((max(n_scores, 1),), float("nan"), dtype=torch.float32,
                                 device=self.dev)
         kept_dev = torch.full((max(n_kept, 1),), -7, dtype=torch.int32, device=self.dev)
+        fc.fc_set_streaming_sinks(self.pool, n_sink)
         fc.fc_compress_batch(self.pool, self.bt_dev, self.lens_g, self.q_dev, window,
                              methods, budgets, pool_kernel, scale, scores_dev, kept_dev)
         torch.cuda.synchronize()
@@ -128,7 +129,7 @@ class SideBySide:
         bt_a, lens_a = self.bt_host.copy(), self.lens_o.copy()
         status, scores_o, kept_o = fo.compress_batch(
             kv_a, st_a, bt_a, lens_a, self.q_host, window, methods, budgets, pool_kernel,
-            scale if scale > 0 else None)
+            scale if scale > 0 else None, n_sink=n_sink)
         assert status is None, status
 
         # ... compared unit by unit
@@ -158,7 +159,7 @@ class SideBySide:
         status, _, _ = fo.compress_batch(
             self.kv_host, self.stack, self.bt_host, self.lens_o, self.q_host, window,
             methods, budgets, pool_kernel, scale if scale > 0 else None,
-            kept_override=kept_g_lists)
+            kept_override=kept_g_lists, n_sink=n_sink)
         assert status is None
         self.compare_state()
         return stats

@@ -306,3 +306,19 @@ def test_random_workloads(seed):
     print("seed", seed, "lens", lens, "budgets", budgets, "methods", methods, "W", W, "d", d,
           "mode", mode, "pool", kernel, flush=True)
     _run(wl, mode, pool_kernel=kernel)
+
+
+@pytest.mark.parametrize("n_sink", [0, 4, 9])
+def test_streaming_method_mixed_with_scored_methods(n_sink, score_mode):
+    """StreamingLLM-style requests (sinks + most recent, nothing scored) in one
+    batch with SnapKV, key-norm and pass-through requests, including a streaming
+    request longer than the fused kernel's score capacity."""
+    M = fo.METHOD_STREAMING
+    wl = _custom([300, 9000, 77, 640, 50, 16], [60, 700, 77, 160, 3, 1],
+                 [M, M, M, fo.METHOD_SNAPKV, fo.METHOD_KNORM, M], W=16, d=128, n_heads=2)
+    s = _sbs(wl, score_mode=score_mode)
+    try:
+        st = s.compress_and_compare(n_sink=n_sink)
+        assert st["units_kept_identical"] == st["units"]
+    finally:
+        s.close()

@@ -350,3 +350,36 @@ def test_errors_leave_state_untouched():
     assert fo.compress_batch(kv, st, bt, lens, q, 2, [fo.METHOD_SNAPKV], [4], 4)[0] == "EINVAL"
     assert unchanged()
     assert fo.compress_batch(kv, st, bt, lens, q, 2, [fo.METHOD_SNAPKV], [4], 7)[0] is None
+
+
+# ---------------------------------------------------------------- streaming (sinks + recent)
+
+@pytest.mark.parametrize("L,B,n_sink", [(10, 5, 2), (10, 10, 4), (10, 1, 4), (10, 4, 4), (10, 3, 0),
+                                         (37, 9, 4), (16, 16, 0)])
+def test_streaming_keeps_sinks_and_most_recent(L, B, n_sink):
+    s = fo.streaming_scores(L, B, n_sink)
+    kept = fo.select_topk(s, B).tolist()
+    sinks = min(n_sink, B)
+    assert kept == list(range(sinks)) + list(range(L - (B - sinks), L))
+    assert np.isposinf(s[kept]).all() and (np.delete(s, kept) == 0).all()
+
+
+def test_streaming_through_compress_batch_reads_no_scores():
+    rng = np.random.default_rng(11)
+    kv = _random_pool(rng, 1, 16, 2, 4, 4)
+    kv[:, :, 0] = np.nan            # keys are never looked at
+    st = fo.FreeStack(16)
+    bt = np.full((1, 5), -1, dtype=np.int32)
+    bt[0, :5] = st.alloc(5)
+    lens = np.array([18], dtype=np.int32)
+    kv0, bt0 = kv.copy(), bt.copy()
+    status, scores, kept = fo.compress_batch(kv, st, bt, lens, None, 0, [fo.METHOD_STREAMING], [7],
+                                             n_sink=3)
+    assert status is None and int(lens[0]) == 7
+    want = [0, 1, 2, 14, 15, 16, 17]
+    for h in range(2):
+        assert kept[0][0, h].tolist() == want
+        for t, idx in enumerate(want):
+            new = kv[0, bt[0, t // 4], 1, h, t % 4]
+            old = kv0[0, bt0[0, idx // 4], 1, h, idx % 4]
+            assert (new == old).all()
