@@ -153,6 +153,20 @@ int fc_compress_batch(fc_pool* pool, int32_t* dev_block_tables, int max_blocks_p
                       int pool_kernel, float scale, float* dev_scores_out,
                       int32_t* dev_kept_out, void* stream);
 
+/*
+ * Where fc_compress_batch puts the kept rows.
+ *   FC_COMPACT_FRESH (default): into freshly popped blocks, as described at
+ *     fc_compress_batch (needs sum ceil(budget_r/16) free blocks).
+ *   FC_COMPACT_IN_PLACE: into the request's own first ceil(budget_r/16) blocks
+ *     (kept row t moves to slot t; rows are moved in ascending chunks so that
+ *     no row is overwritten before it has been read).  No block is popped,
+ *     FC_ENOMEM cannot occur, the table row keeps its first ceil(budget_r/16)
+ *     ids and the remaining ids are pushed on the free stack (batch order,
+ *     table order).  For pools that are nearly full.
+ */
+enum { FC_COMPACT_FRESH = 0, FC_COMPACT_IN_PLACE = 1 };
+int fc_set_compaction_mode(fc_pool* pool, int mode);
+
 /* Number of leading "attention sink" tokens that FC_METHOD_STREAMING requests
  * keep (>= 0, default 4). */
 int fc_set_streaming_sinks(fc_pool* pool, int n_sink);

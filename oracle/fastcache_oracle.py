@@ -197,7 +197,7 @@ def copy_rows(kv_pool, layer, head, old_row, new_row, kept):
 
 
 def validate_batch(stack, block_tables, seq_lens, window, method, budget,
-                   pool_kernel, block_size):
+                   pool_kernel, block_size, in_place=False):
     """Returns None if the batch is acceptable, else 'EINVAL' / 'ENOMEM'."""
     if pool_kernel < 1 or pool_kernel % 2 == 0:
         return "EINVAL"
@@ -215,13 +215,14 @@ def validate_batch(stack, block_tables, seq_lens, window, method, budget,
         if blocks_for(L, block_size) > block_tables.shape[1]:
             return "EINVAL"
         need += blocks_for(B, block_size)
-    if need > stack.num_free():
+    if need > stack.num_free() and not in_place:
         return "ENOMEM"
     return None
 
 
 def compress_batch(kv_pool, stack, block_tables, seq_lens, q_window, window,
-                   method, budget, pool_kernel=7, scale=None, kept_override=None, n_sink=4):
+                   method, budget, pool_kernel=7, scale=None, kept_override=None, n_sink=4,
+                   in_place=False):
     """The whole stage for one batch, in place.
 
     kv_pool      float16 [n_layers][n_blocks][2][n_heads][block_size][d]
@@ -232,6 +233,11 @@ def compress_batch(kv_pool, stack, block_tables, seq_lens, q_window, window,
                  no request uses SnapKV)
     method, budget  int arrays [n_req]
     n_sink       attention sinks kept by METHOD_STREAMING requests
+    in_place     compact inside the request's own blocks: the kept rows move to
+                 slots 0..B-1 of its first ceil(B/bs) blocks (in ascending
+                 order, which never overwrites a row still to be read because
+                 kept[t] >= t), no block is allocated and the remaining blocks
+                 are released
     kept_override   optional list (per request) of int arrays
                  [n_layers][n_heads][B_r]: use these kept indices instead of
                  the oracle's own selection (used to check the copy step on
@@ -244,7 +250,7 @@ def compress_batch(kv_pool, stack, block_tables, seq_lens, q_window, window,
     n_layers, _, _, n_heads, bs, d = kv_pool.shape
     n_req = len(seq_lens)
     status = validate_batch(stack, block_tables, seq_lens, window, method,
-                            budget, pool_kernel, bs)
+                            budget, pool_kernel, bs, in_place)
     if status is not None:
         return status, None, None
     if scale is None or scale <= 0:
@@ -278,7 +284,10 @@ def compress_batch(kv_pool, stack, block_tables, seq_lens, q_window, window,
         if int(method[r]) == METHOD_NONE:
             continue
         old_rows[r] = block_tables[r, :blocks_for(int(seq_lens[r]), bs)].copy()
-        new_rows[r] = stack.alloc(blocks_for(int(budget[r]), bs))
+        if in_place:
+            new_rows[r] = old_rows[r][:blocks_for(int(budget[r]), bs)].copy()
+        else:
+            new_rows[r] = stack.alloc(blocks_for(int(budget[r]), bs))
 
     # 3. copy kept rows old -> new
     for r in range(n_req):
@@ -292,7 +301,7 @@ def compress_batch(kv_pool, stack, block_tables, seq_lens, q_window, window,
     for r in range(n_req):
         if new_rows[r] is None:
             continue
-        stack.free(old_rows[r])
+        stack.free(old_rows[r][new_rows[r].shape[0]:] if in_place else old_rows[r])
         block_tables[r, :] = -1
         block_tables[r, :new_rows[r].shape[0]] = new_rows[r]
         seq_lens[r] = int(budget[r])

@@ -75,6 +75,7 @@ struct fc_pool {
   int32_t* error_flag = nullptr;  // device, one int, zero unless a bounded wait ran out
   int score_mode = FC_SCORE_AUTO;
   int n_sink = 4;
+  int compact_mode = FC_COMPACT_FRESH;
   int team_grid[FC_MAX_WINDOW / 16 + 1] = {};  // co-resident grid per query-tile count, -1 = none
 
   bool profiling = false;
@@ -233,6 +234,14 @@ int fc_pool_import_state(fc_pool* p, const int32_t* host_stack, int top) {
   return FC_OK;
 }
 
+int fc_set_compaction_mode(fc_pool* p, int mode) {
+  if (!p) return fail(FC_EINVAL, "pool is NULL");
+  if (mode != FC_COMPACT_FRESH && mode != FC_COMPACT_IN_PLACE)
+    return fail(FC_EINVAL, "unknown compaction mode %d", mode);
+  p->compact_mode = mode;
+  return FC_OK;
+}
+
 int fc_set_streaming_sinks(fc_pool* p, int n_sink) {
   if (!p) return fail(FC_EINVAL, "pool is NULL");
   if (n_sink < 0) return fail(FC_EINVAL, "n_sink < 0");
@@ -301,7 +310,8 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
   const size_t n_lh = (size_t)p->n_layers * p->n_heads;
   std::vector<ReqDesc> descs;
   descs.reserve(n_req);
-  int total_new = 0, total_old = 0, max_len = 0;
+  const bool in_place = p->compact_mode == FC_COMPACT_IN_PLACE;
+  int total_new = 0, total_old = 0, total_released = 0, max_len = 0;
   size_t score_off = 0, kept_off = 0;
   for (int r = 0; r < n_req; ++r) {
     const int m = host_method[r];
@@ -331,13 +341,14 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
       return fail(FC_EINVAL, "request %d: %d blocks exceed max_blocks_per_req %d", r, d.n_old,
                   max_blocks_per_req);
     d.old_off = total_old;
-    d.new_off = total_new;
+    d.new_off = in_place ? total_released : total_new;
     d.score_off = (int64_t)score_off;
     d.raw_off = 0;
     d.kept_off = (int64_t)kept_off;
     d.q_off = (int64_t)((size_t)r * n_lh * (size_t)std::max(window, 0) * p->head_dim);
     total_old += d.n_old;
-    total_new += d.n_new;
+    total_new += in_place ? 0 : d.n_new;
+    total_released += d.n_old - d.n_new;
     score_off += n_lh * (size_t)L;
     kept_off += n_lh * (size_t)B;
     max_len = std::max(max_len, L);
@@ -484,6 +495,7 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
   bp.window = window;
   bp.pool_kernel = pool_kernel;
   bp.n_sink = p->n_sink;
+  bp.in_place = in_place ? 1 : 0;
   const float sc = (scale > 0.f) ? scale : 1.0f / sqrtf((float)p->head_dim);
   bp.scale_log2e = sc * 1.44269504088896340736f;
   bp.raw_scores = p->raw_scores;
@@ -527,7 +539,7 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
   FC_HIP(run(K_RECLAIM, true, [&] { return launch_reclaim(bp, stream); }));
 
   // ---- host mirrors ------------------------------------------------------------
-  p->top = p->top - total_new + total_old;
+  p->top = in_place ? p->top + total_released : p->top - total_new + total_old;
   for (const ReqDesc& d : descs) host_seq_lens[d.table_row] = d.budget;
   return FC_OK;
 }

@@ -17,7 +17,8 @@ struct ReqDesc {
   int32_t n_old;      // ceil(L_r / 16)
   int32_t n_new;      // ceil(B_r / 16)
   int32_t old_off;    // start of this request in the saved old-id list
-  int32_t new_off;    // start of this request in the new-id list
+  int32_t new_off;    // start of this request in the new-id list (fresh blocks) or in
+                      // the run of released ids (in-place compaction)
   int64_t score_off;  // start of [layer][head][L_r] in the caller's packed scores_out
   int64_t raw_off;    // same in the library's un-pooled score scratch (separate kernels only)
   int64_t kept_off;   // start of [layer][head][B_r] in the kept buffer
@@ -52,6 +53,7 @@ struct BatchParams {
   const _Float16* q_window;
   int32_t window, pool_kernel;
   int32_t n_sink;              // leading tokens kept by streaming requests
+  int32_t in_place;            // 1: compact inside the request's own blocks
   float scale_log2e;           // scale * log2(e)
   float* raw_scores;           // un-pooled scores of the units that take the separate kernels
   float* scores_out;           // nullable

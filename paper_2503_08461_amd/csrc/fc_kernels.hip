@@ -39,18 +39,26 @@ __global__ __launch_bounds__(kThreads) void plan_alloc_kernel(BatchParams p) {
   const int32_t* row = p.block_tables + (size_t)rd.table_row * p.max_blocks;
   for (int i = threadIdx.x; i < rd.n_old; i += kThreads)
     p.old_ids[rd.old_off + i] = row[i];
-  for (int i = threadIdx.x; i < rd.n_new; i += kThreads)
-    p.new_ids[rd.new_off + i] = p.stack[p.top_before - 1 - rd.new_off - i];
+  if (!p.in_place)
+    for (int i = threadIdx.x; i < rd.n_new; i += kThreads)
+      p.new_ids[rd.new_off + i] = p.stack[p.top_before - 1 - rd.new_off - i];
 }
 
 // Zombie reclaim: pushes the pre-compression blocks (batch order, table
 // order) above the stack top left by plan_alloc and rewrites the table rows.
 __global__ __launch_bounds__(kThreads) void reclaim_kernel(BatchParams p) {
   const ReqDesc rd = p.descs[blockIdx.x];
+  int32_t* row = p.block_tables + (size_t)rd.table_row * p.max_blocks;
+  if (p.in_place) {
+    // the request keeps its first n_new blocks; the rest are released
+    for (int i = threadIdx.x; i < rd.n_old - rd.n_new; i += kThreads)
+      p.stack[p.top_before + rd.new_off + i] = p.old_ids[rd.old_off + rd.n_new + i];
+    for (int i = rd.n_new + threadIdx.x; i < p.max_blocks; i += kThreads) row[i] = -1;
+    return;
+  }
   const int base = p.top_before - p.total_new;
   for (int i = threadIdx.x; i < rd.n_old; i += kThreads)
     p.stack[base + rd.old_off + i] = p.old_ids[rd.old_off + i];
-  int32_t* row = p.block_tables + (size_t)rd.table_row * p.max_blocks;
   for (int i = threadIdx.x; i < p.max_blocks; i += kThreads)
     row[i] = (i < rd.n_new) ? p.new_ids[rd.new_off + i] : -1;
 }
@@ -626,7 +634,8 @@ __device__ __forceinline__ void gather_unit(const BatchParams& p, const ReqDesc&
   const int B = rd.budget;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int32_t* new_ids = p.new_ids + rd.new_off;
+  // destination blocks: freshly popped ones, or the request's own first blocks
+  const int32_t* new_ids = p.in_place ? old_ids : p.new_ids + rd.new_off;
   const int32_t* kept = p.kept + rd.kept_off + (size_t)lh * B;
   const size_t chunk = (size_t)16 * D;               // one (block, kv, head)
   const size_t v_off = (size_t)p.n_heads * chunk;    // K chunk -> V chunk of a block
@@ -634,16 +643,19 @@ __device__ __forceinline__ void gather_unit(const BatchParams& p, const ReqDesc&
   _Float16* base = p.kv + (size_t)layer * p.n_blocks * blk_stride + (size_t)head * chunk +
                    (lane % LPR) * 8;
   const int row_in_instr = lane / LPR;
-  for (int nbk = wave; nbk < rd.n_new; nbk += kWaves) {
-    const int dblk = clamp_block(new_ids[nbk], p.n_blocks);
-    _Float16* dst = base + (size_t)dblk * blk_stride;
+  // In place, output t overwrites slot t while kept[t] >= t: a chunk of
+  // kWaves*16 outputs only reads slots at or after its own start, so reading
+  // the whole chunk, a barrier, then writing it never destroys a row that is
+  // still needed (later chunks read strictly later slots).
+  for (int c0 = 0; c0 < rd.n_new; c0 += kWaves) {
+    const int nbk = c0 + wave;
     half8 kk[NI], vv[NI];
     bool ok[NI];
 #pragma unroll
     for (int k = 0; k < NI; ++k) {
       const int row = k * RPI + row_in_instr;
       const int t = nbk * 16 + row;
-      ok[k] = t < B;
+      ok[k] = nbk < rd.n_new && t < B;
       if (ok[k]) {
         const int idx = min(max(kept[t], 0), rd.seq_len - 1);
         const int sblk = clamp_block(old_ids[idx >> 4], p.n_blocks);
@@ -652,12 +664,17 @@ __device__ __forceinline__ void gather_unit(const BatchParams& p, const ReqDesc&
         vv[k] = load_half8(src + v_off);
       }
     }
+    if (p.in_place) __syncthreads();  // uniform: c0 and in_place are the same for all threads
+    if (nbk < rd.n_new) {
+      const int dblk = clamp_block(new_ids[nbk], p.n_blocks);
+      _Float16* dst = base + (size_t)dblk * blk_stride;
 #pragma unroll
-    for (int k = 0; k < NI; ++k) {
-      if (ok[k]) {
-        const int row = k * RPI + row_in_instr;
-        store_half8(dst + (size_t)row * D, kk[k]);
-        store_half8(dst + (size_t)row * D + v_off, vv[k]);
+      for (int k = 0; k < NI; ++k) {
+        if (ok[k]) {
+          const int row = k * RPI + row_in_instr;
+          store_half8(dst + (size_t)row * D, kk[k]);
+          store_half8(dst + (size_t)row * D + v_off, vv[k]);
+        }
       }
     }
   }

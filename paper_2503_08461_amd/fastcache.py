@@ -17,6 +17,7 @@ FC_DTYPE_F16 = 0
 FC_BLOCK_SIZE = 16
 FC_N_KERNELS = 7
 FC_SCORE_AUTO, FC_SCORE_TWO_PASS, FC_SCORE_ONE_PASS = 0, 1, 2
+FC_COMPACT_FRESH, FC_COMPACT_IN_PLACE = 0, 1
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libfastcache.so")
 
@@ -24,7 +25,7 @@ EXPORTS = [
     "fc_pool_create", "fc_pool_destroy", "fc_pool_alloc", "fc_pool_free",
     "fc_pool_num_free", "fc_pool_export_state", "fc_pool_import_state",
     "fc_pool_import_state_dev",
-    "fc_compress_batch", "fc_set_streaming_sinks", "fc_set_score_mode", "fc_set_profiling", "fc_get_kernel_times",
+    "fc_compress_batch", "fc_set_compaction_mode", "fc_set_streaming_sinks", "fc_set_score_mode", "fc_set_profiling", "fc_get_kernel_times",
     "fc_kernel_name", "fc_last_error",
 ]
 
@@ -74,6 +75,7 @@ def load_library():
                                       ctypes.c_float, vp, vp, vp]
     lib.fc_set_score_mode.argtypes = [vp, i]
     lib.fc_set_streaming_sinks.argtypes = [vp, i]
+    lib.fc_set_compaction_mode.argtypes = [vp, i]
     lib.fc_set_profiling.argtypes = [vp, i]
     lib.fc_get_kernel_times.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
     lib.fc_kernel_name.argtypes = [i]
@@ -225,6 +227,10 @@ def fc_compress_batch(pool, block_tables, seq_lens, q_window, window, method, bu
         _host_i32(method), _host_i32(budget), n_req, int(pool_kernel), float(scale),
         _dev_ptr(scores_out, torch.float32), _dev_ptr(kept_out, torch.int32),
         _stream_ptr(stream)))
+
+
+def fc_set_compaction_mode(pool, mode):
+    _check(load_library().fc_set_compaction_mode(pool.ptr, int(mode)))
 
 
 def fc_set_streaming_sinks(pool, n_sink):

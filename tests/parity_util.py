@@ -61,7 +61,8 @@ def check_kept(gk, g_scores, ok, o_scores, budget, where=""):
 class SideBySide:
     """Small workloads only: the whole pool lives on the host too."""
 
-    def __init__(self, wl, device="cuda:0", kv_host=None, q_host=None, score_mode=None):
+    def __init__(self, wl, device="cuda:0", kv_host=None, q_host=None, score_mode=None,
+                 in_place=False):
         import torch
         from paper_2503_08461_amd import fastcache as fc
         self.torch, self.fc, self.wl = torch, fc, wl
@@ -74,6 +75,8 @@ class SideBySide:
                                       wl.head_dim)
         if score_mode is not None:
             fc.fc_set_score_mode(self.pool, score_mode)
+        self.in_place = in_place
+        fc.fc_set_compaction_mode(self.pool, 1 if in_place else 0)
         self.stack = fo.FreeStack(wl.n_blocks)
         # block tables through the public calls of each pool
         rows_o = synth.build_block_tables(wl, self.stack.alloc, self.stack.free,
@@ -129,7 +132,7 @@ class SideBySide:
         bt_a, lens_a = self.bt_host.copy(), self.lens_o.copy()
         status, scores_o, kept_o = fo.compress_batch(
             kv_a, st_a, bt_a, lens_a, self.q_host, window, methods, budgets, pool_kernel,
-            scale if scale > 0 else None, n_sink=n_sink)
+            scale if scale > 0 else None, n_sink=n_sink, in_place=self.in_place)
         assert status is None, status
 
         # ... compared unit by unit
@@ -159,7 +162,7 @@ class SideBySide:
         status, _, _ = fo.compress_batch(
             self.kv_host, self.stack, self.bt_host, self.lens_o, self.q_host, window,
             methods, budgets, pool_kernel, scale if scale > 0 else None,
-            kept_override=kept_g_lists, n_sink=n_sink)
+            kept_override=kept_g_lists, n_sink=n_sink, in_place=self.in_place)
         assert status is None
         self.compare_state()
         return stats

@@ -322,3 +322,28 @@ def test_streaming_method_mixed_with_scored_methods(n_sink, score_mode):
         assert st["units_kept_identical"] == st["units"]
     finally:
         s.close()
+
+
+def test_in_place_compaction(score_mode):
+    """FC_COMPACT_IN_PLACE: same kept lists, rows moved inside the request's own
+    blocks (chunked so that no row is overwritten before it is read), tail
+    blocks released, nothing allocated - here with a pool that has no free
+    block at all, and with heads on both sides of the fused kernel's limit."""
+    M = fo.METHOD_STREAMING
+    lens = [700, 9000, 333, 64, 100, 2500]
+    methods = [fo.METHOD_SNAPKV, fo.METHOD_KNORM, fo.METHOD_KNORM, fo.METHOD_SNAPKV, M,
+               fo.METHOD_SNAPKV]
+    budgets = [350, 8999, 333, 16, 37, 500]
+    nb = int(sum(synth.blocks_for(x) for x in lens))           # pool exactly full
+    wl = _custom(lens, budgets, methods, W=16, d=128, n_heads=2, n_blocks=nb)
+    from parity_util import SideBySide
+    from paper_2503_08461_amd import fastcache as fc
+    s = SideBySide(wl, score_mode=score_mode, in_place=True)
+    try:
+        assert fc.fc_pool_num_free(s.pool) == 0
+        st = s.compress_and_compare()
+        assert st["units_kept_identical"] == st["units"]
+        # compress the compressed caches again, still in place
+        s.compress_and_compare(budgets=np.array([100, 4000, 50, 16, 5, 16], np.int32))
+    finally:
+        s.close()

@@ -383,3 +383,67 @@ def test_streaming_through_compress_batch_reads_no_scores():
             new = kv[0, bt[0, t // 4], 1, h, t % 4]
             old = kv0[0, bt0[0, idx // 4], 1, h, idx % 4]
             assert (new == old).all()
+
+
+# ---------------------------------------------------------------- in-place compaction
+
+def test_in_place_compaction_matches_fresh_blocks_logically():
+    """Compacting inside the request's own blocks must leave the same logical
+    K/V sequence as compacting into fresh blocks, allocate nothing, keep the
+    first ceil(B/bs) table entries and release the tail in table order."""
+    rng = np.random.default_rng(12)
+    n_layers, n_heads, bs, d, nb = 2, 2, 4, 8, 40
+    kv_a = _random_pool(rng, n_layers, nb, n_heads, bs, d)
+    kv_b = kv_a.copy()
+    lens0 = np.array([23, 8, 17], dtype=np.int32)
+    method = np.array([fo.METHOD_SNAPKV, fo.METHOD_KNORM, fo.METHOD_STREAMING])
+    budget = np.array([9, 8, 5])
+    q = rng.standard_normal((3, n_layers, n_heads, 4, d)).astype(np.float16)
+
+    def setup():
+        st = fo.FreeStack(nb)
+        st.free(st.alloc(nb)[rng2.permutation(nb)])      # permuted ids
+        bt = np.full((3, 6), -1, dtype=np.int32)
+        for r in range(3):
+            n = fo.blocks_for(int(lens0[r]), bs)
+            bt[r, :n] = st.alloc(n)
+        return st, bt
+
+    rng2 = np.random.default_rng(13)
+    st_a, bt_a = setup()
+    rng2 = np.random.default_rng(13)
+    st_b, bt_b = setup()
+    assert (bt_a == bt_b).all()
+    bt0 = bt_a.copy()
+    la, lb = lens0.copy(), lens0.copy()
+    sa = fo.compress_batch(kv_a, st_a, bt_a, la, q, 4, method, budget, 3)
+    free_before = st_b.top
+    sb = fo.compress_batch(kv_b, st_b, bt_b, lb, q, 4, method, budget, 3, in_place=True)
+    assert sa[0] is None and sb[0] is None and (la == lb).all()
+    for r in range(3):
+        assert all((sa[2][r] == sb[2][r]).ravel())          # same kept lists
+        B = int(budget[r])
+        n_new, n_old = fo.blocks_for(B, bs), fo.blocks_for(int(lens0[r]), bs)
+        assert (bt_b[r, :n_new] == bt0[r, :n_new]).all() and (bt_b[r, n_new:] == -1).all()
+        for l in range(n_layers):
+            for h in range(n_heads):
+                for c in (0, 1):
+                    a = np.stack([kv_a[l, bt_a[r, t // bs], c, h, t % bs] for t in range(B)])
+                    b = np.stack([kv_b[l, bt_b[r, t // bs], c, h, t % bs] for t in range(B)])
+                    assert (a == b).all()
+    # nothing allocated, tails released in batch order then table order
+    released = sum(fo.blocks_for(int(lens0[r]), bs) - fo.blocks_for(int(budget[r]), bs)
+                   for r in range(3))
+    assert st_b.top == free_before + released
+    want = []
+    for r in range(3):
+        want += bt0[r, fo.blocks_for(int(budget[r]), bs):fo.blocks_for(int(lens0[r]), bs)].tolist()
+    assert st_b.stack[free_before:st_b.top].tolist() == want
+    # in place never runs out of blocks
+    st_c = fo.FreeStack(6)
+    bt_c = st_c.alloc(6)[None, :].copy()
+    kv_c = _random_pool(rng, 1, 6, 1, bs, d)
+    assert fo.compress_batch(kv_c, st_c, bt_c, np.array([24], np.int32), None, 0,
+                             [fo.METHOD_KNORM], [20])[0] == "ENOMEM"
+    assert fo.compress_batch(kv_c, st_c, bt_c, np.array([24], np.int32), None, 0,
+                             [fo.METHOD_KNORM], [20], in_place=True)[0] is None
