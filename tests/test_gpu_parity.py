@@ -347,3 +347,39 @@ def test_in_place_compaction(score_mode):
         s.compress_and_compare(budgets=np.array([100, 4000, 50, 16, 5, 16], np.int32))
     finally:
         s.close()
+
+
+def test_work_is_issued_on_the_callers_stream():
+    """All device work of the pool calls goes to the stream that is passed in
+    (a non-default stream here): results are complete after synchronising that
+    stream alone, and match a run on the default stream bit for bit."""
+    import torch
+    from paper_2503_08461_amd import fastcache as fc
+    wl = _custom([900, 450], [300, 200], [fo.METHOD_SNAPKV, fo.METHOD_KNORM], W=32, d=128, n_heads=4)
+    kv_host = synth.fill_pool_host(wl)
+    q_host = synth.fill_q_window_host(wl)
+    outs = []
+    for use_side_stream in (False, True):
+        kv = torch.from_numpy(kv_host.copy()).cuda()
+        q = torch.from_numpy(q_host.copy()).cuda()
+        torch.cuda.synchronize()
+        stream = torch.cuda.Stream() if use_side_stream else torch.cuda.current_stream()
+        pool = fc.fc_pool_create(kv, wl.n_blocks, wl.n_layers, wl.n_heads, wl.head_dim)
+        try:
+            with torch.cuda.stream(stream):
+                bt = torch.full((2, wl.max_blocks), -1, dtype=torch.int32, device="cuda")
+                for r in range(2):
+                    n = synth.blocks_for(int(wl.seq_lens[r]))
+                    fc.fc_pool_alloc(pool, n, bt[r, :n], stream=stream)
+                lens = wl.seq_lens.copy()
+                kept = torch.empty(int(wl.budgets.sum()) * 4, dtype=torch.int32, device="cuda")
+                fc.fc_compress_batch(pool, bt, lens, q, 32, wl.methods, wl.budgets, 7, 0.0, None,
+                                     kept, stream=stream)
+            stream.synchronize()
+            outs.append((kv.cpu(), bt.cpu(), kept.cpu(), fc.fc_pool_export_state(pool)))
+        finally:
+            fc.fc_pool_destroy(pool)
+    a, b = outs
+    assert torch.equal(a[1], b[1]) and torch.equal(a[2], b[2])
+    assert torch.equal(a[0].view(torch.int16), b[0].view(torch.int16))
+    assert a[3][1] == b[3][1] and (a[3][0][:a[3][1]] == b[3][0][:b[3][1]]).all()
