@@ -154,6 +154,49 @@ int fc_compress_batch(fc_pool* pool, int32_t* dev_block_tables, int max_blocks_p
                       int32_t* dev_kept_out, void* stream);
 
 /*
+ * The paper's own compressor shape ("Multimodal Compressor" section): the cache
+ * is split at the modality boundary, every run of k consecutive tokens of one
+ * modality is reshaped into one vector of k*head_dim numbers and mapped to ONE
+ * row by that modality's MLP, and the results are concatenated in the
+ * original order.  The paper gives neither architecture nor weights; this
+ * library takes  y = W2 . gelu(W1 . x + b1) + b2  (erf gelu, one hidden layer)
+ * with caller-supplied weights, shared by all layers, heads and by K and V.
+ * fp16 rows and weights, fp32 accumulation, hidden activations rounded to
+ * fp16 (they are the fp16 operand of the second MFMA product), output rounded
+ * to fp16.  head_dim 64 or 128; hidden 128 or 256; k in 1..8.
+ */
+typedef struct fc_mlp_weights {
+  int k;              /* tokens per chunk = compression factor */
+  int hidden;         /* hidden width */
+  const void* w1[2];  /* dev, fp16 [hidden][k*head_dim] row-major; [0] text, [1] image */
+  const float* b1[2]; /* dev, fp32 [hidden] */
+  const void* w2[2];  /* dev, fp16 [head_dim][hidden] row-major */
+  const float* b2[2]; /* dev, fp32 [head_dim] */
+} fc_mlp_weights;
+
+/* Copies the weights into library-owned device memory in the operand order of
+ * the kernel (the caller's buffers may be released after the stream has run
+ * past this call).  FC_EINVAL for unsupported sizes or NULL pointers. */
+int fc_mlp_set_weights(fc_pool* pool, const fc_mlp_weights* weights, void* stream);
+
+/*
+ * Chunk-MLP compression of a whole batch.  Request r (if host_enable is NULL
+ * or host_enable[r] != 0) has text tokens [0, img_begin_r), image tokens
+ * [img_begin_r, img_end_r) and text tokens [img_end_r, L_r); each of the three
+ * segments is cut into ceil(n/k) chunks (the last one zero-padded) and every
+ * chunk becomes one row, for every layer and head, K and V alike.  New blocks
+ * for ceil(L'_r/16) rows (L'_r = number of chunks) are popped for all
+ * requests first, then all old blocks are pushed, exactly as in
+ * fc_compress_batch; host_seq_lens[r] becomes L'_r.  Block-table and length
+ * arguments as in fc_compress_batch.  FC_EINVAL: weights not set, bad span,
+ * table too small; FC_ENOMEM: not enough free blocks.
+ */
+int fc_compress_batch_mlp(fc_pool* pool, int32_t* dev_block_tables, int max_blocks_per_req,
+                          int32_t* host_seq_lens, const int32_t* host_img_begin,
+                          const int32_t* host_img_end, const int32_t* host_enable, int n_req,
+                          void* stream);
+
+/*
  * Where fc_compress_batch puts the kept rows.
  *   FC_COMPACT_FRESH (default): into freshly popped blocks, as described at
  *     fc_compress_batch (needs sum ceil(budget_r/16) free blocks).
@@ -201,7 +244,7 @@ int fc_set_score_mode(fc_pool* pool, int mode);
  * fc_kernel_name(i) names slot i.  fc_set_profiling(pool, 1) restarts the
  * average.
  */
-#define FC_N_KERNELS 7
+#define FC_N_KERNELS 8
 int fc_set_profiling(fc_pool* pool, int enable);
 int fc_get_kernel_times(fc_pool* pool, float* host_ms);
 const char* fc_kernel_name(int i);

@@ -39,7 +39,7 @@ int fail(int code, const char* fmt, ...) {
 
 const char* const kKernelNames[K_COUNT] = {"plan_alloc", "snapkv_score", "knorm_score",
                                            "select",     "gather",       "reclaim",
-                                           "fused_unit"};
+                                           "fused_unit", "mlp_compress"};
 
 size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -76,6 +76,12 @@ struct fc_pool {
   int score_mode = FC_SCORE_AUTO;
   int n_sink = 4;
   int compact_mode = FC_COMPACT_FRESH;
+  // chunk-MLP compressor weights in operand order (library-owned)
+  int mlp_k = 0, mlp_hidden = 0;
+  _Float16* mlp_w1p[2] = {nullptr, nullptr};
+  _Float16* mlp_w2p[2] = {nullptr, nullptr};
+  float* mlp_b1[2] = {nullptr, nullptr};
+  float* mlp_b2[2] = {nullptr, nullptr};
   int team_grid[FC_MAX_WINDOW / 16 + 1] = {};  // co-resident grid per query-tile count, -1 = none
 
   bool profiling = false;
@@ -140,6 +146,7 @@ int fc_pool_create(fc_pool** out, void* kv_base, size_t kv_bytes, int n_blocks, 
     return fail(FC_EINVAL, "kv_bytes %zu is smaller than the pool geometry needs (%zu)", kv_bytes,
                 need);
   FC_HIP(kernels_one_time_setup());
+  FC_HIP(mlp_one_time_setup());
   fc_pool* p = new fc_pool();
   p->kv = static_cast<_Float16*>(kv_base);
   p->kv_bytes = kv_bytes;
@@ -175,6 +182,12 @@ int fc_pool_destroy(fc_pool* p) {
   if (p->team_counters) (void)hipFree(p->team_counters);
   if (p->team_stats) (void)hipFree(p->team_stats);
   if (p->error_flag) (void)hipFree(p->error_flag);
+  for (int m = 0; m < 2; ++m) {
+    if (p->mlp_w1p[m]) (void)hipFree(p->mlp_w1p[m]);
+    if (p->mlp_w2p[m]) (void)hipFree(p->mlp_w2p[m]);
+    if (p->mlp_b1[m]) (void)hipFree(p->mlp_b1[m]);
+    if (p->mlp_b2[m]) (void)hipFree(p->mlp_b2[m]);
+  }
   if (p->dev_meta) (void)hipFree(p->dev_meta);
   if (p->host_meta) (void)hipHostFree(p->host_meta);
   if (p->meta_event) (void)hipEventDestroy(p->meta_event);
@@ -540,6 +553,178 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
 
   // ---- host mirrors ------------------------------------------------------------
   p->top = in_place ? p->top + total_released : p->top - total_new + total_old;
+  for (const ReqDesc& d : descs) host_seq_lens[d.table_row] = d.budget;
+  return FC_OK;
+}
+
+int fc_mlp_set_weights(fc_pool* p, const fc_mlp_weights* w, void* stream_) {
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  if (!p || !w) return fail(FC_EINVAL, "NULL argument");
+  if (w->k < 1 || w->k > 8) return fail(FC_EINVAL, "k must be in 1..8");
+  if (w->hidden != 128 && w->hidden != 256) return fail(FC_EINVAL, "hidden must be 128 or 256");
+  for (int m = 0; m < 2; ++m)
+    if (!w->w1[m] || !w->b1[m] || !w->w2[m] || !w->b2[m])
+      return fail(FC_EINVAL, "NULL weight pointer");
+  FC_HIP(hipDeviceSynchronize());  // earlier calls may still read the old copies
+  const size_t n1 = mlp_w1p_elems(p->head_dim, w->hidden, w->k);
+  const size_t n2 = mlp_w2p_elems(p->head_dim, w->hidden);
+  for (int m = 0; m < 2; ++m) {
+    if (p->mlp_w1p[m]) FC_HIP(hipFree(p->mlp_w1p[m]));
+    if (p->mlp_w2p[m]) FC_HIP(hipFree(p->mlp_w2p[m]));
+    if (p->mlp_b1[m]) FC_HIP(hipFree(p->mlp_b1[m]));
+    if (p->mlp_b2[m]) FC_HIP(hipFree(p->mlp_b2[m]));
+    p->mlp_w1p[m] = p->mlp_w2p[m] = nullptr;
+    p->mlp_b1[m] = p->mlp_b2[m] = nullptr;
+  }
+  p->mlp_k = p->mlp_hidden = 0;
+  for (int m = 0; m < 2; ++m) {
+    FC_HIP(hipMalloc(reinterpret_cast<void**>(&p->mlp_w1p[m]), n1 * sizeof(_Float16)));
+    FC_HIP(hipMalloc(reinterpret_cast<void**>(&p->mlp_w2p[m]), n2 * sizeof(_Float16)));
+    FC_HIP(hipMalloc(reinterpret_cast<void**>(&p->mlp_b1[m]), (size_t)w->hidden * sizeof(float)));
+    FC_HIP(hipMalloc(reinterpret_cast<void**>(&p->mlp_b2[m]), (size_t)p->head_dim * sizeof(float)));
+    FC_HIP(launch_mlp_permute_weights(static_cast<const _Float16*>(w->w1[m]),
+                                      static_cast<const _Float16*>(w->w2[m]), p->mlp_w1p[m],
+                                      p->mlp_w2p[m], p->head_dim, w->hidden, w->k, stream));
+    FC_HIP(hipMemcpyAsync(p->mlp_b1[m], w->b1[m], (size_t)w->hidden * sizeof(float),
+                          hipMemcpyDeviceToDevice, stream));
+    FC_HIP(hipMemcpyAsync(p->mlp_b2[m], w->b2[m], (size_t)p->head_dim * sizeof(float),
+                          hipMemcpyDeviceToDevice, stream));
+  }
+  p->mlp_k = w->k;
+  p->mlp_hidden = w->hidden;
+  return FC_OK;
+}
+
+int fc_compress_batch_mlp(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_req,
+                          int32_t* host_seq_lens, const int32_t* host_img_begin,
+                          const int32_t* host_img_end, const int32_t* host_enable, int n_req,
+                          void* stream_) {
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  if (!p) return fail(FC_EINVAL, "pool is NULL");
+  if (p->mlp_k == 0) return fail(FC_EINVAL, "fc_mlp_set_weights has not been called");
+  if (n_req < 0) return fail(FC_EINVAL, "n_req < 0");
+  if (n_req == 0) return FC_OK;
+  if (!dev_block_tables || !host_seq_lens || !host_img_begin || !host_img_end)
+    return fail(FC_EINVAL, "NULL argument");
+  if (max_blocks_per_req < 1) return fail(FC_EINVAL, "max_blocks_per_req < 1");
+  const int k = p->mlp_k;
+  const int n_units = p->n_layers * p->n_heads * 2;
+  std::vector<ReqDesc> descs;
+  std::vector<MlpJob> jobs;
+  int total_new = 0, total_old = 0;
+  long long n_tiles = 0;
+  for (int r = 0; r < n_req; ++r) {
+    if (host_enable && !host_enable[r]) continue;
+    const int L = host_seq_lens[r], ib = host_img_begin[r], ie = host_img_end[r];
+    if (L < 1 || L > FC_MAX_SEQ_LEN)
+      return fail(FC_EINVAL, "request %d: length %d outside 1..%d", r, L, FC_MAX_SEQ_LEN);
+    if (ib < 0 || ib > ie || ie > L)
+      return fail(FC_EINVAL, "request %d: image span [%d, %d) outside [0, %d]", r, ib, ie, L);
+    ReqDesc d = {};
+    d.seq_len = L;
+    d.img_begin = ib;
+    d.img_end = ie;
+    d.chunks_text0 = (ib + k - 1) / k;
+    d.chunks_image = (ie - ib + k - 1) / k;
+    d.chunks_text1 = (L - ie + k - 1) / k;
+    d.budget = d.chunks_text0 + d.chunks_image + d.chunks_text1;
+    d.method = FC_METHOD_NONE;
+    d.table_row = r;
+    d.n_old = (L + FC_BLOCK_SIZE - 1) / FC_BLOCK_SIZE;
+    d.n_new = (d.budget + FC_BLOCK_SIZE - 1) / FC_BLOCK_SIZE;
+    if (d.n_old > max_blocks_per_req)
+      return fail(FC_EINVAL, "request %d: %d blocks exceed max_blocks_per_req %d", r, d.n_old,
+                  max_blocks_per_req);
+    d.old_off = total_old;
+    d.new_off = total_new;
+    total_old += d.n_old;
+    total_new += d.n_new;
+    const int di = (int)descs.size();
+    const int per_modality[2] = {d.chunks_text0 + d.chunks_text1, d.chunks_image};
+    for (int m = 0; m < 2; ++m) {
+      if (per_modality[m] == 0) continue;
+      MlpJob j;
+      j.desc = di;
+      j.modality = m;
+      j.chunks = per_modality[m];
+      j.tile_start = (int)n_tiles;
+      n_tiles += ((long long)n_units * per_modality[m] + 255) / 256;
+      jobs.push_back(j);
+    }
+    descs.push_back(d);
+  }
+  const int n_comp = (int)descs.size();
+  if (n_comp == 0) return FC_OK;
+  if (n_tiles > 0x7fffffffLL) return fail(FC_EINVAL, "batch too large for one launch");
+  if (total_new > p->top)
+    return fail(FC_ENOMEM, "batch needs %d new blocks, %d free", total_new, p->top);
+
+  int rc;
+  if ((rc = grow(&p->ids, &p->ids_cap, (size_t)total_old + total_new)) != FC_OK) return rc;
+  const size_t desc_bytes = round_up((size_t)n_comp * sizeof(ReqDesc), 16);
+  const size_t job_bytes = round_up(jobs.size() * sizeof(MlpJob), 16);
+  if ((rc = grow_meta(p, desc_bytes + job_bytes)) != FC_OK) return rc;
+  if (p->meta_pending) {
+    FC_HIP(hipEventSynchronize(p->meta_event));
+    p->meta_pending = false;
+  }
+  memcpy(p->host_meta, descs.data(), (size_t)n_comp * sizeof(ReqDesc));
+  memcpy(p->host_meta + desc_bytes, jobs.data(), jobs.size() * sizeof(MlpJob));
+  FC_HIP(hipMemcpyAsync(p->dev_meta, p->host_meta, desc_bytes + job_bytes, hipMemcpyHostToDevice,
+                        stream));
+  FC_HIP(hipEventRecord(p->meta_event, stream));
+  p->meta_pending = true;
+
+  BatchParams bp = {};
+  bp.kv = p->kv;
+  bp.n_blocks = p->n_blocks;
+  bp.n_layers = p->n_layers;
+  bp.n_heads = p->n_heads;
+  bp.head_dim = p->head_dim;
+  bp.stack = p->stack;
+  bp.top_before = p->top;
+  bp.total_new = total_new;
+  bp.total_old = total_old;
+  bp.descs = reinterpret_cast<const ReqDesc*>(p->dev_meta);
+  bp.n_comp = n_comp;
+  bp.block_tables = dev_block_tables;
+  bp.max_blocks = max_blocks_per_req;
+  bp.old_ids = p->ids;
+  bp.new_ids = p->ids + total_old;
+  bp.error_flag = p->error_flag;
+  MlpParams mp = {};
+  mp.jobs = reinterpret_cast<const MlpJob*>(p->dev_meta + desc_bytes);
+  mp.n_jobs = (int)jobs.size();
+  mp.n_tiles = (int)n_tiles;
+  mp.k = k;
+  mp.hidden = p->mlp_hidden;
+  for (int m = 0; m < 2; ++m) {
+    mp.w1p[m] = p->mlp_w1p[m];
+    mp.w2p[m] = p->mlp_w2p[m];
+    mp.b1[m] = p->mlp_b1[m];
+    mp.b2[m] = p->mlp_b2[m];
+  }
+
+  const int ring = p->prof_calls % kProfRing;
+  if (p->profiling) {
+    for (int kk = 0; kk < K_COUNT; ++kk) p->timed[ring][kk] = false;
+    ++p->prof_calls;
+  }
+  auto run = [&](int slot, auto&& launch) -> hipError_t {
+    hipError_t e = hipSuccess;
+    if (p->profiling) e = hipEventRecord(p->ev[ring][slot][0], stream);
+    if (e == hipSuccess) e = launch();
+    if (e == hipSuccess && p->profiling) {
+      e = hipEventRecord(p->ev[ring][slot][1], stream);
+      p->timed[ring][slot] = true;
+    }
+    return e;
+  };
+  FC_HIP(run(K_PLAN_ALLOC, [&] { return launch_plan_alloc(bp, stream); }));
+  FC_HIP(run(K_MLP, [&] { return launch_mlp_compress(bp, mp, stream); }));
+  FC_HIP(run(K_RECLAIM, [&] { return launch_reclaim(bp, stream); }));
+
+  p->top = p->top - total_new + total_old;
   for (const ReqDesc& d : descs) host_seq_lens[d.table_row] = d.budget;
   return FC_OK;
 }

@@ -27,6 +27,29 @@ struct ReqDesc {
   int32_t team_size;     // g_r
   int32_t team_counter;  // first of this request's n_wg/g_r team counters
   int64_t team_stats;    // first float of this request's exchange buffers
+  // chunk-MLP compressor: the image span and the chunk counts of the three segments
+  int32_t img_begin, img_end;
+  int32_t chunks_text0, chunks_image, chunks_text1;
+  int32_t pad_;
+};
+
+// One (request, modality) job of the chunk-MLP kernel: rows = units x chunks.
+struct MlpJob {
+  int32_t desc;        // index into descs
+  int32_t modality;    // 0 text, 1 image
+  int32_t chunks;      // chunks of this modality in the request
+  int32_t tile_start;  // first 256-row tile of this job
+};
+
+struct MlpParams {
+  const MlpJob* jobs;
+  int32_t n_jobs, n_tiles;
+  int32_t k, hidden;
+  // weights in operand order, index 0 text / 1 image
+  const _Float16* w1p[2];
+  const _Float16* w2p[2];
+  const float* b1[2];
+  const float* b2[2];
 };
 
 // Everything a kernel of the stage needs.  Passed by value.
@@ -72,7 +95,8 @@ enum KernelSlot {
   K_GATHER = 4,
   K_RECLAIM = 5,
   K_FUSED = 6,
-  K_COUNT = 7
+  K_MLP = 7,
+  K_COUNT = 8
 };
 
 // Launchers (fc_kernels.hip).  Each returns the hipError_t of the launch.
@@ -97,5 +121,13 @@ hipError_t launch_fused(const BatchParams& p, bool any_snap, int max_seq_len, hi
 static constexpr int kFusedMaxLen = 8192;
 hipError_t launch_reclaim(const BatchParams& p, hipStream_t s);
 hipError_t kernels_one_time_setup();
+// chunk-MLP compressor (fc_mlp.hip)
+hipError_t mlp_one_time_setup();
+size_t mlp_w1p_elems(int head_dim, int hidden, int k);
+size_t mlp_w2p_elems(int head_dim, int hidden);
+hipError_t launch_mlp_permute_weights(const _Float16* w1, const _Float16* w2, _Float16* w1p,
+                                      _Float16* w2p, int head_dim, int hidden, int k,
+                                      hipStream_t s);
+hipError_t launch_mlp_compress(const BatchParams& p, const MlpParams& mp, hipStream_t s);
 
 }  // namespace fc

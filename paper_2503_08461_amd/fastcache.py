@@ -15,7 +15,7 @@ FC_OK, FC_EINVAL, FC_ENOMEM, FC_EDEVICE = 0, -1, -2, -3
 FC_METHOD_NONE, FC_METHOD_SNAPKV, FC_METHOD_KNORM, FC_METHOD_STREAMING = 0, 1, 2, 3
 FC_DTYPE_F16 = 0
 FC_BLOCK_SIZE = 16
-FC_N_KERNELS = 7
+FC_N_KERNELS = 8
 FC_SCORE_AUTO, FC_SCORE_TWO_PASS, FC_SCORE_ONE_PASS = 0, 1, 2
 FC_COMPACT_FRESH, FC_COMPACT_IN_PLACE = 0, 1
 
@@ -25,11 +25,18 @@ EXPORTS = [
     "fc_pool_create", "fc_pool_destroy", "fc_pool_alloc", "fc_pool_free",
     "fc_pool_num_free", "fc_pool_export_state", "fc_pool_import_state",
     "fc_pool_import_state_dev",
-    "fc_compress_batch", "fc_set_compaction_mode", "fc_set_streaming_sinks", "fc_set_score_mode", "fc_set_profiling", "fc_get_kernel_times",
+    "fc_compress_batch", "fc_mlp_set_weights", "fc_compress_batch_mlp", "fc_set_compaction_mode", "fc_set_streaming_sinks", "fc_set_score_mode", "fc_set_profiling", "fc_get_kernel_times",
     "fc_kernel_name", "fc_last_error",
 ]
 
 _lib = None
+
+
+class McpWeights(ctypes.Structure):
+    """struct fc_mlp_weights"""
+    _fields_ = [("k", ctypes.c_int), ("hidden", ctypes.c_int),
+                ("w1", ctypes.c_void_p * 2), ("b1", ctypes.c_void_p * 2),
+                ("w2", ctypes.c_void_p * 2), ("b2", ctypes.c_void_p * 2)]
 
 
 class FastCacheError(RuntimeError):
@@ -73,6 +80,8 @@ def load_library():
     lib.fc_pool_import_state_dev.argtypes = [vp, vp, i, vp]
     lib.fc_compress_batch.argtypes = [vp, vp, i, i32p, vp, i, i32p, i32p, i, i,
                                       ctypes.c_float, vp, vp, vp]
+    lib.fc_mlp_set_weights.argtypes = [vp, ctypes.POINTER(McpWeights), vp]
+    lib.fc_compress_batch_mlp.argtypes = [vp, vp, i, i32p, i32p, i32p, i32p, i, vp]
     lib.fc_set_score_mode.argtypes = [vp, i]
     lib.fc_set_streaming_sinks.argtypes = [vp, i]
     lib.fc_set_compaction_mode.argtypes = [vp, i]
@@ -227,6 +236,41 @@ def fc_compress_batch(pool, block_tables, seq_lens, q_window, window, method, bu
         _host_i32(method), _host_i32(budget), n_req, int(pool_kernel), float(scale),
         _dev_ptr(scores_out, torch.float32), _dev_ptr(kept_out, torch.int32),
         _stream_ptr(stream)))
+
+
+def fc_mlp_set_weights(pool, k, w1, b1, w2, b2, stream=None):
+    """w1, b1, w2, b2: pairs (text, image) of device tensors: w1 fp16
+    [hidden][k*head_dim], b1 fp32 [hidden], w2 fp16 [head_dim][hidden], b2 fp32 [head_dim]."""
+    import torch
+    lib = load_library()
+    hidden = int(w1[0].shape[0])
+    for m in range(2):
+        if tuple(w1[m].shape) != (hidden, k * pool.head_dim) or \
+                tuple(w2[m].shape) != (pool.head_dim, hidden) or \
+                tuple(b1[m].shape) != (hidden,) or tuple(b2[m].shape) != (pool.head_dim,):
+            raise ValueError("weight shapes do not match k, hidden and head_dim")
+    w = McpWeights()
+    w.k, w.hidden = int(k), hidden
+    for m in range(2):
+        w.w1[m] = _dev_ptr(w1[m], torch.float16).value
+        w.b1[m] = _dev_ptr(b1[m], torch.float32).value
+        w.w2[m] = _dev_ptr(w2[m], torch.float16).value
+        w.b2[m] = _dev_ptr(b2[m], torch.float32).value
+    _check(lib.fc_mlp_set_weights(pool.ptr, ctypes.byref(w), _stream_ptr(stream)))
+
+
+def fc_compress_batch_mlp(pool, block_tables, seq_lens, img_begin, img_end, enable=None,
+                          stream=None):
+    """seq_lens (in/out), img_begin, img_end, enable: int32 numpy arrays [n_req]."""
+    import torch
+    lib = load_library()
+    n_req = int(seq_lens.shape[0])
+    if block_tables.dim() != 2 or block_tables.shape[0] != n_req:
+        raise ValueError("block_tables must be [n_req][max_blocks]")
+    _check(lib.fc_compress_batch_mlp(
+        pool.ptr, _dev_ptr(block_tables, torch.int32), int(block_tables.shape[1]),
+        _host_i32(seq_lens), _host_i32(img_begin), _host_i32(img_end),
+        _host_i32(enable) if enable is not None else None, n_req, _stream_ptr(stream)))
 
 
 def fc_set_compaction_mode(pool, mode):
