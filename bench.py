@@ -79,15 +79,81 @@ def cpu_baseline(dw, seconds=15.0, seed=0):
     }
 
 
+MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X published dense fp16 MFMA peak
+
+
+def bench_mlp(args, wl):
+    """The chunk-MLP compressor on the same batch: text 64 | image | text 64,
+    k = 5, hidden 256, seeded random weights.  MFMA-bound, so the roofline
+    object reports TFLOP/s against the dense fp16 MFMA peak."""
+    import numpy as np
+    import torch
+    from paper_2503_08461_amd import fastcache as fc
+    from paper_2503_08461_amd.device_setup import DeviceWorkload
+    k, hidden, d = 5, 256, wl.head_dim
+    wl.name += "_mlp"
+    dw = DeviceWorkload(wl, verbose=True)
+    gen = torch.Generator(device=dw.dev)
+    gen.manual_seed(wl.seed + 5000)
+    w1 = [(torch.randn((hidden, k * d), generator=gen, device=dw.dev) / (k * d) ** 0.5).half()
+          for _ in range(2)]
+    w2 = [(torch.randn((d, hidden), generator=gen, device=dw.dev) / hidden ** 0.5).half()
+          for _ in range(2)]
+    b1 = [0.1 * torch.randn(hidden, generator=gen, device=dw.dev) for _ in range(2)]
+    b2 = [0.1 * torch.randn(d, generator=gen, device=dw.dev) for _ in range(2)]
+    fc.fc_mlp_set_weights(dw.pool, k, w1, b1, w2, b2)
+    img_b = np.full(wl.n_req, 64, dtype=np.int32)
+    img_e = (wl.seq_lens - 64).astype(np.int32)
+
+    def step():
+        dw.rewind_async()
+        fc.fc_compress_batch_mlp(dw.pool, dw.bt, dw.lens, img_b, img_e)
+
+    for _ in range(args.warmup):
+        step()
+    fc.fc_set_profiling(dw.pool, True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / args.steps
+    kms = fc.fc_get_kernel_times(dw.pool)
+    n_units = wl.n_layers * wl.n_heads * 2
+    tokens = int(wl.seq_lens.astype(np.int64).sum())
+    chunks = int(sum(-(-64 // k) + -(-(int(L) - 128) // k) + -(-64 // k) for L in wl.seq_lens))
+    flops = chunks * n_units * 2.0 * (k * d * hidden + hidden * d)
+    bytes_ = n_units * (tokens + chunks) * 2 * d
+    tf = flops / (kms["mlp_compress"] * 1e-3) / 1e12
+    out = {
+        "metric": "KV tokens compressed/sec (all layers x heads), batched, chunk-MLP compressor",
+        "value": tokens / sec, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": wl.name, "n_req": wl.n_req, "tokens": tokens, "k": k,
+                   "hidden": hidden, "rows_out": chunks, "pool_GiB": round(wl.pool_bytes() / 2**30, 1)},
+        "path": {"flops": flops, "algorithmic_bytes": bytes_,
+                 "achieved_GBps": bytes_ / sec / 1e9},
+        "kernel_ms": {kk: round(v, 4) for kk, v in kms.items() if v > 0},
+        "roofline": {"kernel": "mlp_compress", "bound": "mfma", "achieved": tf,
+                     "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": tf / MFMA_F16_PEAK_TFLOPS, "traffic": None},
+    }
+    dw.close()
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="config4",
-                    choices=["config2", "config3", "config4", "config4_streaming"],
+                    choices=["config2", "config3", "config4", "config4_streaming", "config4_mlp"],
                     help="config4_streaming: the config-4 batch with every request using the "
-                         "score-free sinks + recent rule (gather and pool work only)")
+                         "score-free sinks + recent rule (gather and pool work only); "
+                         "config4_mlp: the config-4 batch through the chunk-MLP compressor "
+                         "(k = 5, hidden 256, synthetic weights)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="CPU time budget of the oracle baseline (0 = skip)")
     ap.add_argument("--score-mode", default="auto", choices=["auto", "two_pass", "one_pass"],
@@ -131,6 +197,9 @@ def main():
             wl.name, need / 2**30, total / 2**30), file=sys.stderr)
         sys.exit(2)
 
+    if args.workload.endswith("_mlp"):
+        bench_mlp(args, wl)
+        return
     dw = DeviceWorkload(wl, verbose=True)
     fc.fc_set_score_mode(dw.pool, {"auto": 0, "two_pass": 1, "one_pass": 2}[args.score_mode])
     fc.fc_set_profiling(dw.pool, True)

@@ -159,7 +159,7 @@ int fc_compress_batch(fc_pool* pool, int32_t* dev_block_tables, int max_blocks_p
  * modality is reshaped into one vector of k*head_dim numbers and mapped to ONE
  * row by that modality's MLP, and the results are concatenated in the
  * original order.  The paper gives neither architecture nor weights; this
- * library takes  y = W2 . gelu(W1 . x + b1) + b2  (erf gelu, one hidden layer)
+ * library takes  y = W2 . gelu(W1 . x + b1) + b2  (tanh-form GELU, one hidden layer)
  * with caller-supplied weights, shared by all layers, heads and by K and V.
  * fp16 rows and weights, fp32 accumulation, hidden activations rounded to
  * fp16 (they are the fp16 operand of the second MFMA product), output rounded

@@ -15,8 +15,9 @@ taken here are:
     consecutive tokens, the last chunk of a segment zero-padded;
   * a chunk is the concatenation of its k token rows (k*d numbers); the
     network of the chunk's modality maps it to ONE row of d numbers:
-        y = W2 . gelu(W1 . x + b1) + b2,   gelu(v) = v/2 * (1 + erf(v/sqrt 2))
-    with W1 [hidden][k*d], W2 [d][hidden];
+        y = W2 . gelu(W1 . x + b1) + b2
+    with W1 [hidden][k*d], W2 [d][hidden] and the tanh form of GELU,
+        gelu(v) = v/2 * (1 + tanh(sqrt(2/pi) * (v + 0.044715 v^3)));
   * the same two networks serve every layer, every head, and both K and V;
   * precision: rows, W1, W2 are fp16 values; sums are exact (fp64 here); the
     hidden activations are rounded to fp16 before the second product (they are
@@ -28,13 +29,12 @@ taken here are:
 """
 
 import numpy as np
-from scipy.special import erf
 
 from .fastcache_oracle import blocks_for, fetch_rows
 
 
 def gelu(v):
-    return 0.5 * v * (1.0 + erf(v / np.sqrt(2.0)))
+    return 0.5 * v * (1.0 + np.tanh(np.sqrt(2.0 / np.pi) * (v + 0.044715 * v ** 3)))
 
 
 def chunk_plan(n_tokens, img_begin, img_end, k):

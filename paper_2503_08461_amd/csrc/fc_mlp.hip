@@ -1,5 +1,5 @@
 // Chunk-MLP compressor kernel for gfx950: every run of k consecutive tokens
-// of one modality becomes one row, y = W2 . gelu(W1 . x + b1) + b2.
+// of one modality becomes one row, y = W2 . gelu(W1 . x + b1) + b2 (tanh GELU).
 //
 // This is the one dense contraction of the library that is MFMA-bound
 // (about 390 kflop per 1.3 KB chunk at k = 5, d = 128, hidden = 256), so it is
@@ -43,7 +43,11 @@ __host__ __device__ constexpr int mlp_hidden_unit(int sl, int kh, int e) {
 size_t mlp_w1p_elems(int head_dim, int hidden, int k) { return (size_t)hidden * k * head_dim; }
 size_t mlp_w2p_elems(int head_dim, int hidden) { return (size_t)hidden * head_dim; }
 
-// w1p[s][mt][lane][e] = w1[mt*32 + lane%32][s*16 + 8*(lane/32) + e]
+// Contraction position (slab s = t*SPT + j, lane half kh, element e) of the
+// first product is channel (D/2)*kh + 8*j + e of token t of the chunk: each
+// lane half owns one contiguous half row (128 B at D = 128), so a lane's loads
+// for one token fall into a single cache line.
+// w1p[s][mt][lane][e] = w1[mt*32 + lane%32][t*D + (D/2)*(lane/32) + 8*j + e]
 // w2p[sl][ot][lane][e] = w2[ot*32 + lane%32][mlp_hidden_unit(sl, lane/32, e)]
 __global__ void mlp_permute_kernel(const _Float16* w1, const _Float16* w2, _Float16* w1p,
                                    _Float16* w2p, int head_dim, int hidden, int k) {
@@ -55,7 +59,10 @@ __global__ void mlp_permute_kernel(const _Float16* w1, const _Float16* w2, _Floa
     const size_t rest = i >> 9;
     const int mt1 = hidden / 32;
     const int mt = rest % mt1, s = rest / mt1;
-    w1p[i] = w1[(size_t)(mt * 32 + (lane & 31)) * kd + s * 16 + 8 * (lane >> 5) + e];
+    const int spt = head_dim / 16;
+    const int t = s / spt, j = s - t * spt;
+    w1p[i] = w1[(size_t)(mt * 32 + (lane & 31)) * kd + t * head_dim + (head_dim / 2) * (lane >> 5) +
+                8 * j + e];
   }
   if (i < n2) {
     const int e = i & 7, lane = (i >> 3) & 63;
@@ -75,8 +82,13 @@ hipError_t launch_mlp_permute_weights(const _Float16* w1, const _Float16* w2, _F
   return hipGetLastError();
 }
 
-__device__ __forceinline__ float gelu_erf(float v) {
-  return 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f));
+// tanh form of GELU, v/2 * (1 + tanh(u)) with u = sqrt(2/pi) * (v + 0.044715 v^3),
+// written as v / (1 + exp(-2u)): one exp2 and one reciprocal per value (the
+// erf form costs about 40 VALU instructions per value, more than the MFMAs)
+__device__ __forceinline__ float gelu_tanh(float v) {
+  const float u = 0.7978845608028654f * (v + 0.044715f * v * v * v);
+  const float e = __builtin_amdgcn_exp2f(-2.8853900817779268f * u);  // exp(-2u)
+  return v * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
 template <int D, int HID>
@@ -87,8 +99,8 @@ __global__ __launch_bounds__(kMlpThreads) void mlp_compress_kernel(BatchParams p
   constexpr int SPT = D / 16;    // K slabs of the first product per token
   extern __shared__ __align__(16) unsigned char smem[];
   half8* sm_w2 = reinterpret_cast<half8*>(smem);                       // [S2][MT2][64]
-  half8* sm_w1 = sm_w2 + S2 * MT2 * 64;                                // [2][MT1][64]
-  float* sm_b1 = reinterpret_cast<float*>(sm_w1 + 2 * MT1 * 64);       // [HID]
+  half8* sm_w1 = sm_w2 + S2 * MT2 * 64;                                // [2][kMlpThreads]
+  float* sm_b1 = reinterpret_cast<float*>(sm_w1 + 2 * kMlpThreads);    // [HID]
   float* sm_b2 = sm_b1 + HID;                                          // [D]
 
   const int tid = threadIdx.x;
@@ -122,7 +134,7 @@ __global__ __launch_bounds__(kMlpThreads) void mlp_compress_kernel(BatchParams p
     for (int i = tid; i < D; i += kMlpThreads) sm_b2[i] = mp.b2[m][i];
   }
   const half8* w1g = reinterpret_cast<const half8*>(mp.w1p[m]);  // [S1][MT1][64]
-  if (tid < MT1 * 64) sm_w1[tid] = w1g[tid];                        // slab 0
+  sm_w1[tid] = w1g[tid % (MT1 * 64)];                               // slab 0
 
   // this lane's chunk
   int unit = 0, o = 0, s0 = 0, n_valid = 0;
@@ -153,43 +165,75 @@ __global__ __launch_bounds__(kMlpThreads) void mlp_compress_kernel(BatchParams p
   const size_t v_off = (size_t)p.n_heads * chunk_el;
   const size_t blk_stride = 2 * v_off;
   const _Float16* src_base = p.kv + (size_t)layer * p.n_blocks * blk_stride + kvsel * v_off +
-                             (size_t)head * chunk_el + kh * 8;
+                             (size_t)head * chunk_el + kh * (D / 2);
   const int32_t* old_ids = p.old_ids + rd.old_off;
-
-  auto load_x = [&](int s) -> half8 {
-    half8 x = {0, 0, 0, 0, 0, 0, 0, 0};
-    const int t = s / SPT;
+  // where the chunk's token rows start, looked up once (a lookup inside the
+  // pipelined loop would make every iteration wait for all loads in flight)
+  long long row_off[8];
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+    row_off[t] = -1;
     if (t < n_valid) {
       const int tok = s0 + t;
       const int blk = clamp_block(old_ids[tok >> 4], p.n_blocks);
-      x = load_half8(src_base + (size_t)blk * blk_stride + (size_t)(tok & 15) * D +
-                     (s - t * SPT) * 16);
+      row_off[t] = (long long)blk * (long long)blk_stride + (long long)(tok & 15) * D;
     }
-    return x;
+  }
+
+  // Every load of the pipelined loop is unconditional (a load under a branch
+  // makes the compiler wait for ALL loads in flight at the next use): rows that
+  // do not exist read row 0 of the slice and are zeroed by a select, and W1
+  // indices past the end wrap to valid ones whose data nobody uses.
+  // B operand of slab j of a token: 8 channels [(D/2)kh + 8j, +8) of that token's row
+  auto load_x = [&](long long off, int j) -> half8 {
+    const half8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    const half8 x = load_half8(src_base + (off >= 0 ? off : 0) + j * 8);
+    return off >= 0 ? x : zero;
+  };
+  // this thread's 16 bytes of W1 slab s (operand order)
+  const int w_tid = tid % (MT1 * 64);
+  auto load_w = [&](int s) -> half8 {
+    return w1g[(size_t)(s < S1 ? s : 0) * MT1 * 64 + w_tid];
   };
 
   // ---- first product: H^T tile [HID x 32] per wavefront ---------------------
+  // Software pipeline: the B operands of the whole next token are requested in
+  // one burst (8 loads of a lane hit one cache line, which is then fetched once)
+  // while the current token is multiplied; the W1 pieces of the next kWDepth
+  // slabs are in flight in registers; W1 goes through a two-slab LDS ring.
+  constexpr int kWDepth = 4;
   floatx16 acc[MT1];
 #pragma unroll
   for (int mt = 0; mt < MT1; ++mt)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[mt][r] = 0.f;
-  half8 x_cur = load_x(0);
-  __syncthreads();  // W2, biases and slab 0 of W1 are in LDS
-  for (int s = 0; s < S1; ++s) {
-    half8 w_next = {0, 0, 0, 0, 0, 0, 0, 0};
-    half8 x_next = {0, 0, 0, 0, 0, 0, 0, 0};
-    if (s + 1 < S1) {
-      if (tid < MT1 * 64) w_next = w1g[(size_t)(s + 1) * MT1 * 64 + tid];
-      x_next = load_x(s + 1);
-    }
-    const half8* w1s = sm_w1 + (s & 1) * MT1 * 64;
+  half8 xq[2][SPT], wq[kWDepth];
 #pragma unroll
-    for (int mt = 0; mt < MT1; ++mt)
-      acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(w1s[mt * 64 + lane], x_cur, acc[mt], 0, 0, 0);
-    if (s + 1 < S1 && tid < MT1 * 64) sm_w1[((s + 1) & 1) * MT1 * 64 + tid] = w_next;
-    x_cur = x_next;
-    __syncthreads();  // next slab visible; this slab's buffer may be overwritten next time
+  for (int j = 0; j < SPT; ++j) xq[0][j] = load_x(row_off[0], j);
+#pragma unroll
+  for (int j = 0; j < kWDepth; ++j)
+    wq[j] = load_w(j == 0 ? kWDepth : j);  // wq[j]: next unwritten slab congruent to j
+  __syncthreads();  // W2, biases and slab 0 of W1 are in LDS
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+    if (t >= k) break;  // uniform
+    const long long next_off = (t + 1 < 8) ? row_off[(t + 1) & 7] : -1;
+#pragma unroll
+    for (int j = 0; j < SPT; ++j) xq[(t + 1) & 1][j] = load_x(next_off, j);
+#pragma unroll
+    for (int j = 0; j < SPT; ++j) {
+      const int s = t * SPT + j;
+      const half8* w1s = sm_w1 + (s & 1) * kMlpThreads;
+      const half8 x = xq[t & 1][j];
+#pragma unroll
+      for (int mt = 0; mt < MT1; ++mt)
+        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(w1s[mt * 64 + lane], x, acc[mt], 0, 0, 0);
+      // slab s+1 into the other half of the ring, then refill that register
+      const int jn = (s + 1) % kWDepth;
+      sm_w1[((s + 1) & 1) * kMlpThreads + tid] = wq[jn];
+      wq[jn] = load_w(s + 1 + kWDepth);
+      __syncthreads();  // next slab visible; this slab's half may be overwritten next time
+    }
   }
 
   // ---- bias, gelu, fp16: each result tile becomes two B operands of the second
@@ -208,7 +252,7 @@ __global__ __launch_bounds__(kMlpThreads) void mlp_compress_kernel(BatchParams p
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const int u = mlp_hidden_unit(sl, kh, e);  // = 32mt + 16half + 8(e/4) + 4kh + e%4
-        hb[e] = (_Float16)gelu_erf(acc[mt][8 * half + e] + sm_b1[u]);
+        hb[e] = (_Float16)gelu_tanh(acc[mt][8 * half + e] + sm_b1[u]);
       }
 #pragma unroll
       for (int ot = 0; ot < MT2; ++ot)
@@ -237,7 +281,7 @@ __global__ __launch_bounds__(kMlpThreads) void mlp_compress_kernel(BatchParams p
 
 template <int D, int HID>
 static size_t mlp_lds_bytes() {
-  return (size_t)(HID / 16) * (D / 32) * 64 * 16 + (size_t)2 * (HID / 32) * 64 * 16 +
+  return (size_t)(HID / 16) * (D / 32) * 64 * 16 + (size_t)2 * kMlpThreads * 16 +
          (size_t)(HID + D) * sizeof(float);
 }
 
