@@ -183,8 +183,7 @@ int fc_pool_destroy(fc_pool* p) {
   if (p->team_stats) (void)hipFree(p->team_stats);
   if (p->error_flag) (void)hipFree(p->error_flag);
   for (int m = 0; m < 2; ++m) {
-    if (p->mlp_w1p[m]) (void)hipFree(p->mlp_w1p[m]);
-    if (p->mlp_w2p[m]) (void)hipFree(p->mlp_w2p[m]);
+    if (p->mlp_w1p[m]) (void)hipFree(p->mlp_w1p[m]);  // w2p lies in the same allocation
     if (p->mlp_b1[m]) (void)hipFree(p->mlp_b1[m]);
     if (p->mlp_b2[m]) (void)hipFree(p->mlp_b2[m]);
   }
@@ -569,8 +568,7 @@ int fc_mlp_set_weights(fc_pool* p, const fc_mlp_weights* w, void* stream_) {
   const size_t n1 = mlp_w1p_elems(p->head_dim, w->hidden, w->k);
   const size_t n2 = mlp_w2p_elems(p->head_dim, w->hidden);
   for (int m = 0; m < 2; ++m) {
-    if (p->mlp_w1p[m]) FC_HIP(hipFree(p->mlp_w1p[m]));
-    if (p->mlp_w2p[m]) FC_HIP(hipFree(p->mlp_w2p[m]));
+    if (p->mlp_w1p[m]) FC_HIP(hipFree(p->mlp_w1p[m]));  // w2p lies in the same allocation
     if (p->mlp_b1[m]) FC_HIP(hipFree(p->mlp_b1[m]));
     if (p->mlp_b2[m]) FC_HIP(hipFree(p->mlp_b2[m]));
     p->mlp_w1p[m] = p->mlp_w2p[m] = nullptr;
@@ -578,8 +576,9 @@ int fc_mlp_set_weights(fc_pool* p, const fc_mlp_weights* w, void* stream_) {
   }
   p->mlp_k = p->mlp_hidden = 0;
   for (int m = 0; m < 2; ++m) {
-    FC_HIP(hipMalloc(reinterpret_cast<void**>(&p->mlp_w1p[m]), n1 * sizeof(_Float16)));
-    FC_HIP(hipMalloc(reinterpret_cast<void**>(&p->mlp_w2p[m]), n2 * sizeof(_Float16)));
+    // one allocation: the kernel streams W1 and then W2 through the same ring
+    FC_HIP(hipMalloc(reinterpret_cast<void**>(&p->mlp_w1p[m]), (n1 + n2) * sizeof(_Float16)));
+    p->mlp_w2p[m] = p->mlp_w1p[m] + n1;
     FC_HIP(hipMalloc(reinterpret_cast<void**>(&p->mlp_b1[m]), (size_t)w->hidden * sizeof(float)));
     FC_HIP(hipMalloc(reinterpret_cast<void**>(&p->mlp_b2[m]), (size_t)p->head_dim * sizeof(float)));
     FC_HIP(launch_mlp_permute_weights(static_cast<const _Float16*>(w->w1[m]),
@@ -609,6 +608,7 @@ int fc_compress_batch_mlp(fc_pool* p, int32_t* dev_block_tables, int max_blocks_
   if (max_blocks_per_req < 1) return fail(FC_EINVAL, "max_blocks_per_req < 1");
   const int k = p->mlp_k;
   const int n_units = p->n_layers * p->n_heads * 2;
+  const int tile_rows = mlp_rows_per_tile(p->mlp_hidden);
   std::vector<ReqDesc> descs;
   std::vector<MlpJob> jobs;
   int total_new = 0, total_old = 0;
@@ -648,7 +648,7 @@ int fc_compress_batch_mlp(fc_pool* p, int32_t* dev_block_tables, int max_blocks_
       j.modality = m;
       j.chunks = per_modality[m];
       j.tile_start = (int)n_tiles;
-      n_tiles += ((long long)n_units * per_modality[m] + 255) / 256;
+      n_tiles += ((long long)n_units * per_modality[m] + tile_rows - 1) / tile_rows;
       jobs.push_back(j);
     }
     descs.push_back(d);
@@ -696,6 +696,12 @@ int fc_compress_batch_mlp(fc_pool* p, int32_t* dev_block_tables, int max_blocks_
   mp.jobs = reinterpret_cast<const MlpJob*>(p->dev_meta + desc_bytes);
   mp.n_jobs = (int)jobs.size();
   mp.n_tiles = (int)n_tiles;
+  {
+    int dev = 0, cus = 0;
+    FC_HIP(hipGetDevice(&dev));
+    FC_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    mp.max_grid = std::max(cus, 1) * mlp_workgroups_per_cu();
+  }
   mp.k = k;
   mp.hidden = p->mlp_hidden;
   for (int m = 0; m < 2; ++m) {

@@ -38,14 +38,15 @@ struct MlpJob {
   int32_t desc;        // index into descs
   int32_t modality;    // 0 text, 1 image
   int32_t chunks;      // chunks of this modality in the request
-  int32_t tile_start;  // first 256-row tile of this job
+  int32_t tile_start;  // first tile of this job (mlp_rows_per_tile rows each)
 };
 
 struct MlpParams {
   const MlpJob* jobs;
   int32_t n_jobs, n_tiles;
+  int32_t max_grid;    // workgroups to launch at most (as many as are resident)
   int32_t k, hidden;
-  // weights in operand order, index 0 text / 1 image
+  // weights in operand order, index 0 text / 1 image; w2p[m] starts where w1p[m] ends
   const _Float16* w1p[2];
   const _Float16* w2p[2];
   const float* b1[2];
@@ -125,6 +126,8 @@ hipError_t kernels_one_time_setup();
 hipError_t mlp_one_time_setup();
 size_t mlp_w1p_elems(int head_dim, int hidden, int k);
 size_t mlp_w2p_elems(int head_dim, int hidden);
+int mlp_rows_per_tile(int hidden);   // rows (units x chunks) one workgroup takes at a time
+int mlp_workgroups_per_cu();
 hipError_t launch_mlp_permute_weights(const _Float16* w1, const _Float16* w2, _Float16* w1p,
                                       _Float16* w2p, int head_dim, int hidden, int k,
                                       hipStream_t s);

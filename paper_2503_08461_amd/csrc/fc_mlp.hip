@@ -12,14 +12,16 @@
 //     block, no staging;
 //   * the A operand (weights) is pre-permuted once into operand order, so a
 //     16-wide K slab of W1 is one contiguous 8 KiB piece that the workgroup
-//     double-buffers through LDS, and W2 (64 KiB) stays in LDS;
+//     pulls through a ring in LDS, and W2 (64 KiB) stays in LDS;
 //   * the 32x32 result tile of the first product already has the chunk on the
 //     lane, which is what the B operand of the second product needs; only the
 //     order of the contraction index differs, and that is folded into the
 //     pre-permutation of W2.  The hidden activations therefore never leave
 //     registers.
-// A workgroup of 8 wavefronts handles 256 rows (row = (layer, head, K|V) x
-// chunk of one request and one modality), 32 per wavefront.
+// A workgroup handles tiles of 256 rows (row = (layer, head, K|V) x chunk of
+// one request and one modality), 32 NT per wavefront; the kernel
+// is persistent (one workgroup per CU walks the tile list) so that W2 is loaded
+// into LDS once per modality change rather than once per tile.
 
 #include "fc_device.h"
 
@@ -30,8 +32,12 @@ namespace fc {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 
-static constexpr int kMlpThreads = 512;
 static constexpr int kMlpRowsPerTile = 256;
+// threads of a workgroup when a wavefront takes NT column tiles of 32 chunks
+constexpr int mlp_threads(int nt) { return kMlpRowsPerTile / (32 * nt) * 64; }
+
+int mlp_rows_per_tile(int) { return kMlpRowsPerTile; }
+int mlp_workgroups_per_cu() { return 1; }
 
 // hidden unit that sits at contraction position (slab sl, lane half kh, element e)
 // of the second product, given how the first product leaves its result in
@@ -44,10 +50,9 @@ size_t mlp_w1p_elems(int head_dim, int hidden, int k) { return (size_t)hidden * 
 size_t mlp_w2p_elems(int head_dim, int hidden) { return (size_t)hidden * head_dim; }
 
 // Contraction position (slab s = t*SPT + j, lane half kh, element e) of the
-// first product is channel (D/2)*kh + 8*j + e of token t of the chunk: each
-// lane half owns one contiguous half row (128 B at D = 128), so a lane's loads
-// for one token fall into a single cache line.
-// w1p[s][mt][lane][e] = w1[mt*32 + lane%32][t*D + (D/2)*(lane/32) + 8*j + e]
+// first product is channel 16*j + 8*kh + e of token t of the chunk: the two
+// lane halves read neighbouring 16-byte pieces of a row.
+// w1p[s][mt][lane][e] = w1[mt*32 + lane%32][t*D + 16*j + 8*(lane/32) + e]
 // w2p[sl][ot][lane][e] = w2[ot*32 + lane%32][mlp_hidden_unit(sl, lane/32, e)]
 __global__ void mlp_permute_kernel(const _Float16* w1, const _Float16* w2, _Float16* w1p,
                                    _Float16* w2p, int head_dim, int hidden, int k) {
@@ -61,8 +66,8 @@ __global__ void mlp_permute_kernel(const _Float16* w1, const _Float16* w2, _Floa
     const int mt = rest % mt1, s = rest / mt1;
     const int spt = head_dim / 16;
     const int t = s / spt, j = s - t * spt;
-    w1p[i] = w1[(size_t)(mt * 32 + (lane & 31)) * kd + t * head_dim + (head_dim / 2) * (lane >> 5) +
-                8 * j + e];
+    w1p[i] = w1[(size_t)(mt * 32 + (lane & 31)) * kd + t * head_dim + 16 * j + 8 * (lane >> 5) +
+                e];
   }
   if (i < n2) {
     const int e = i & 7, lane = (i >> 3) & 63;
@@ -91,205 +96,301 @@ __device__ __forceinline__ float gelu_tanh(float v) {
   return v * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
-template <int D, int HID>
-__global__ __launch_bounds__(kMlpThreads) void mlp_compress_kernel(BatchParams p, MlpParams mp) {
-  constexpr int MT1 = HID / 32;  // 32-row tiles of hidden units
-  constexpr int MT2 = D / 32;    // 32-row tiles of output channels
-  constexpr int S2 = HID / 16;   // K slabs of the second product
-  constexpr int SPT = D / 16;    // K slabs of the first product per token
+// what the lanes of a chunk read for the tokens its segment does not have
+__device__ __align__(256) _Float16 g_zero_row[128];
+
+template <int D, int HID, int NT>
+__global__ __launch_bounds__(mlp_threads(NT), 1) void mlp_compress_kernel(BatchParams p,
+                                                                      MlpParams mp) {
+  constexpr int MT1 = HID / 32;               // 32-row tiles of hidden units
+  constexpr int MT2 = D / 32;                 // 32-row tiles of output channels
+  constexpr int S2 = HID / 16;                // K slabs of the second product
+  constexpr int SPT = D / 16;                 // K slabs of the first product per token
+  constexpr int GPT = 4;                      // W1 groups per token
+  constexpr int GS = SPT / GPT;               // K slabs per group
+  constexpr int GO = GS * MT1;                // A operands (W1 tiles) per group
+  constexpr int kMlpThreads = mlp_threads(NT);  // NT column tiles (32 chunks each) per wavefront
+  constexpr int PPG = GO * 64 / kMlpThreads;  // 16-byte pieces of a W1 group per thread
+  constexpr int AR = 4;                       // A operands in flight from LDS
+  constexpr int XR = NT == 1 ? 2 : 1;         // tokens of B operands held in registers
+  constexpr int RT = 8 + XR;                  // rows of the per-lane token table
+  static_assert(GO % AR == 0 && PPG >= 1, "tiling");
   extern __shared__ __align__(16) unsigned char smem[];
-  half8* sm_w2 = reinterpret_cast<half8*>(smem);                       // [S2][MT2][64]
-  half8* sm_w1 = sm_w2 + S2 * MT2 * 64;                                // [2][kMlpThreads]
-  float* sm_b1 = reinterpret_cast<float*>(sm_w1 + 2 * kMlpThreads);    // [HID]
-  float* sm_b2 = sm_b1 + HID;                                          // [D]
+  // the W1 ring comes first so that every read of it is one base register
+  // plus an immediate offset (the offset field holds less than 64 KB)
+  half8* sm_w1 = reinterpret_cast<half8*>(smem);                     // [GPT groups][GO][64]
+  half8* sm_w2 = sm_w1 + GPT * GO * 64;                              // [S2][MT2][64]
+  float* sm_b1 = reinterpret_cast<float*>(sm_w2 + S2 * MT2 * 64);    // [HID]
+  float* sm_b2 = sm_b1 + HID;                                        // [D]
+  int* sm_rows = reinterpret_cast<int*>(sm_b2 + D);                  // [RT][NT][threads]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const int col = lane & 31;  // chunk within the wavefront's 32
+  const int col = lane & 31;  // chunk within a 32-wide column tile
   const int kh = lane >> 5;   // which 8 of the slab's 16 contraction positions
-
-  // which job does this tile belong to (jobs are sorted by tile_start)
-  int lo = 0, hi = mp.n_jobs - 1;
-  while (lo < hi) {
-    const int mid = (lo + hi + 1) >> 1;
-    if (mp.jobs[mid].tile_start <= (int)blockIdx.x) lo = mid; else hi = mid - 1;
-  }
-  const MlpJob job = mp.jobs[lo];
-  const ReqDesc rd = p.descs[job.desc];
-  const int m = job.modality;
-  const int n_units = p.n_layers * p.n_heads * 2;
-  const long long n_rows = (long long)n_units * job.chunks;
-  const long long row = (long long)((int)blockIdx.x - job.tile_start) * kMlpRowsPerTile +
-                        wave * 32 + col;
-  const bool valid = row < n_rows;
   const int k = mp.k;
   const int S1 = k * SPT;
-
-  // weights of this modality: W2 and the biases stay in LDS for the whole tile
-  {
-    const half8* w2g = reinterpret_cast<const half8*>(mp.w2p[m]);
-    for (int i = tid; i < S2 * MT2 * 64; i += kMlpThreads) sm_w2[i] = w2g[i];
-    for (int i = tid; i < HID; i += kMlpThreads) sm_b1[i] = mp.b1[m][i];
-    for (int i = tid; i < D; i += kMlpThreads) sm_b2[i] = mp.b2[m][i];
-  }
-  const half8* w1g = reinterpret_cast<const half8*>(mp.w1p[m]);  // [S1][MT1][64]
-  sm_w1[tid] = w1g[tid % (MT1 * 64)];                               // slab 0
-
-  // this lane's chunk
-  int unit = 0, o = 0, s0 = 0, n_valid = 0;
-  if (valid) {
-    unit = (int)(row / job.chunks);
-    const int cl = (int)(row - (long long)unit * job.chunks);
-    int seg_end;
-    if (m == 1) {
-      o = rd.chunks_text0 + cl;
-      s0 = rd.img_begin + cl * k;
-      seg_end = rd.img_end;
-    } else if (cl < rd.chunks_text0) {
-      o = cl;
-      s0 = cl * k;
-      seg_end = rd.img_begin;
-    } else {
-      o = rd.chunks_text0 + rd.chunks_image + (cl - rd.chunks_text0);
-      s0 = rd.img_end + (cl - rd.chunks_text0) * k;
-      seg_end = rd.seq_len;
-    }
-    n_valid = min(k, seg_end - s0);
-  }
-  const int kvsel = unit & 1;
-  const int lh = unit >> 1;
-  const int layer = lh / p.n_heads;
-  const int head = lh - layer * p.n_heads;
+  const int n_units = p.n_layers * p.n_heads * 2;
   const size_t chunk_el = (size_t)16 * D;
   const size_t v_off = (size_t)p.n_heads * chunk_el;
   const size_t blk_stride = 2 * v_off;
-  const _Float16* src_base = p.kv + (size_t)layer * p.n_blocks * blk_stride + kvsel * v_off +
-                             (size_t)head * chunk_el + kh * (D / 2);
-  const int32_t* old_ids = p.old_ids + rd.old_off;
-  // where the chunk's token rows start, looked up once (a lookup inside the
-  // pipelined loop would make every iteration wait for all loads in flight)
-  long long row_off[8];
-#pragma unroll
-  for (int t = 0; t < 8; ++t) {
-    row_off[t] = -1;
-    if (t < n_valid) {
-      const int tok = s0 + t;
-      const int blk = clamp_block(old_ids[tok >> 4], p.n_blocks);
-      row_off[t] = (long long)blk * (long long)blk_stride + (long long)(tok & 15) * D;
+  const int blk_rows = 2 * p.n_heads * 16;  // blk_stride in rows of D elements
+
+  // persistent: a workgroup walks tiles blockIdx.x, blockIdx.x + gridDim.x, ...
+  int cur_m = -1;
+  int cur_job = 0, next_start = 0;  // next_start = 0 forces the first lookup
+  MlpJob job = mp.jobs[0];
+  ReqDesc rd = p.descs[job.desc];
+  for (int tile = blockIdx.x; tile < mp.n_tiles; tile += gridDim.x) {
+    // which job does this tile belong to: jobs are sorted by tile_start and a
+    // workgroup visits tiles in increasing order, so a running index suffices
+    if (tile >= next_start) {  // uniform
+      while (cur_job + 1 < mp.n_jobs && mp.jobs[cur_job + 1].tile_start <= tile) ++cur_job;
+      job = mp.jobs[cur_job];
+      rd = p.descs[job.desc];
+      next_start = (cur_job + 1 < mp.n_jobs) ? mp.jobs[cur_job + 1].tile_start : 0x7fffffff;
     }
-  }
+    const int m = job.modality;
+    const long long n_rows = (long long)n_units * job.chunks;
 
-  // Every load of the pipelined loop is unconditional (a load under a branch
-  // makes the compiler wait for ALL loads in flight at the next use): rows that
-  // do not exist read row 0 of the slice and are zeroed by a select, and W1
-  // indices past the end wrap to valid ones whose data nobody uses.
-  // B operand of slab j of a token: 8 channels [(D/2)kh + 8j, +8) of that token's row
-  auto load_x = [&](long long off, int j) -> half8 {
-    const half8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-    const half8 x = load_half8(src_base + (off >= 0 ? off : 0) + j * 8);
-    return off >= 0 ? x : zero;
-  };
-  // this thread's 16 bytes of W1 slab s (operand order)
-  const int w_tid = tid % (MT1 * 64);
-  auto load_w = [&](int s) -> half8 {
-    return w1g[(size_t)(s < S1 ? s : 0) * MT1 * 64 + w_tid];
-  };
-
-  // ---- first product: H^T tile [HID x 32] per wavefront ---------------------
-  // Software pipeline: the B operands of the whole next token are requested in
-  // one burst (8 loads of a lane hit one cache line, which is then fetched once)
-  // while the current token is multiplied; the W1 pieces of the next kWDepth
-  // slabs are in flight in registers; W1 goes through a two-slab LDS ring.
-  constexpr int kWDepth = 4;
-  floatx16 acc[MT1];
-#pragma unroll
-  for (int mt = 0; mt < MT1; ++mt)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[mt][r] = 0.f;
-  half8 xq[2][SPT], wq[kWDepth];
-#pragma unroll
-  for (int j = 0; j < SPT; ++j) xq[0][j] = load_x(row_off[0], j);
-#pragma unroll
-  for (int j = 0; j < kWDepth; ++j)
-    wq[j] = load_w(j == 0 ? kWDepth : j);  // wq[j]: next unwritten slab congruent to j
-  __syncthreads();  // W2, biases and slab 0 of W1 are in LDS
-#pragma unroll
-  for (int t = 0; t < 8; ++t) {
-    if (t >= k) break;  // uniform
-    const long long next_off = (t + 1 < 8) ? row_off[(t + 1) & 7] : -1;
-#pragma unroll
-    for (int j = 0; j < SPT; ++j) xq[(t + 1) & 1][j] = load_x(next_off, j);
-#pragma unroll
-    for (int j = 0; j < SPT; ++j) {
-      const int s = t * SPT + j;
-      const half8* w1s = sm_w1 + (s & 1) * kMlpThreads;
-      const half8 x = xq[t & 1][j];
-#pragma unroll
-      for (int mt = 0; mt < MT1; ++mt)
-        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(w1s[mt * 64 + lane], x, acc[mt], 0, 0, 0);
-      // slab s+1 into the other half of the ring, then refill that register
-      const int jn = (s + 1) % kWDepth;
-      sm_w1[((s + 1) & 1) * kMlpThreads + tid] = wq[jn];
-      wq[jn] = load_w(s + 1 + kWDepth);
-      __syncthreads();  // next slab visible; this slab's half may be overwritten next time
+    // weights of this modality: W2 and the biases stay in LDS across tiles and
+    // are only reloaded when the modality changes
+    if (m != cur_m) {  // uniform
+      __syncthreads();  // the previous tile may still be reading them
+      const half8* w2g = reinterpret_cast<const half8*>(mp.w2p[m]);
+      for (int i = tid; i < S2 * MT2 * 64; i += kMlpThreads) sm_w2[i] = w2g[i];
+      for (int i = tid; i < HID; i += kMlpThreads) sm_b1[i] = mp.b1[m][i];
+      for (int i = tid; i < D; i += kMlpThreads) sm_b2[i] = mp.b2[m][i];
+      cur_m = m;
     }
-  }
+    const half8* w1g = reinterpret_cast<const half8*>(mp.w1p[m]);  // [S1][MT1][64]
+    const int32_t* old_ids = p.old_ids + rd.old_off;
 
-  // ---- bias, gelu, fp16: each result tile becomes two B operands of the second
-  // product, Y^T tile [D x 32], and is consumed at once (keeps registers down)
-  floatx16 acc2[MT2];
+    // this lane's two chunks (one per column tile): the pool rows of their
+    // tokens (units of D elements, -1 = no such row) and where they start
+    int rows[NT];
+    const _Float16* src_base[NT];
 #pragma unroll
-  for (int ot = 0; ot < MT2; ++ot)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc2[ot][r] = 0.f;
-#pragma unroll
-  for (int mt = 0; mt < MT1; ++mt) {
-#pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      const int sl = 2 * mt + half;
-      half8 hb;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int u = mlp_hidden_unit(sl, kh, e);  // = 32mt + 16half + 8(e/4) + 4kh + e%4
-        hb[e] = (_Float16)gelu_tanh(acc[mt][8 * half + e] + sm_b1[u]);
+    for (int nt = 0; nt < NT; ++nt) {
+      const long long row = (long long)(tile - job.tile_start) * kMlpRowsPerTile +
+                            wave * (32 * NT) + nt * 32 + col;
+      rows[nt] = row < n_rows ? (int)row : -1;
+      int unit = 0, s0 = 0, n_valid = 0;
+      if (row < n_rows) {
+        unit = (int)(row / job.chunks);
+        const int cl = (int)(row - (long long)unit * job.chunks);
+        int seg_end;
+        if (m == 1) {
+          s0 = rd.img_begin + cl * k;
+          seg_end = rd.img_end;
+        } else if (cl < rd.chunks_text0) {
+          s0 = cl * k;
+          seg_end = rd.img_begin;
+        } else {
+          s0 = rd.img_end + (cl - rd.chunks_text0) * k;
+          seg_end = rd.seq_len;
+        }
+        n_valid = min(k, seg_end - s0);
       }
+      const int lh = unit >> 1;
+      const int layer = lh / p.n_heads;
+      src_base[nt] = p.kv + (size_t)layer * p.n_blocks * blk_stride + (unit & 1) * v_off +
+                     (size_t)(lh - layer * p.n_heads) * chunk_el + kh * 8;
+      // looked up once: a lookup inside the pipelined loop would make every
+      // iteration wait for all loads in flight
+      // (kept in LDS, each lane reading back only what it wrote: registers are
+      // needed for data in flight)
 #pragma unroll
-      for (int ot = 0; ot < MT2; ++ot)
-        acc2[ot] = __builtin_amdgcn_mfma_f32_32x32x16_f16(sm_w2[(sl * MT2 + ot) * 64 + lane], hb,
-                                                          acc2[ot], 0, 0, 0);
+      for (int t = 0; t < RT; ++t) {
+        int ri = -1;
+        if (t < n_valid) {
+          const int tok = s0 + t;
+          ri = clamp_block(old_ids[tok >> 4], p.n_blocks) * blk_rows + (tok & 15);
+        }
+        sm_rows[(t * NT + nt) * kMlpThreads + tid] = ri;
+      }
     }
-  }
+    auto row_of = [&](int nt, int t) -> int { return sm_rows[(t * NT + nt) * kMlpThreads + tid]; };
 
-  // ---- bias, fp16, store the row into the request's new blocks ---------------
-  if (valid) {
-    const int nblk = clamp_block(p.new_ids[rd.new_off + (o >> 4)], p.n_blocks);
-    _Float16* dst = p.kv + (size_t)layer * p.n_blocks * blk_stride + (size_t)nblk * blk_stride +
-                    kvsel * v_off + (size_t)head * chunk_el + (size_t)(o & 15) * D;
+    // Every load of the pipelined loop is unconditional (a load under a branch
+    // makes the compiler wait for ALL loads in flight at the next use): a token
+    // that does not exist (past the end of a chunk's segment, or a lane without
+    // a chunk) reads a row of zeros instead, and W1 groups past the end wrap to
+    // group 0, whose copy nobody uses.
+    // B operand of slab j of a token: 8 channels [(D/2)kh + 8j, +8) of its row
+    auto load_x = [&](int nt, int ri, int j) -> half8 {
+      const _Float16* row = ri >= 0 ? src_base[nt] + (size_t)ri * D : g_zero_row + kh * 8;
+      return load_half8(row + j * 16);
+    };
+    // piece i of this thread's share of W1 group g (operand order, contiguous)
+    auto load_w = [&](int g, int i) -> half8 {
+      return w1g[(size_t)(g < k * GPT ? g : 0) * GO * 64 + i * kMlpThreads + tid];
+    };
+
+    // ---- first product: H^T tile [HID x 64] per wavefront -------------------
+    // Each W1 operand read from LDS feeds two MFMAs (two column tiles), which
+    // halves the LDS traffic per flop.  The wavefront runs alone on its SIMD,
+    // so latency is hidden by software pipelining: W1 moves through registers
+    // (two groups in flight) into a ring of GPT groups in LDS, one barrier per
+    // group; a group is visible one barrier before its turn, so A operands are
+    // read AR ahead of their use, across group boundaries.  A scattered pool
+    // row takes microseconds to arrive (address translation, HBM) and loads
+    // complete in order, so every load waits for the slowest one before it:
+    // the B operands of XR tokens are held, and those of a finished group are
+    // replaced at once by the same slabs XR tokens on.
+    floatx16 acc[MT1][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT1; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[mt][nt][r] = 0.f;
+    half8 xq[XR][NT][SPT], wq[2][PPG], ar[AR];
+#pragma unroll
+    for (int u = 0; u < XR; ++u)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const int ri = row_of(nt, u);
+#pragma unroll
+        for (int j = 0; j < SPT; ++j) xq[u][nt][j] = load_x(nt, ri, j);
+      }
+    // groups 0 and 1 go straight to LDS; wq[i] holds the next unwritten group congruent to i
+#pragma unroll
+    for (int g = 0; g < 2; ++g)
+#pragma unroll
+      for (int i = 0; i < PPG; ++i) sm_w1[g * GO * 64 + i * kMlpThreads + tid] = load_w(g, i);
+#pragma unroll
+    for (int g = 0; g < 2; ++g)
+#pragma unroll
+      for (int i = 0; i < PPG; ++i) wq[g][i] = load_w(2 + g, i);
+    __syncthreads();  // W2, biases and groups 0, 1 of W1 are in LDS
+#pragma unroll
+    for (int n = 0; n < AR; ++n) ar[n] = sm_w1[n * 64 + lane];
+    for (int t0 = 0; t0 < k; t0 += XR) {
+#pragma unroll
+    for (int u = 0; u < XR; ++u) {
+      const int t = t0 + u;
+      if (t >= k) break;  // uniform
+      int ri_new[NT];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) ri_new[nt] = row_of(nt, t + XR);
+#pragma unroll
+      for (int jj = 0; jj < GPT; ++jj) {
+        // group 4t+jj+2 into the ring slot that group 4t+jj-2 left, then refill those registers
+        half8* w1n = sm_w1 + ((jj + 2) % GPT) * GO * 64;
+#pragma unroll
+        for (int i = 0; i < PPG; ++i) {
+          w1n[i * kMlpThreads + tid] = wq[jj % 2][i];
+          wq[jj % 2][i] = load_w(GPT * t + jj + 4, i);
+        }
+        const half8* w1s = sm_w1 + jj * GO * 64;
+        const half8* w1f = sm_w1 + ((jj + 1) % GPT) * GO * 64;  // visible since the last barrier
+#pragma unroll
+        for (int n = 0; n < GO; ++n) {
+          const half8 a = ar[n % AR];
+          const int nn = n + AR;
+          ar[n % AR] = (nn < GO) ? w1s[nn * 64 + lane] : w1f[(nn - GO) * 64 + lane];
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt)
+            acc[n % MT1][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                a, xq[u][nt][GS * jj + n / MT1], acc[n % MT1][nt], 0, 0, 0);
+          // pin the issue order "one LDS read, NT MFMAs": left alone, the
+          // scheduler sinks each read to just before its use
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        // this group's B operands are done: fetch the same slabs XR tokens on
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int h = 0; h < GS; ++h)
+            xq[u][nt][GS * jj + h] = load_x(nt, ri_new[nt], GS * jj + h);
+        __syncthreads();  // the new group is visible; nobody reads this one any more
+      }
+    }
+    }
+
+    // ---- bias, gelu, fp16: each result tile becomes two B operands of the
+    // second product, Y^T tile [D x 64], and is consumed at once
+    floatx16 acc2[MT2][NT];
 #pragma unroll
     for (int ot = 0; ot < MT2; ++ot)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int c0 = 32 * ot + 8 * g + 4 * kh;
-        half4 y;
+      for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) y[r] = (_Float16)(acc2[ot][4 * g + r] + sm_b2[c0 + r]);
-        *reinterpret_cast<half4*>(dst + c0) = y;
+        for (int r = 0; r < 16; ++r) acc2[ot][nt][r] = 0.f;
+#pragma unroll
+    for (int mt = 0; mt < MT1; ++mt) {
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        const int sl = 2 * mt + half;
+        half8 hb[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const int u = mlp_hidden_unit(sl, kh, e);  // = 32mt + 16half + 8(e/4) + 4kh + e%4
+            hb[nt][e] = (_Float16)gelu_tanh(acc[mt][nt][8 * half + e] + sm_b1[u]);
+          }
+#pragma unroll
+        for (int ot = 0; ot < MT2; ++ot) {
+          const half8 w = sm_w2[(sl * MT2 + ot) * 64 + lane];
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt)
+            acc2[ot][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(w, hb[nt], acc2[ot][nt], 0, 0, 0);
+        }
       }
+    }
+
+    // ---- bias, fp16, store the rows into the request's new blocks -------------
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      if (rows[nt] >= 0) {
+        const int unit = rows[nt] / job.chunks;
+        const int cl = rows[nt] - unit * job.chunks;
+        const int o = (m == 1) ? rd.chunks_text0 + cl
+                               : (cl < rd.chunks_text0 ? cl : rd.chunks_image + cl);
+        const int lh = unit >> 1;
+        const int layer = lh / p.n_heads;
+        const int nblk = clamp_block(p.new_ids[rd.new_off + (o >> 4)], p.n_blocks);
+        _Float16* dst = p.kv + (size_t)layer * p.n_blocks * blk_stride +
+                        (size_t)nblk * blk_stride + (unit & 1) * v_off +
+                        (size_t)(lh - layer * p.n_heads) * chunk_el + (size_t)(o & 15) * D;
+#pragma unroll
+        for (int ot = 0; ot < MT2; ++ot)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const int c0 = 32 * ot + 8 * g + 4 * kh;
+            half4 y;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) y[r] = (_Float16)(acc2[ot][nt][4 * g + r] + sm_b2[c0 + r]);
+            *reinterpret_cast<half4*>(dst + c0) = y;
+          }
+      }
+    }
   }
 }
 
-template <int D, int HID>
+template <int D, int HID, int NT>
 static size_t mlp_lds_bytes() {
-  return (size_t)(HID / 16) * (D / 32) * 64 * 16 + (size_t)2 * kMlpThreads * 16 +
-         (size_t)(HID + D) * sizeof(float);
+  return (size_t)(HID / 16) * (D / 32) * 64 * 16 + (size_t)(D / 16) * (HID / 32) * 64 * 16 +
+         (size_t)(HID + D) * sizeof(float) + (size_t)(8 + 2) * NT * mlp_threads(NT) * sizeof(int);
 }
+
+// Column tiles per wavefront: with a hidden width of 256 one column tile
+// already needs 128 accumulator registers.
+#ifndef FC_MLP_NT_WIDE
+#define FC_MLP_NT_WIDE 1
+#endif
+template <int HID>
+constexpr int mlp_nt() { return HID >= 256 ? FC_MLP_NT_WIDE : 2; }
 
 template <int D, int HID>
 static hipError_t mlp_setup_one() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_compress_kernel<D, HID>),
+  constexpr int NT = mlp_nt<HID>();
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_compress_kernel<D, HID, NT>),
                              hipFuncAttributeMaxDynamicSharedMemorySize,
-                             (int)mlp_lds_bytes<D, HID>());
+                             (int)mlp_lds_bytes<D, HID, NT>());
 }
 
 hipError_t mlp_one_time_setup() {
@@ -302,7 +403,9 @@ hipError_t mlp_one_time_setup() {
 
 template <int D, int HID>
 static hipError_t mlp_launch_one(const BatchParams& p, const MlpParams& mp, hipStream_t s) {
-  mlp_compress_kernel<D, HID><<<mp.n_tiles, kMlpThreads, mlp_lds_bytes<D, HID>(), s>>>(p, mp);
+  constexpr int NT = mlp_nt<HID>();
+  mlp_compress_kernel<D, HID, NT><<<std::min(mp.n_tiles, mp.max_grid), mlp_threads(NT),
+                                    mlp_lds_bytes<D, HID, NT>(), s>>>(p, mp);
   return hipGetLastError();
 }
 
