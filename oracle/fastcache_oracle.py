@@ -196,13 +196,25 @@ def copy_rows(kv_pool, layer, head, old_row, new_row, kept):
                 kv_pool[layer, old_row[idx // bs], kv, head, idx % bs, :]
 
 
+def per_request(value, n_req):
+    """An int (the same for every request) or a sequence of n_req ints."""
+    if np.ndim(value) == 0:
+        return [int(value)] * n_req
+    assert len(value) == n_req
+    return [int(v) for v in value]
+
+
 def validate_batch(stack, block_tables, seq_lens, window, method, budget,
                    pool_kernel, block_size, in_place=False):
-    """Returns None if the batch is acceptable, else 'EINVAL' / 'ENOMEM'."""
-    if pool_kernel < 1 or pool_kernel % 2 == 0:
-        return "EINVAL"
+    """Returns None if the batch is acceptable, else 'EINVAL' / 'ENOMEM'.
+    window and pool_kernel: one int, or one per request (only looked at for
+    SnapKV requests)."""
+    n_req = len(seq_lens)
+    if np.ndim(pool_kernel) == 0 and (pool_kernel < 1 or pool_kernel % 2 == 0):
+        return "EINVAL"   # one size for the batch: checked whatever the methods
+    window, pool_kernel = per_request(window, n_req), per_request(pool_kernel, n_req)
     need = 0
-    for r in range(len(seq_lens)):
+    for r in range(n_req):
         m, L, B = int(method[r]), int(seq_lens[r]), int(budget[r])
         if m == METHOD_NONE:
             continue
@@ -210,7 +222,9 @@ def validate_batch(stack, block_tables, seq_lens, window, method, budget,
             return "EINVAL"
         if B < 1 or B > L:
             return "EINVAL"
-        if m == METHOD_SNAPKV and (window < 1 or L < window or B < window):
+        if m == METHOD_SNAPKV and (window[r] < 1 or L < window[r] or B < window[r]):
+            return "EINVAL"
+        if m == METHOD_SNAPKV and (pool_kernel[r] < 1 or pool_kernel[r] % 2 == 0):
             return "EINVAL"
         if blocks_for(L, block_size) > block_tables.shape[1]:
             return "EINVAL"
@@ -230,7 +244,10 @@ def compress_batch(kv_pool, stack, block_tables, seq_lens, q_window, window,
     block_tables int32 [n_req][max_blocks], row r valid for ceil(L_r/bs) entries
     seq_lens     int array [n_req], L_r on entry, B_r on exit
     q_window     float16 [n_req][n_layers][n_heads][window][d] (may be None if
-                 no request uses SnapKV)
+                 no request uses SnapKV); with per-request windows, a list of
+                 n_req arrays [n_layers][n_heads][window_r][d] (None where the
+                 request does not use SnapKV)
+    window, pool_kernel  one int for the batch, or int arrays [n_req]
     method, budget  int arrays [n_req]
     n_sink       attention sinks kept by METHOD_STREAMING requests
     in_place     compact inside the request's own blocks: the kept rows move to
@@ -255,6 +272,7 @@ def compress_batch(kv_pool, stack, block_tables, seq_lens, q_window, window,
         return status, None, None
     if scale is None or scale <= 0:
         scale = 1.0 / np.sqrt(d)
+    pool_kernel = per_request(pool_kernel, n_req)
 
     # 1. score and select, every unit independently
     scores = [None] * n_req
@@ -268,9 +286,9 @@ def compress_batch(kv_pool, stack, block_tables, seq_lens, q_window, window,
         kept[r] = np.empty((n_layers, n_heads, B), dtype=np.int32)
         for l in range(n_layers):
             for h in range(n_heads):
-                qw = q_window[r, l, h] if m == METHOD_SNAPKV else None
+                qw = q_window[r][l, h] if m == METHOD_SNAPKV else None
                 s = unit_scores(kv_pool, l, block_tables[r], h, L, m, qw, scale,
-                                pool_kernel, B, n_sink)
+                                pool_kernel[r], B, n_sink)
                 scores[r][l, h] = s
                 if kept_override is not None:
                     kept[r][l, h] = kept_override[r][l, h]

@@ -447,3 +447,77 @@ def test_in_place_compaction_matches_fresh_blocks_logically():
                              [fo.METHOD_KNORM], [20])[0] == "ENOMEM"
     assert fo.compress_batch(kv_c, st_c, bt_c, np.array([24], np.int32), None, 0,
                              [fo.METHOD_KNORM], [20], in_place=True)[0] is None
+
+
+# ---------------------------------------------------------------- per-request window / pool kernel
+
+def test_per_request_window_and_pool_kernel_equal_separate_uniform_calls():
+    """A batch whose requests have their own observation window and pooling
+    width must score and keep exactly what each request gets when it is
+    compressed alone with its own sizes (units are independent; only the pool
+    bookkeeping couples requests, and that depends on budgets alone), and a
+    window of 1 with pooling width 1 must reduce to the plain softmax of the
+    last query."""
+    rng = np.random.default_rng(21)
+    n_layers, n_heads, bs, d, nb = 2, 2, 4, 8, 96
+    kv = _random_pool(rng, n_layers, nb, n_heads, bs, d)
+    lens0 = np.array([37, 18, 25, 30], dtype=np.int32)
+    windows = [6, 1, 4, 9]
+    pools = [5, 1, 3, 7]
+    method = np.array([fo.METHOD_SNAPKV, fo.METHOD_SNAPKV, fo.METHOD_KNORM, fo.METHOD_SNAPKV])
+    budget = np.array([12, 5, 7, 9])
+    q = [rng.standard_normal((n_layers, n_heads, w, d)).astype(np.float16) for w in windows]
+    q[2] = None
+
+    def tables(st):
+        bt = np.full((4, 10), -1, dtype=np.int32)
+        for r in range(4):
+            n = fo.blocks_for(int(lens0[r]), bs)
+            bt[r, :n] = st.alloc(n)
+        return bt
+
+    st = fo.FreeStack(nb)
+    bt = tables(st)
+    kv_m, lens = kv.copy(), lens0.copy()
+    status, scores, kept = fo.compress_batch(kv_m, st, bt, lens, q, windows, method, budget, pools)
+    assert status is None and lens.tolist() == budget.tolist()
+    for r in range(4):
+        st1 = fo.FreeStack(nb)
+        bt1 = tables(st1)
+        only = np.where(np.arange(4) == r, method, fo.METHOD_NONE)
+        q1 = np.zeros((4, n_layers, n_heads, windows[r], d), dtype=np.float16)
+        if q[r] is not None:
+            q1[r] = q[r]
+        s1, sc1, k1 = fo.compress_batch(kv.copy(), st1, bt1, lens0.copy(), q1, windows[r], only,
+                                        budget, pools[r])
+        assert s1 is None
+        assert (sc1[r] == scores[r]).all() and (k1[r] == kept[r]).all()
+    # window 1, pooling 1: scores of the prefix are the softmax row of the last token's query
+    r = 1
+    L = int(lens0[r])
+    st2 = fo.FreeStack(nb)
+    bt2 = tables(st2)
+    for l in range(n_layers):
+        for h in range(n_heads):
+            keys = fo.fetch_rows(kv, l, bt2[r], 0, h, L)
+            z = keys @ q[r][l, h, 0].astype(np.float64) / np.sqrt(d)
+            pr = np.exp(z - z.max())
+            pr /= pr.sum()
+            assert np.allclose(scores[r][l, h][:L - 1], pr[:L - 1], rtol=1e-12, atol=0)
+            assert np.isinf(scores[r][l, h][L - 1])
+    # sizes are checked per SnapKV request only
+    bad = list(pools)
+    bad[2] = 4                                    # key-norm request: not looked at
+    st3 = fo.FreeStack(nb)
+    assert fo.compress_batch(kv.copy(), st3, tables(st3), lens0.copy(), q, windows, method,
+                             budget, bad)[0] is None
+    bad[0] = 4                                    # SnapKV request: even width is an error
+    st4 = fo.FreeStack(nb)
+    bt4 = tables(st4)
+    top4 = st4.top
+    assert fo.compress_batch(kv.copy(), st4, bt4, lens0.copy(), q, windows, method, budget,
+                             bad)[0] == "EINVAL" and st4.top == top4
+    wbad = list(windows)
+    wbad[3] = 10                                  # window above the budget
+    assert fo.compress_batch(kv.copy(), st4, bt4, lens0.copy(), q, wbad, method, budget,
+                             pools)[0] == "EINVAL" and st4.top == top4
