@@ -154,6 +154,28 @@ int fc_compress_batch(fc_pool* pool, int32_t* dev_block_tables, int max_blocks_p
                       int32_t* dev_kept_out, void* stream);
 
 /*
+ * The same stage (Algorithm 1, "Batch compression") for a batch whose SnapKV
+ * requests each have their own observation window and max-pool width, as
+ * when requests come from models or prompts with different settings.
+ *
+ * host_window, host_pool_kernel  host, int32 [n_req]; entry r is looked at
+ *                   only if host_method[r] == FC_METHOD_SNAPKV (window in
+ *                   1..FC_MAX_WINDOW, pool width odd in 1..FC_MAX_POOL_KERNEL).
+ * dev_q_window      dev, fp16, 16-byte aligned, packed in batch order over the
+ *                   SnapKV requests only: request r contributes
+ *                   [n_layers][n_heads][host_window[r]][head_dim].
+ * Everything else, including errors, as for fc_compress_batch.  The one-pass
+ * scheduling (FC_SCORE_ONE_PASS) takes one window size per batch: FC_EINVAL
+ * otherwise.
+ */
+int fc_compress_batch_var(fc_pool* pool, int32_t* dev_block_tables, int max_blocks_per_req,
+                          int32_t* host_seq_lens, const void* dev_q_window,
+                          const int32_t* host_window, const int32_t* host_method,
+                          const int32_t* host_budget, const int32_t* host_pool_kernel, int n_req,
+                          float scale, float* dev_scores_out, int32_t* dev_kept_out,
+                          void* stream);
+
+/*
  * The paper's own compressor shape ("Multimodal Compressor" section): the cache
  * is split at the modality boundary, every run of k consecutive tokens of one
  * modality is reshaped into one vector of k*head_dim numbers and mapped to ONE

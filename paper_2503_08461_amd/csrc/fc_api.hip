@@ -303,11 +303,14 @@ int fc_pool_import_state_dev(fc_pool* p, const int32_t* dev_stack, int top, void
   return FC_OK;
 }
 
-int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_req,
-                      int32_t* host_seq_lens, const void* dev_q_window, int window,
-                      const int32_t* host_method, const int32_t* host_budget, int n_req,
-                      int pool_kernel, float scale, float* dev_scores_out, int32_t* dev_kept_out,
-                      void* stream_) {
+// Both entry points of the pruning stage.  host_window / host_pool_kernel are
+// NULL for the call that takes one size for the whole batch.
+static int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_req,
+                               int32_t* host_seq_lens, const void* dev_q_window,
+                               const int32_t* host_window, int window,
+                               const int32_t* host_method, const int32_t* host_budget, int n_req,
+                               const int32_t* host_pool_kernel, int pool_kernel, float scale,
+                               float* dev_scores_out, int32_t* dev_kept_out, void* stream_) {
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   if (!p) return fail(FC_EINVAL, "pool is NULL");
   if (n_req < 0) return fail(FC_EINVAL, "n_req < 0");
@@ -315,7 +318,10 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
   if (!dev_block_tables || !host_seq_lens || !host_method || !host_budget)
     return fail(FC_EINVAL, "NULL argument");
   if (max_blocks_per_req < 1) return fail(FC_EINVAL, "max_blocks_per_req < 1");
-  if (pool_kernel < 1 || pool_kernel > FC_MAX_POOL_KERNEL || (pool_kernel & 1) == 0)
+  const bool per_request = host_window != nullptr;
+  if (per_request && !host_pool_kernel) return fail(FC_EINVAL, "NULL argument");
+  if (!per_request &&
+      (pool_kernel < 1 || pool_kernel > FC_MAX_POOL_KERNEL || (pool_kernel & 1) == 0))
     return fail(FC_EINVAL, "pool_kernel must be odd and in 1..%d", FC_MAX_POOL_KERNEL);
 
   // ---- validate with host-known quantities; nothing is touched on error ----
@@ -324,25 +330,42 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
   descs.reserve(n_req);
   const bool in_place = p->compact_mode == FC_COMPACT_IN_PLACE;
   int total_new = 0, total_old = 0, total_released = 0, max_len = 0;
-  size_t score_off = 0, kept_off = 0;
+  size_t score_off = 0, kept_off = 0, q_off = 0;
+  int window_lo = 0, window_hi = 0;  // over the SnapKV requests
   for (int r = 0; r < n_req; ++r) {
     const int m = host_method[r];
+    // queries are packed: with per-request windows only SnapKV requests have any
+    const size_t q_here = q_off;
+    if (per_request) {
+      if (m == FC_METHOD_SNAPKV) q_off += n_lh * (size_t)std::max(host_window[r], 0) * p->head_dim;
+    } else {
+      q_off += n_lh * (size_t)std::max(window, 0) * p->head_dim;
+    }
     if (m == FC_METHOD_NONE) continue;
     const int L = host_seq_lens[r], B = host_budget[r];
+    const int win = per_request ? host_window[r] : window;
+    const int pk = per_request ? host_pool_kernel[r] : pool_kernel;
     if (m != FC_METHOD_SNAPKV && m != FC_METHOD_KNORM && m != FC_METHOD_STREAMING)
       return fail(FC_EINVAL, "request %d: unknown method %d", r, m);
     if (L < 1 || L > FC_MAX_SEQ_LEN)
       return fail(FC_EINVAL, "request %d: length %d outside 1..%d", r, L, FC_MAX_SEQ_LEN);
     if (B < 1 || B > L) return fail(FC_EINVAL, "request %d: budget %d outside 1..%d", r, B, L);
     if (m == FC_METHOD_SNAPKV) {
-      if (window < 1 || window > FC_MAX_WINDOW)
-        return fail(FC_EINVAL, "window %d outside 1..%d", window, FC_MAX_WINDOW);
-      if (L < window || B < window)
+      if (win < 1 || win > FC_MAX_WINDOW)
+        return fail(FC_EINVAL, "request %d: window %d outside 1..%d", r, win, FC_MAX_WINDOW);
+      if (pk < 1 || pk > FC_MAX_POOL_KERNEL || (pk & 1) == 0)
+        return fail(FC_EINVAL, "request %d: pool_kernel must be odd and in 1..%d", r,
+                    FC_MAX_POOL_KERNEL);
+      if (L < win || B < win)
         return fail(FC_EINVAL, "request %d: SnapKV needs length and budget >= window", r);
       if (!dev_q_window || (reinterpret_cast<uintptr_t>(dev_q_window) & 15))
         return fail(FC_EINVAL, "dev_q_window must be a 16-byte aligned device pointer");
+      window_lo = window_lo == 0 ? win : std::min(window_lo, win);
+      window_hi = std::max(window_hi, win);
     }
-    ReqDesc d;
+    ReqDesc d = {};
+    d.window = m == FC_METHOD_SNAPKV ? win : 0;
+    d.pool_kernel = m == FC_METHOD_SNAPKV ? pk : 1;
     d.seq_len = L;
     d.budget = B;
     d.method = m;
@@ -357,7 +380,7 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
     d.score_off = (int64_t)score_off;
     d.raw_off = 0;
     d.kept_off = (int64_t)kept_off;
-    d.q_off = (int64_t)((size_t)r * n_lh * (size_t)std::max(window, 0) * p->head_dim);
+    d.q_off = (int64_t)q_here;
     total_old += d.n_old;
     total_new += in_place ? 0 : d.n_new;
     total_released += d.n_old - d.n_new;
@@ -379,6 +402,9 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
   for (const ReqDesc& d : descs) any_snap |= d.method == FC_METHOD_SNAPKV;
   // AUTO currently means two-pass: measured faster on MI355X for every benchmark shape
   if (any_snap && p->score_mode == FC_SCORE_ONE_PASS) {
+    if (window_lo != window_hi)
+      return fail(FC_EINVAL, "one-pass scoring takes one window size per batch");
+    window = window_hi;
     const int nt = (window + 15) / 16;
     if (p->team_grid[nt] == 0) {
       const int gsz = team_grid_size(p->head_dim, window);
@@ -415,7 +441,16 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
   if ((rc = grow(&p->ids, &p->ids_cap, (size_t)total_old + total_new)) != FC_OK) return rc;
   const size_t desc_bytes = round_up((size_t)n_comp * sizeof(ReqDesc), 16);
   const size_t order_bytes = round_up((size_t)n_comp * sizeof(int32_t), 16);
-  const size_t meta_bytes = desc_bytes + 4 * order_bytes;
+  // Work lists (descriptor indices, heaviest first so that the tail of each
+  // launch is made of light units).  Heads short enough for the fused kernel
+  // (score -> select -> gather in one workgroup) are listed per window class
+  // (class c: SnapKV with ceil(window/16) == c, which is the number of 16-row
+  // query tiles the kernel is compiled for; class 0: no queries at all); the
+  // rest go through the separate kernels: SnapKV per class, key-norm, and one
+  // list of all of them for select and gather.
+  enum { kClasses = 5 };
+  enum { LIST_FUSED = 0, LIST_SNAP = kClasses, LIST_KNORM = 2 * kClasses, LIST_ALL, N_LISTS };
+  const size_t meta_bytes = desc_bytes + N_LISTS * order_bytes;
   if ((rc = grow_meta(p, meta_bytes)) != FC_OK) return rc;
   if (p->meta_pending) {
     // the previous call's descriptor upload must have left the staging buffer
@@ -423,11 +458,6 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
     p->meta_pending = false;
   }
   memcpy(p->host_meta, descs.data(), (size_t)n_comp * sizeof(ReqDesc));
-  // Work lists (descriptor indices, heaviest first so that the tail of each
-  // launch is made of light units).  Heads short enough for the fused kernel
-  // (score -> select -> gather in one workgroup) share one list; the rest go
-  // through the separate kernels, listed per method.
-  enum { LIST_FUSED = 0, LIST_SNAP, LIST_KNORM, LIST_ALL, N_LISTS };
   int32_t* lists[N_LISTS];
   size_t list_off[N_LISTS];
   int n_list[N_LISTS] = {};
@@ -447,32 +477,32 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
   std::stable_sort(sorted.begin(), sorted.end(),
                    [&](int a, int b) { return weight(a) > weight(b); });
   const bool allow_fused = p->score_mode == FC_SCORE_AUTO;
-  bool fused_has_snap = false;
   size_t raw_need = 0;
   for (int di : sorted) {
     const ReqDesc& d = descs[di];
     const bool snap = d.method == FC_METHOD_SNAPKV;
+    const int cls = snap ? (d.window + 15) / 16 : 0;
     int li;
-    if (d.method == FC_METHOD_STREAMING) {
-      // no score, no LDS: always the fused kernel, whatever the length
-      lists[LIST_FUSED][n_list[LIST_FUSED]++] = di;
-      continue;
-    }
-    if (allow_fused && d.seq_len <= kFusedMaxLen) {
-      li = LIST_FUSED;
-      fused_has_snap |= snap;
+    if (d.method == FC_METHOD_STREAMING || (allow_fused && d.seq_len <= kFusedMaxLen)) {
+      // (streaming: no score, no LDS, so the fused kernel whatever the length)
+      li = LIST_FUSED + cls;
     } else {
       // scores of these units travel through the library's scratch
       reinterpret_cast<ReqDesc*>(p->host_meta)[di].raw_off = (int64_t)raw_need;
       raw_need += n_lh * (size_t)d.seq_len;
-      li = snap ? LIST_SNAP : LIST_KNORM;
+      li = snap ? LIST_SNAP + cls : LIST_KNORM;
       lists[LIST_ALL][n_list[LIST_ALL]++] = di;
       max_len_list[LIST_ALL] = std::max(max_len_list[LIST_ALL], d.seq_len);
     }
     lists[li][n_list[li]++] = di;
     max_len_list[li] = std::max(max_len_list[li], d.seq_len);
   }
-  const int ns = n_list[LIST_SNAP], nk = n_list[LIST_KNORM];
+  int ns = 0, n_fused = 0;
+  for (int c = 0; c < kClasses; ++c) {
+    ns += n_list[LIST_SNAP + c];
+    n_fused += n_list[LIST_FUSED + c];
+  }
+  const int nk = n_list[LIST_KNORM];
   if ((rc = grow(&p->raw_scores, &p->raw_cap, raw_need)) != FC_OK) return rc;
   FC_HIP(hipMemcpyAsync(p->dev_meta, p->host_meta, meta_bytes, hipMemcpyHostToDevice, stream));
   FC_HIP(hipEventRecord(p->meta_event, stream));
@@ -491,21 +521,19 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
   bp.descs = reinterpret_cast<const ReqDesc*>(p->dev_meta);
   auto dev_list = [&](int i) { return reinterpret_cast<const int32_t*>(p->dev_meta + list_off[i]); };
   bp.order_all = dev_list(LIST_ALL);
-  bp.order_snap = dev_list(LIST_SNAP);
   bp.order_knorm = dev_list(LIST_KNORM);
   bp.n_comp = n_comp;  // plan_alloc / reclaim walk every descriptor
-  bp.n_snap = ns;
   bp.n_knorm = nk;
   bp.n_unfused = n_list[LIST_ALL];
-  bp.n_fused = n_list[LIST_FUSED];
-  bp.order_fused = dev_list(LIST_FUSED);
+  // per launch: order_snap / n_snap, order_fused / n_fused, window (of the class)
+  bp.order_snap = bp.order_fused = nullptr;
+  bp.n_snap = bp.n_fused = 0;
   bp.block_tables = dev_block_tables;
   bp.max_blocks = max_blocks_per_req;
   bp.old_ids = p->ids;
   bp.new_ids = p->ids + total_old;
   bp.q_window = static_cast<const _Float16*>(dev_q_window);
-  bp.window = window;
-  bp.pool_kernel = pool_kernel;
+  bp.window = window_hi;
   bp.n_sink = p->n_sink;
   bp.in_place = in_place ? 1 : 0;
   const float sc = (scale > 0.f) ? scale : 1.0f / sqrtf((float)p->head_dim);
@@ -538,15 +566,33 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
   if (ns > 0 && team_grid > 0)
     FC_HIP(launch_zero_ints(p->team_counters, (int)n_team_counters, stream));
   FC_HIP(run(K_SNAPKV_SCORE, ns > 0, [&] {
-    return team_grid > 0 ? launch_snapkv_score_team(bp, team_grid, stream)
-                         : launch_snapkv_score(bp, stream);
+    hipError_t e = hipSuccess;
+    for (int c = 1; c < kClasses && e == hipSuccess; ++c) {
+      if (n_list[LIST_SNAP + c] == 0) continue;
+      BatchParams bc = bp;
+      bc.order_snap = dev_list(LIST_SNAP + c);
+      bc.n_snap = n_list[LIST_SNAP + c];
+      bc.window = team_grid > 0 ? window_hi : 16 * c;
+      e = team_grid > 0 ? launch_snapkv_score_team(bc, team_grid, stream)
+                        : launch_snapkv_score(bc, stream);
+    }
+    return e;
   }));
   FC_HIP(run(K_KNORM_SCORE, nk > 0, [&] { return launch_knorm_score(bp, stream); }));
   FC_HIP(run(K_SELECT, bp.n_unfused > 0,
              [&] { return launch_select(bp, max_len_list[LIST_ALL], stream); }));
   FC_HIP(run(K_GATHER, bp.n_unfused > 0, [&] { return launch_gather(bp, stream); }));
-  FC_HIP(run(K_FUSED, bp.n_fused > 0, [&] {
-    return launch_fused(bp, fused_has_snap, max_len_list[LIST_FUSED], stream);
+  FC_HIP(run(K_FUSED, n_fused > 0, [&] {
+    hipError_t e = hipSuccess;
+    for (int c = 0; c < kClasses && e == hipSuccess; ++c) {
+      if (n_list[LIST_FUSED + c] == 0) continue;
+      BatchParams bc = bp;
+      bc.order_fused = dev_list(LIST_FUSED + c);
+      bc.n_fused = n_list[LIST_FUSED + c];
+      bc.window = 16 * c;
+      e = launch_fused(bc, c > 0, max_len_list[LIST_FUSED + c], stream);
+    }
+    return e;
   }));
   FC_HIP(run(K_RECLAIM, true, [&] { return launch_reclaim(bp, stream); }));
 
@@ -554,6 +600,28 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
   p->top = in_place ? p->top + total_released : p->top - total_new + total_old;
   for (const ReqDesc& d : descs) host_seq_lens[d.table_row] = d.budget;
   return FC_OK;
+}
+
+int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_req,
+                      int32_t* host_seq_lens, const void* dev_q_window, int window,
+                      const int32_t* host_method, const int32_t* host_budget, int n_req,
+                      int pool_kernel, float scale, float* dev_scores_out, int32_t* dev_kept_out,
+                      void* stream) {
+  return compress_batch_impl(p, dev_block_tables, max_blocks_per_req, host_seq_lens, dev_q_window,
+                             nullptr, window, host_method, host_budget, n_req, nullptr,
+                             pool_kernel, scale, dev_scores_out, dev_kept_out, stream);
+}
+
+int fc_compress_batch_var(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_req,
+                          int32_t* host_seq_lens, const void* dev_q_window,
+                          const int32_t* host_window, const int32_t* host_method,
+                          const int32_t* host_budget, const int32_t* host_pool_kernel, int n_req,
+                          float scale, float* dev_scores_out, int32_t* dev_kept_out,
+                          void* stream) {
+  if (n_req > 0 && (!host_window || !host_pool_kernel)) return fail(FC_EINVAL, "NULL argument");
+  return compress_batch_impl(p, dev_block_tables, max_blocks_per_req, host_seq_lens, dev_q_window,
+                             host_window, 0, host_method, host_budget, n_req, host_pool_kernel, 0,
+                             scale, dev_scores_out, dev_kept_out, stream);
 }
 
 int fc_mlp_set_weights(fc_pool* p, const fc_mlp_weights* w, void* stream_) {

@@ -30,6 +30,8 @@ struct ReqDesc {
   // chunk-MLP compressor: the image span and the chunk counts of the three segments
   int32_t img_begin, img_end;
   int32_t chunks_text0, chunks_image, chunks_text1;
+  // SnapKV: this request's observation window and max-pool width
+  int32_t window, pool_kernel;
   int32_t pad_;
 };
 
@@ -75,7 +77,8 @@ struct BatchParams {
   int32_t* old_ids;            // [total_old] saved pre-compression ids
   int32_t* new_ids;            // [total_new]
   const _Float16* q_window;
-  int32_t window, pool_kernel;
+  int32_t window;              // a bound on the windows of this launch's SnapKV units (picks the
+                               // number of 16-row query tiles); the unit's own is in its descriptor
   int32_t n_sink;              // leading tokens kept by streaming requests
   int32_t in_place;            // 1: compact inside the request's own blocks
   float scale_log2e;           // scale * log2(e)

@@ -100,7 +100,7 @@ __device__ __forceinline__ void snapkv_unit(const BatchParams& p, const ReqDesc&
   const int layer = lh / p.n_heads;
   const int head = lh - layer * p.n_heads;
   const int L = rd.seq_len;
-  const int W = p.window;
+  const int W = rd.window;  // <= 16 NT; the rows past it are padding
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int c16 = lane & 15;
@@ -419,8 +419,8 @@ __device__ __forceinline__ void select_unit(const BatchParams& p, const ReqDesc&
   const int lane = tid & 63;
   const int wave = tid >> 6;
   const bool snap = rd.method == 1 /* FC_METHOD_SNAPKV */;
-  const int n_sel = snap ? L - p.window : L;  // tokens that compete
-  const int k_sel = snap ? B - p.window : B;  // how many of them are kept
+  const int n_sel = snap ? L - rd.window : L;  // tokens that compete
+  const int k_sel = snap ? B - rd.window : B;  // how many of them are kept
   const float* raw = p.raw_scores + rd.raw_off + (size_t)lh * L;
   float* out = p.scores_out ? p.scores_out + rd.score_off + (size_t)lh * L : nullptr;
   int32_t* kept = p.kept + rd.kept_off + (size_t)lh * B;
@@ -433,7 +433,7 @@ __device__ __forceinline__ void select_unit(const BatchParams& p, const ReqDesc&
       for (int j = tid; j < n_sel; j += kThreads) stage[j] = raw[j];
       __syncthreads();
     }
-    const int h = p.pool_kernel >> 1;
+    const int h = rd.pool_kernel >> 1;
     float pv[kStagePerThread];
 #pragma unroll
     for (int i = 0; i < kStagePerThread; ++i) {
@@ -459,7 +459,7 @@ __device__ __forceinline__ void select_unit(const BatchParams& p, const ReqDesc&
       }
     }
   } else if (snap) {
-    const int h = p.pool_kernel >> 1;
+    const int h = rd.pool_kernel >> 1;
     for (int j = tid; j < n_sel; j += kThreads) {
       const int lo = max(0, j - h), hi = min(n_sel - 1, j + h);
       float s = raw[lo];
@@ -483,7 +483,7 @@ __device__ __forceinline__ void select_unit(const BatchParams& p, const ReqDesc&
   if (snap) {
     if (out)
       for (int j = n_sel + tid; j < L; j += kThreads) out[j] = INFINITY;
-    for (int j = tid; j < p.window; j += kThreads) kept[k_sel + j] = n_sel + j;  // forced window
+    for (int j = tid; j < rd.window; j += kThreads) kept[k_sel + j] = n_sel + j;  // forced window
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {

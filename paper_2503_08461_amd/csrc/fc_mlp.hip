@@ -130,7 +130,6 @@ __global__ __launch_bounds__(mlp_threads(NT), 1) void mlp_compress_kernel(BatchP
   const int col = lane & 31;  // chunk within a 32-wide column tile
   const int kh = lane >> 5;   // which 8 of the slab's 16 contraction positions
   const int k = mp.k;
-  const int S1 = k * SPT;
   const int n_units = p.n_layers * p.n_heads * 2;
   const size_t chunk_el = (size_t)16 * D;
   const size_t v_off = (size_t)p.n_heads * chunk_el;

@@ -39,7 +39,7 @@ __global__ __launch_bounds__(kThreads, 2) void snapkv_score_team_kernel(BatchPar
   const int n_lh = p.n_layers * p.n_heads;
   const int n_wg = gridDim.x;
   const int wg = blockIdx.x;
-  const int W = p.window;
+  const int W = p.window;  // the host admits one window size per batch to this kernel
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int c16 = lane & 15;

@@ -25,7 +25,7 @@ EXPORTS = [
     "fc_pool_create", "fc_pool_destroy", "fc_pool_alloc", "fc_pool_free",
     "fc_pool_num_free", "fc_pool_export_state", "fc_pool_import_state",
     "fc_pool_import_state_dev",
-    "fc_compress_batch", "fc_mlp_set_weights", "fc_compress_batch_mlp", "fc_set_compaction_mode", "fc_set_streaming_sinks", "fc_set_score_mode", "fc_set_profiling", "fc_get_kernel_times",
+    "fc_compress_batch", "fc_compress_batch_var", "fc_mlp_set_weights", "fc_compress_batch_mlp", "fc_set_compaction_mode", "fc_set_streaming_sinks", "fc_set_score_mode", "fc_set_profiling", "fc_get_kernel_times",
     "fc_kernel_name", "fc_last_error",
 ]
 
@@ -80,6 +80,8 @@ def load_library():
     lib.fc_pool_import_state_dev.argtypes = [vp, vp, i, vp]
     lib.fc_compress_batch.argtypes = [vp, vp, i, i32p, vp, i, i32p, i32p, i, i,
                                       ctypes.c_float, vp, vp, vp]
+    lib.fc_compress_batch_var.argtypes = [vp, vp, i, i32p, vp, i32p, i32p, i32p, i32p, i,
+                                          ctypes.c_float, vp, vp, vp]
     lib.fc_mlp_set_weights.argtypes = [vp, ctypes.POINTER(McpWeights), vp]
     lib.fc_compress_batch_mlp.argtypes = [vp, vp, i, i32p, i32p, i32p, i32p, i, vp]
     lib.fc_set_score_mode.argtypes = [vp, i]
@@ -234,6 +236,41 @@ def fc_compress_batch(pool, block_tables, seq_lens, q_window, window, method, bu
         pool.ptr, _dev_ptr(block_tables, torch.int32), int(block_tables.shape[1]),
         _host_i32(seq_lens), _dev_ptr(q_window, torch.float16), int(window),
         _host_i32(method), _host_i32(budget), n_req, int(pool_kernel), float(scale),
+        _dev_ptr(scores_out, torch.float32), _dev_ptr(kept_out, torch.int32),
+        _stream_ptr(stream)))
+
+
+def fc_compress_batch_var(pool, block_tables, seq_lens, q_window, window, method, budget,
+                          pool_kernel, scale=0.0, scores_out=None, kept_out=None, stream=None):
+    """As fc_compress_batch with window and pool_kernel as int32 numpy arrays
+    [n_req]; q_window: flat fp16 device tensor, the SnapKV requests' queries
+    [n_layers][n_heads][window_r][head_dim] one after the other, or None."""
+    import torch
+    lib = load_library()
+    n_req = int(seq_lens.shape[0])
+    if block_tables.dim() != 2 or block_tables.shape[0] != n_req:
+        raise ValueError("block_tables must be [n_req][max_blocks]")
+    for a in (window, method, budget, pool_kernel):
+        if a.shape[0] != n_req:
+            raise ValueError("window / method / budget / pool_kernel must have n_req entries")
+    snap = method == FC_METHOD_SNAPKV
+    need_q = int(window[snap].astype(np.int64).clip(min=0).sum()) * pool.n_layers * \
+        pool.n_heads * pool.head_dim
+    if need_q > 0 and (q_window is None or q_window.numel() < need_q):
+        raise ValueError("q_window holds fewer than %d elements" % need_q)
+    comp = method != FC_METHOD_NONE
+    if scores_out is not None:
+        need = int((seq_lens[comp].astype(np.int64)).sum()) * pool.n_layers * pool.n_heads
+        if scores_out.numel() < need:
+            raise ValueError("scores_out too small")
+    if kept_out is not None:
+        need = int((budget[comp].astype(np.int64)).sum()) * pool.n_layers * pool.n_heads
+        if kept_out.numel() < need:
+            raise ValueError("kept_out too small")
+    _check(lib.fc_compress_batch_var(
+        pool.ptr, _dev_ptr(block_tables, torch.int32), int(block_tables.shape[1]),
+        _host_i32(seq_lens), _dev_ptr(q_window, torch.float16), _host_i32(window),
+        _host_i32(method), _host_i32(budget), _host_i32(pool_kernel), n_req, float(scale),
         _dev_ptr(scores_out, torch.float32), _dev_ptr(kept_out, torch.int32),
         _stream_ptr(stream)))
 

@@ -104,8 +104,11 @@ class SideBySide:
         assert (stack_g[:top_g] == self.stack.stack[:top_g]).all(), "free stacks differ"
 
     def compress_and_compare(self, methods=None, budgets=None, window=None, pool_kernel=None,
-                             scale=0.0, n_sink=4):
-        """One fc_compress_batch on both sides + full comparison.  Returns stats."""
+                             scale=0.0, n_sink=4, q_list=None):
+        """One fc_compress_batch on both sides + full comparison.  Returns stats.
+        With q_list (per request: fp16 array [n_layers][n_heads][window_r][d] or
+        None), window and pool_kernel are int32 arrays and the call is
+        fc_compress_batch_var."""
         torch, fc, wl = self.torch, self.fc, self.wl
         methods = wl.methods if methods is None else methods
         budgets = wl.budgets if budgets is None else budgets
@@ -120,8 +123,17 @@ class SideBySide:
                                 device=self.dev)
         kept_dev = torch.full((max(n_kept, 1),), -7, dtype=torch.int32, device=self.dev)
         fc.fc_set_streaming_sinks(self.pool, n_sink)
-        fc.fc_compress_batch(self.pool, self.bt_dev, self.lens_g, self.q_dev, window,
-                             methods, budgets, pool_kernel, scale, scores_dev, kept_dev)
+        q_host = self.q_host
+        if q_list is None:
+            fc.fc_compress_batch(self.pool, self.bt_dev, self.lens_g, self.q_dev, window,
+                                 methods, budgets, pool_kernel, scale, scores_dev, kept_dev)
+        else:
+            q_host = q_list
+            packed = [q.reshape(-1) for r, q in enumerate(q_list)
+                      if methods[r] == fo.METHOD_SNAPKV]
+            q_flat = (torch.from_numpy(np.concatenate(packed)).to(self.dev) if packed else None)
+            fc.fc_compress_batch_var(self.pool, self.bt_dev, self.lens_g, q_flat, window, methods,
+                                     budgets, pool_kernel, scale, scores_dev, kept_dev)
         torch.cuda.synchronize()
         scores_g = scores_dev.cpu().numpy()
         kept_g = kept_dev.cpu().numpy()
@@ -131,7 +143,7 @@ class SideBySide:
         st_a.stack[:], st_a.top = self.stack.stack, self.stack.top
         bt_a, lens_a = self.bt_host.copy(), self.lens_o.copy()
         status, scores_o, kept_o = fo.compress_batch(
-            kv_a, st_a, bt_a, lens_a, self.q_host, window, methods, budgets, pool_kernel,
+            kv_a, st_a, bt_a, lens_a, q_host, window, methods, budgets, pool_kernel,
             scale if scale > 0 else None, n_sink=n_sink, in_place=self.in_place)
         assert status is None, status
 
@@ -160,7 +172,7 @@ class SideBySide:
 
         # oracle copy step applied to the GPU's kept lists = expected final state
         status, _, _ = fo.compress_batch(
-            self.kv_host, self.stack, self.bt_host, self.lens_o, self.q_host, window,
+            self.kv_host, self.stack, self.bt_host, self.lens_o, q_host, window,
             methods, budgets, pool_kernel, scale if scale > 0 else None,
             kept_override=kept_g_lists, n_sink=n_sink, in_place=self.in_place)
         assert status is None

@@ -383,3 +383,70 @@ def test_work_is_issued_on_the_callers_stream():
     assert torch.equal(a[1], b[1]) and torch.equal(a[2], b[2])
     assert torch.equal(a[0].view(torch.int16), b[0].view(torch.int16))
     assert a[3][1] == b[3][1] and (a[3][0][:a[3][1]] == b[3][0][:b[3][1]]).all()
+
+
+def _mixed_window_batch(seed, lens, n_layers=1, n_heads=2, d=64):
+    rng = np.random.default_rng(seed)
+    R = len(lens)
+    methods = np.array([fo.METHOD_SNAPKV if r % 4 != 3 else fo.METHOD_KNORM for r in range(R)],
+                       np.int32)
+    windows = np.array([[64, 16, 33, 1, 48, 17, 5, 32][r % 8] for r in range(R)], np.int32)
+    pools = np.array([[7, 1, 3, 15, 5, 63, 7, 9][r % 8] for r in range(R)], np.int32)
+    budgets = np.array([max(int(windows[r]), int(lens[r]) // (2 + r % 3)) for r in range(R)],
+                       np.int32)
+    wl = _custom(lens, budgets, methods, W=16, d=d, n_heads=n_heads, n_layers=n_layers, seed=seed)
+    q_list = [rng.standard_normal((n_layers, n_heads, int(windows[r]), d)).astype(np.float16)
+              if methods[r] == fo.METHOD_SNAPKV else None for r in range(R)]
+    return wl, methods, budgets, windows, pools, q_list
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_per_request_window_and_pool_kernel_in_one_batch(d, score_mode):
+    """Requests of one batch with their own observation window (1..64, every
+    number of 16-row query tiles) and pooling width, key-norm requests mixed
+    in, one head longer than the fused kernel's capacity."""
+    if score_mode == 2:
+        pytest.skip("the one-pass scheduling takes one window size per batch")
+    lens = [700, 130, 333, 250, 1200, 96, 64, 513, 90, 8300]
+    wl, methods, budgets, windows, pools, q_list = _mixed_window_batch(77, lens, d=d)
+    sbs = _sbs(wl, score_mode=score_mode)
+    try:
+        stats = sbs.compress_and_compare(methods, budgets, windows, pools, q_list=q_list)
+    finally:
+        sbs.close()
+    print(stats, flush=True)
+    assert stats["units"] == len(lens) * wl.n_layers * wl.n_heads
+    assert stats["max_rel_err"] < 2e-3
+
+
+def test_per_request_sizes_errors_and_one_pass_restriction():
+    import torch
+    from paper_2503_08461_amd import fastcache as fc
+    lens = [200, 300, 150]
+    wl, methods, budgets, windows, pools, q_list = _mixed_window_batch(78, lens)
+    sbs = _sbs(wl)
+    try:
+        q_flat = torch.zeros((int(windows.sum()) + 65) * wl.n_layers * wl.n_heads * wl.head_dim,
+                             dtype=torch.float16, device=sbs.dev)
+        top = fc.fc_pool_num_free(sbs.pool)
+        bad = pools.copy()
+        bad[0] = 4
+        with pytest.raises(fc.FastCacheError) as e:
+            fc.fc_compress_batch_var(sbs.pool, sbs.bt_dev, sbs.lens_g, q_flat, windows, methods,
+                                     budgets, bad)
+        assert e.value.code == fc.FC_EINVAL
+        bad_w = windows.copy()
+        bad_w[1] = 65
+        with pytest.raises(fc.FastCacheError) as e:
+            fc.fc_compress_batch_var(sbs.pool, sbs.bt_dev, sbs.lens_g, q_flat, bad_w, methods,
+                                     budgets, pools)
+        assert e.value.code == fc.FC_EINVAL
+        fc.fc_set_score_mode(sbs.pool, fc.FC_SCORE_ONE_PASS)
+        with pytest.raises(fc.FastCacheError) as e:
+            fc.fc_compress_batch_var(sbs.pool, sbs.bt_dev, sbs.lens_g, q_flat, windows, methods,
+                                     budgets, pools)
+        assert e.value.code == fc.FC_EINVAL
+        assert fc.fc_pool_num_free(sbs.pool) == top and (sbs.lens_g == np.array(lens)).all()
+        sbs.compare_state()
+    finally:
+        sbs.close()
