@@ -274,6 +274,44 @@ const char* fc_kernel_name(int i);
 /* Text of the most recent error raised on the calling thread ("" if none). */
 const char* fc_last_error(void);
 
+/*
+ * Host-side scheduler of the compress queue (Algorithm 1, ServeRequests:
+ * AccumulateRequests, the |Q| >= B_min / WaitTimeExceeded test, FormBatch(Q,
+ * B_max), AdjustBatch; "Memory-Aware Scheduling" paragraph: all pending
+ * requests are examined and the largest batch that fits the free memory is
+ * built, not the head of the queue).  Pure host code, no device work: the
+ * caller passes fc_pool_num_free() and hands the batch to fc_compress_batch.
+ * Times are integer microseconds on any clock of the caller's.
+ *
+ *  - a request needs ceil(budget/16) free blocks in the compress stage;
+ *  - the trigger fires when requests are pending and (their number >= the
+ *    current batch target, which starts at b_min, or the oldest has waited
+ *    max_wait_us or longer);
+ *  - fc_sched_form_batch: 0 if the trigger has not fired; else requests whose
+ *    wait time is exceeded are taken first, in arrival order, each if it
+ *    still fits (free blocks, b_max, capacity) and skipped if not; then the
+ *    others in order of (need, arrival, id) while they fit.  The ids are
+ *    written to out_ids (host, capacity entries) in arrival order, the
+ *    requests leave the queue, the return value is their number (0 if nothing
+ *    fits).
+ *  - fc_sched_adjust(service_us): report how long the last batch took; the
+ *    batch target becomes ceil(service / gap) clamped to [b_min, b_max],
+ *    with running averages avg += floor((x - avg)/4) (first sample sets avg)
+ *    of the service times and of the gaps between arrivals; returns it.
+ * fc_sched_submit: FC_EINVAL (nothing changed) for an arrival before the last
+ * one, a budget outside 1..seq_len, or an id that is still pending.
+ */
+typedef struct fc_sched fc_sched;
+int fc_sched_create(fc_sched** out, int b_min, int b_max, int64_t max_wait_us);
+void fc_sched_destroy(fc_sched* sched);
+int fc_sched_submit(fc_sched* sched, int64_t req_id, int64_t arrival_us, int seq_len, int budget);
+int fc_sched_pending(const fc_sched* sched);
+int fc_sched_batch_target(const fc_sched* sched);
+int fc_sched_ready(const fc_sched* sched, int64_t now_us);
+int fc_sched_form_batch(fc_sched* sched, int64_t now_us, int free_blocks, int64_t* out_ids,
+                        int capacity);
+int fc_sched_adjust(fc_sched* sched, int64_t service_us);
+
 #ifdef __cplusplus
 }
 #endif

@@ -27,6 +27,8 @@ EXPORTS = [
     "fc_pool_import_state_dev",
     "fc_compress_batch", "fc_compress_batch_var", "fc_mlp_set_weights", "fc_compress_batch_mlp", "fc_set_compaction_mode", "fc_set_streaming_sinks", "fc_set_score_mode", "fc_set_profiling", "fc_get_kernel_times",
     "fc_kernel_name", "fc_last_error",
+    "fc_sched_create", "fc_sched_destroy", "fc_sched_submit", "fc_sched_pending",
+    "fc_sched_batch_target", "fc_sched_ready", "fc_sched_form_batch", "fc_sched_adjust",
 ]
 
 _lib = None
@@ -89,11 +91,21 @@ def load_library():
     lib.fc_set_compaction_mode.argtypes = [vp, i]
     lib.fc_set_profiling.argtypes = [vp, i]
     lib.fc_get_kernel_times.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
+    i64 = ctypes.c_int64
+    lib.fc_sched_create.argtypes = [ctypes.POINTER(vp), i, i, i64]
+    lib.fc_sched_destroy.argtypes = [vp]
+    lib.fc_sched_destroy.restype = None
+    lib.fc_sched_submit.argtypes = [vp, i64, i64, i, i]
+    lib.fc_sched_pending.argtypes = [vp]
+    lib.fc_sched_batch_target.argtypes = [vp]
+    lib.fc_sched_ready.argtypes = [vp, i64]
+    lib.fc_sched_form_batch.argtypes = [vp, i64, i, ctypes.POINTER(i64), i]
+    lib.fc_sched_adjust.argtypes = [vp, i64]
     lib.fc_kernel_name.argtypes = [i]
     lib.fc_kernel_name.restype = ctypes.c_char_p
     lib.fc_last_error.restype = ctypes.c_char_p
     for name in EXPORTS:
-        if name not in ("fc_kernel_name", "fc_last_error"):
+        if name not in ("fc_kernel_name", "fc_last_error", "fc_sched_destroy"):
             getattr(lib, name).restype = i
     _lib = lib
     return lib
@@ -333,3 +345,48 @@ def fc_get_kernel_times(pool):
     ms = (ctypes.c_float * FC_N_KERNELS)()
     _check(lib.fc_get_kernel_times(pool.ptr, ms))
     return {lib.fc_kernel_name(k).decode(): float(ms[k]) for k in range(FC_N_KERNELS)}
+
+
+class Scheduler:
+    """fc_sched_*: the host-side scheduler of the compress queue (same names
+    as the C ABI; times in integer microseconds)."""
+
+    def __init__(self, b_min, b_max, max_wait_us):
+        lib = load_library()
+        self._lib = lib
+        out = ctypes.c_void_p()
+        rc = lib.fc_sched_create(ctypes.byref(out), int(b_min), int(b_max), int(max_wait_us))
+        if rc < 0:
+            raise FastCacheError(rc, "fc_sched_create: invalid bounds")
+        self.ptr = out
+        self.b_max = int(b_max)
+
+    def submit(self, req_id, arrival_us, seq_len, budget):
+        return self._lib.fc_sched_submit(self.ptr, int(req_id), int(arrival_us), int(seq_len),
+                                         int(budget)) == FC_OK
+
+    def pending(self):
+        return self._lib.fc_sched_pending(self.ptr)
+
+    def batch_target(self):
+        return self._lib.fc_sched_batch_target(self.ptr)
+
+    def ready(self, now_us):
+        return self._lib.fc_sched_ready(self.ptr, int(now_us)) == 1
+
+    def form_batch(self, now_us, free_blocks):
+        ids = (ctypes.c_int64 * self.b_max)()
+        n = self._lib.fc_sched_form_batch(self.ptr, int(now_us), int(free_blocks), ids,
+                                          self.b_max)
+        if n < 0:
+            raise FastCacheError(n, "fc_sched_form_batch")
+        return [int(ids[i]) for i in range(n)]
+
+    def adjust(self, service_us):
+        return self._lib.fc_sched_adjust(self.ptr, int(service_us))
+
+    def close(self):
+        if self.ptr:
+            self._lib.fc_sched_destroy(self.ptr)
+            self.ptr = None
+
