@@ -199,13 +199,144 @@ def bench_mlp(args, wl):
     print(json.dumps(out), flush=True)
 
 
+def bench_replay(args):
+    """Replay of a Poisson arrival trace through the compress stage (Algorithm
+    1's loop around `kv_c <- C(kv, lambda)`): requests with the config-4 length
+    mix arrive already prefilled (their blocks are taken from the pool at
+    arrival, or they wait for admission), the C-ABI scheduler forms batches
+    from the pool's free count, every batch is really compressed on the GPU
+    (SnapKV, window 64, keep 20 %) and its measured time advances the simulated
+    clock; a compressed request then holds its blocks for a modelled decode
+    residence and releases them.  Prefill and decode are a stage-time MODEL
+    (constants below), the compress times are measurements."""
+    import numpy as np
+    import torch
+    from paper_2503_08461_amd import synth, fastcache as fc
+    dev = torch.device("cuda:0")
+    n_layers, n_heads, d, W = 32, 32, 128, 64
+    n_blocks = 8192                      # 64 GiB pool
+    B_MIN, B_MAX, MAX_WAIT_US = 2, 32, 50_000
+    DECODE_RESIDENCE_US = 2_000_000      # model: 64 output tokens at about 30 ms per step
+    N_REQ = 200
+    RESERVE = 1024                       # blocks that admission leaves free, so that compression
+                                         # (which needs new blocks) can always proceed
+    kv = torch.empty((n_layers, n_blocks, 2, n_heads, 16, d), dtype=torch.float16, device=dev)
+    for l in range(n_layers):
+        kv[l].normal_(0.0, 1.0)
+    q = torch.randn((B_MAX, n_layers, n_heads, W, d), device=dev).half()
+    pool = fc.fc_pool_create(kv, n_blocks, n_layers, n_heads, d)
+    max_blocks = synth.blocks_for(576 * 12 + 128)
+    out = []
+    for rate in (1, 5, 10, 20, 40, 200, 1000):
+        rng = np.random.Generator(np.random.PCG64(4000 + rate))
+        arrivals = np.cumsum(rng.exponential(1e6 / rate, size=N_REQ)).astype(np.int64)
+        lens = (576 * rng.integers(2, 13, size=N_REQ) + 128).astype(np.int32)
+        budgets = np.maximum(lens // 5, W).astype(np.int32)
+        sched = fc.Scheduler(B_MIN, B_MAX, MAX_WAIT_US)
+        rows = {}                        # id -> device tensor of block ids
+        admission, holding = [], []      # waiting ids; (release time, id)
+        waits, batch_sizes, busy_us, now = [], [], 0, 0
+        nxt, done, peak_used, adm_waits = 0, 0, 0, 0
+        admitted_at = {}
+
+        def admit(i, t):
+            need = synth.blocks_for(int(lens[i]))
+            if fc.fc_pool_num_free(pool) < need + RESERVE:
+                return False
+            rows[i] = fc.fc_pool_alloc(pool, need)
+            admitted_at[i] = t
+            assert sched.submit(i, t, int(lens[i]), int(budgets[i]))
+            return True
+
+        spins = 0
+        while done < N_REQ:
+            spins += 1
+            if spins > 3_000_000:
+                raise RuntimeError("replay cannot make progress at %d req/s" % rate)
+            # next event: arrival, release, or the wait-time trigger
+            cand = []
+            if nxt < N_REQ:
+                cand.append(int(arrivals[nxt]))
+            if holding:
+                cand.append(holding[0][0])
+            if sched.pending() and not sched.ready(now):
+                cand.append(now + 1000)  # poll the trigger every millisecond of simulated time
+            if not sched.ready(now) and cand:
+                now = max(now, min(cand))
+            while holding and holding[0][0] <= now:
+                _, i = holding.pop(0)
+                fc.fc_pool_free(pool, rows.pop(i))
+                done += 1
+            still = []
+            for i in admission:
+                if not admit(i, now):
+                    still.append(i)
+            admission = still
+            while nxt < N_REQ and arrivals[nxt] <= now:
+                if admission or not admit(nxt, int(arrivals[nxt])):
+                    admission.append(nxt)
+                    adm_waits += 1
+                nxt += 1
+            peak_used = max(peak_used, n_blocks - fc.fc_pool_num_free(pool))
+            batch = sched.form_batch(now, fc.fc_pool_num_free(pool))
+            if not batch:
+                if sched.ready(now) and not holding and not admission and nxt >= N_REQ:
+                    raise RuntimeError("replay cannot make progress: pool too small")
+                if sched.ready(now):
+                    # nothing fits: wait for the next release
+                    now = max(now, holding[0][0]) if holding else now + 1000
+                continue
+            n = len(batch)
+            bt = torch.full((n, max_blocks), -1, dtype=torch.int32, device=dev)
+            for r, i in enumerate(batch):
+                bt[r, :rows[i].shape[0]] = rows[i]
+            blens = lens[batch].copy()
+            meth = np.full(n, synth.METHOD_SNAPKV, np.int32)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            fc.fc_compress_batch(pool, bt, blens, q[:n], W, meth, budgets[batch].copy(), 7)
+            torch.cuda.synchronize()
+            dt = max(1, int((time.perf_counter() - t0) * 1e6))
+            for r, i in enumerate(batch):
+                waits.append(now - admitted_at[i])
+                rows[i] = bt[r, :synth.blocks_for(int(budgets[i]))].clone()
+                holding.append((now + dt + DECODE_RESIDENCE_US, i))
+            holding.sort()
+            now += dt
+            busy_us += dt
+            batch_sizes.append(n)
+            sched.adjust(dt)
+        sched.close()
+        w = np.array(waits, dtype=np.float64) / 1e3
+        out.append({"rate_req_s": rate, "batches": len(batch_sizes),
+                    "mean_batch": round(float(np.mean(batch_sizes)), 2),
+                    "mean_wait_ms": round(float(w.mean()), 3),
+                    "p95_wait_ms": round(float(np.percentile(w, 95)), 3),
+                    "compress_ms_per_request": round(busy_us / 1e3 / N_REQ, 3),
+                    "compress_busy_frac": round(busy_us / max(now, 1), 5),
+                    "peak_pool_occupancy": round(peak_used / n_blocks, 3),
+                    "arrivals_that_waited_for_admission": adm_waits})
+        assert fc.fc_pool_num_free(pool) == n_blocks
+    fc.fc_pool_destroy(pool)
+    print(json.dumps({
+        "metric": "compress-stage queueing under Poisson arrivals (C-ABI scheduler, measured "
+                  "compress times, modelled decode residence)",
+        "unit": "ms", "n_gpus": 1, "data": "synthetic", "dtype": "f16",
+        "config": {"workload": "replay_config4_mix", "requests_per_rate": N_REQ,
+                   "pool_blocks": n_blocks, "admission_reserve_blocks": RESERVE, "b_min": B_MIN, "b_max": B_MAX,
+                   "max_wait_ms": MAX_WAIT_US / 1e3,
+                   "decode_residence_ms_model": DECODE_RESIDENCE_US / 1e3},
+        "rates": out}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="config4",
-                    choices=["config2", "config3", "config4", "config4_streaming", "config4_mlp"],
+                    choices=["config2", "config3", "config4", "config4_streaming", "config4_mlp",
+                             "replay"],
                     help="config4_streaming: the config-4 batch with every request using the "
                          "score-free sinks + recent rule (gather and pool work only); "
                          "config4_mlp: the config-4 batch through the chunk-MLP compressor "
@@ -242,6 +373,9 @@ def main():
                           "bytes_written_per_copy": n, "copies": 5}), flush=True)
         return
     fc.load_library()
+    if args.workload == "replay":
+        bench_replay(args)
+        return
     wl = synth.make_workload(int(args.workload[6]))
     if args.workload.endswith("_streaming"):
         wl.methods[:] = synth.METHOD_STREAMING
