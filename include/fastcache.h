@@ -266,13 +266,44 @@ int fc_set_score_mode(fc_pool* pool, int mode);
  * fc_kernel_name(i) names slot i.  fc_set_profiling(pool, 1) restarts the
  * average.
  */
-#define FC_N_KERNELS 8
+#define FC_N_KERNELS 10
 int fc_set_profiling(fc_pool* pool, int enable);
 int fc_get_kernel_times(fc_pool* pool, float* host_ms);
 const char* fc_kernel_name(int i);
 
 /* Text of the most recent error raised on the calling thread ("" if none). */
 const char* fc_last_error(void);
+
+/*
+ * Decode-side pool traffic (Algorithm 1, ExecuteDecoding: every decode step
+ * reads the compressed cache of each request, M.Generate, and appends the new
+ * token's K and V, UpdateKVCache).
+ *
+ * fc_append_batch: for every request r (with host_enable[r] != 0 if
+ * host_enable is given) the new token's rows dev_new_kv[r] go to token
+ * position L_r = host_seq_lens[r]: slot L_r % 16 of the block in table entry
+ * L_r / 16.  When L_r is a multiple of 16 a block is popped first (requests
+ * in batch order) and written to that table entry.  host_seq_lens[r] becomes
+ * L_r + 1 before the call returns; the device work is asynchronous on stream.
+ *   dev_new_kv  dev, fp16 [n_req][n_layers][2][n_heads][head_dim], 16-byte aligned
+ * FC_EINVAL: L_r < 0 or >= FC_MAX_SEQ_LEN, table row full (L_r/16 >=
+ * max_blocks_per_req); FC_ENOMEM: more blocks needed than are free.  Nothing
+ * is modified on error.
+ *
+ * fc_decode_attention: the single-query attention of one decode step over
+ * the paged cache, for every request, layer and head:
+ *   out = softmax(scale * K q) . V   over the request's L_r cached tokens
+ * (fp16 K, V, q; fp32 arithmetic; zeros for L_r = 0; scale <= 0 means
+ * 1/sqrt(head_dim)).  Reads every cached K and V row once.
+ *   dev_q    dev, fp16 [n_req][n_layers][n_heads][head_dim], 16-byte aligned
+ *   dev_out  dev, fp32 [n_req][n_layers][n_heads][head_dim]
+ */
+int fc_append_batch(fc_pool* pool, int32_t* dev_block_tables, int max_blocks_per_req,
+                    int32_t* host_seq_lens, const void* dev_new_kv, const int32_t* host_enable,
+                    int n_req, void* stream);
+int fc_decode_attention(fc_pool* pool, const int32_t* dev_block_tables, int max_blocks_per_req,
+                        const int32_t* host_seq_lens, const void* dev_q, float* dev_out,
+                        int n_req, float scale, void* stream);
 
 /*
  * Host-side scheduler of the compress queue (Algorithm 1, ServeRequests:

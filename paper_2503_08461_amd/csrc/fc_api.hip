@@ -39,7 +39,8 @@ int fail(int code, const char* fmt, ...) {
 
 const char* const kKernelNames[K_COUNT] = {"plan_alloc", "snapkv_score", "knorm_score",
                                            "select",     "gather",       "reclaim",
-                                           "fused_unit", "mlp_compress"};
+                                           "fused_unit", "mlp_compress", "append",
+                                           "decode_attention"};
 
 size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -800,6 +801,137 @@ int fc_compress_batch_mlp(fc_pool* p, int32_t* dev_block_tables, int max_blocks_
 
   p->top = p->top - total_new + total_old;
   for (const ReqDesc& d : descs) host_seq_lens[d.table_row] = d.budget;
+  return FC_OK;
+}
+
+}  // extern "C"
+
+namespace {
+
+// One profiled launch outside fc_compress_batch (same event ring).
+template <typename F>
+hipError_t run_profiled(fc_pool* p, int slot, hipStream_t stream, F&& launch) {
+  const int ring = p->prof_calls % kProfRing;
+  if (p->profiling) {
+    for (int k = 0; k < K_COUNT; ++k) p->timed[ring][k] = false;
+    ++p->prof_calls;
+  }
+  hipError_t e = hipSuccess;
+  if (p->profiling) e = hipEventRecord(p->ev[ring][slot][0], stream);
+  if (e == hipSuccess) e = launch();
+  if (e == hipSuccess && p->profiling) {
+    e = hipEventRecord(p->ev[ring][slot][1], stream);
+    p->timed[ring][slot] = true;
+  }
+  return e;
+}
+
+// descriptors of a decode step to the device through the pinned staging buffer
+int upload_decode_reqs(fc_pool* p, const std::vector<DecodeReq>& reqs, hipStream_t stream) {
+  const size_t bytes = round_up(reqs.size() * sizeof(DecodeReq), 16);
+  int rc;
+  if ((rc = grow_meta(p, bytes)) != FC_OK) return rc;
+  if (p->meta_pending) {
+    FC_HIP(hipEventSynchronize(p->meta_event));
+    p->meta_pending = false;
+  }
+  memcpy(p->host_meta, reqs.data(), reqs.size() * sizeof(DecodeReq));
+  FC_HIP(hipMemcpyAsync(p->dev_meta, p->host_meta, bytes, hipMemcpyHostToDevice, stream));
+  FC_HIP(hipEventRecord(p->meta_event, stream));
+  p->meta_pending = true;
+  return FC_OK;
+}
+
+DecodeParams decode_params(fc_pool* p) {
+  DecodeParams dp = {};
+  dp.kv = p->kv;
+  dp.n_blocks = p->n_blocks;
+  dp.n_layers = p->n_layers;
+  dp.n_heads = p->n_heads;
+  dp.head_dim = p->head_dim;
+  dp.stack = p->stack;
+  dp.top_before = p->top;
+  dp.reqs = reinterpret_cast<const DecodeReq*>(p->dev_meta);
+  return dp;
+}
+
+}  // namespace
+
+extern "C" {
+
+int fc_append_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_req,
+                    int32_t* host_seq_lens, const void* dev_new_kv, const int32_t* host_enable,
+                    int n_req, void* stream_) {
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  if (!p) return fail(FC_EINVAL, "pool is NULL");
+  if (n_req < 0) return fail(FC_EINVAL, "n_req < 0");
+  if (n_req == 0) return FC_OK;
+  if (!dev_block_tables || !host_seq_lens || !dev_new_kv) return fail(FC_EINVAL, "NULL argument");
+  if (reinterpret_cast<uintptr_t>(dev_new_kv) & 15)
+    return fail(FC_EINVAL, "dev_new_kv must be 16-byte aligned");
+  if (max_blocks_per_req < 1) return fail(FC_EINVAL, "max_blocks_per_req < 1");
+  std::vector<DecodeReq> reqs;
+  int n_pop = 0;
+  for (int r = 0; r < n_req; ++r) {
+    if (host_enable && !host_enable[r]) continue;
+    const int L = host_seq_lens[r];
+    if (L < 0 || L >= FC_MAX_SEQ_LEN)
+      return fail(FC_EINVAL, "request %d: length %d outside 0..%d", r, L, FC_MAX_SEQ_LEN - 1);
+    if (L / FC_BLOCK_SIZE >= max_blocks_per_req)
+      return fail(FC_EINVAL, "request %d: its table row is full", r);
+    DecodeReq q = {r, L, (L % FC_BLOCK_SIZE == 0) ? n_pop++ : -1, 0};
+    reqs.push_back(q);
+  }
+  if (reqs.empty()) return FC_OK;
+  if (n_pop > p->top) return fail(FC_ENOMEM, "append needs %d new blocks, %d free", n_pop, p->top);
+  int rc;
+  if ((rc = upload_decode_reqs(p, reqs, stream)) != FC_OK) return rc;
+  DecodeParams dp = decode_params(p);
+  dp.block_tables = dev_block_tables;
+  dp.max_blocks = max_blocks_per_req;
+  dp.n_req = (int)reqs.size();
+  dp.new_kv = static_cast<const _Float16*>(dev_new_kv);
+  FC_HIP(run_profiled(p, K_APPEND, stream, [&] { return launch_append(dp, stream); }));
+  p->top -= n_pop;
+  for (const DecodeReq& q : reqs) host_seq_lens[q.table_row] = q.seq_len + 1;
+  return FC_OK;
+}
+
+int fc_decode_attention(fc_pool* p, const int32_t* dev_block_tables, int max_blocks_per_req,
+                        const int32_t* host_seq_lens, const void* dev_q, float* dev_out, int n_req,
+                        float scale, void* stream_) {
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  if (!p) return fail(FC_EINVAL, "pool is NULL");
+  if (n_req < 0) return fail(FC_EINVAL, "n_req < 0");
+  if (n_req == 0) return FC_OK;
+  if (!dev_block_tables || !host_seq_lens || !dev_q || !dev_out)
+    return fail(FC_EINVAL, "NULL argument");
+  if (reinterpret_cast<uintptr_t>(dev_q) & 15) return fail(FC_EINVAL, "dev_q must be 16-byte aligned");
+  if (max_blocks_per_req < 1) return fail(FC_EINVAL, "max_blocks_per_req < 1");
+  std::vector<DecodeReq> reqs(n_req);
+  for (int r = 0; r < n_req; ++r) {
+    const int L = host_seq_lens[r];
+    if (L < 0 || L > FC_MAX_SEQ_LEN)
+      return fail(FC_EINVAL, "request %d: length %d outside 0..%d", r, L, FC_MAX_SEQ_LEN);
+    if ((L + FC_BLOCK_SIZE - 1) / FC_BLOCK_SIZE > max_blocks_per_req)
+      return fail(FC_EINVAL, "request %d: %d tokens exceed max_blocks_per_req", r, L);
+    reqs[r] = {r, L, -1, 0};
+  }
+  // longest first, so that the tail of the launch is made of short units
+  std::stable_sort(reqs.begin(), reqs.end(),
+                   [](const DecodeReq& a, const DecodeReq& b) { return a.seq_len > b.seq_len; });
+  int rc;
+  if ((rc = upload_decode_reqs(p, reqs, stream)) != FC_OK) return rc;
+  DecodeParams dp = decode_params(p);
+  dp.block_tables = const_cast<int32_t*>(dev_block_tables);
+  dp.max_blocks = max_blocks_per_req;
+  dp.n_req = n_req;
+  dp.q = static_cast<const _Float16*>(dev_q);
+  dp.out = dev_out;
+  const float sc = (scale > 0.f) ? scale : 1.0f / sqrtf((float)p->head_dim);
+  dp.scale_log2e = sc * 1.44269504088896340736f;
+  FC_HIP(run_profiled(p, K_DECODE_ATTENTION, stream,
+                      [&] { return launch_decode_attention(dp, stream); }));
   return FC_OK;
 }
 

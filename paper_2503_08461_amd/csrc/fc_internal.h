@@ -55,6 +55,29 @@ struct MlpParams {
   const float* b2[2];
 };
 
+// One request of a decode step (append / attention).
+struct DecodeReq {
+  int32_t table_row;  // row of dev_block_tables, of new_kv, q and out
+  int32_t seq_len;    // tokens cached before the step
+  int32_t pop_index;  // append: which pop of this call gives the request its new block, -1 = none
+  int32_t pad_;
+};
+
+struct DecodeParams {
+  _Float16* kv;
+  int32_t n_blocks, n_layers, n_heads, head_dim;
+  const int32_t* stack;  // free stack (append: new blocks are stack[top_before - 1 - pop_index])
+  int32_t top_before;
+  int32_t* block_tables;
+  int32_t max_blocks;
+  const DecodeReq* reqs;
+  int32_t n_req;
+  const _Float16* new_kv;  // append: [row][layer][2][head][d]
+  const _Float16* q;       // attention: [row][layer][head][d]
+  float* out;              // attention: [row][layer][head][d]
+  float scale_log2e;
+};
+
 // Everything a kernel of the stage needs.  Passed by value.
 struct BatchParams {
   // pool geometry
@@ -100,7 +123,9 @@ enum KernelSlot {
   K_RECLAIM = 5,
   K_FUSED = 6,
   K_MLP = 7,
-  K_COUNT = 8
+  K_APPEND = 8,
+  K_DECODE_ATTENTION = 9,
+  K_COUNT = 10
 };
 
 // Launchers (fc_kernels.hip).  Each returns the hipError_t of the launch.
@@ -125,6 +150,9 @@ hipError_t launch_fused(const BatchParams& p, bool any_snap, int max_seq_len, hi
 static constexpr int kFusedMaxLen = 8192;
 hipError_t launch_reclaim(const BatchParams& p, hipStream_t s);
 hipError_t kernels_one_time_setup();
+// decode-side pool traffic (fc_decode.hip)
+hipError_t launch_append(const DecodeParams& p, hipStream_t s);
+hipError_t launch_decode_attention(const DecodeParams& p, hipStream_t s);
 // chunk-MLP compressor (fc_mlp.hip)
 hipError_t mlp_one_time_setup();
 size_t mlp_w1p_elems(int head_dim, int hidden, int k);

@@ -15,7 +15,7 @@ FC_OK, FC_EINVAL, FC_ENOMEM, FC_EDEVICE = 0, -1, -2, -3
 FC_METHOD_NONE, FC_METHOD_SNAPKV, FC_METHOD_KNORM, FC_METHOD_STREAMING = 0, 1, 2, 3
 FC_DTYPE_F16 = 0
 FC_BLOCK_SIZE = 16
-FC_N_KERNELS = 8
+FC_N_KERNELS = 10
 FC_SCORE_AUTO, FC_SCORE_TWO_PASS, FC_SCORE_ONE_PASS = 0, 1, 2
 FC_COMPACT_FRESH, FC_COMPACT_IN_PLACE = 0, 1
 
@@ -25,7 +25,8 @@ EXPORTS = [
     "fc_pool_create", "fc_pool_destroy", "fc_pool_alloc", "fc_pool_free",
     "fc_pool_num_free", "fc_pool_export_state", "fc_pool_import_state",
     "fc_pool_import_state_dev",
-    "fc_compress_batch", "fc_compress_batch_var", "fc_mlp_set_weights", "fc_compress_batch_mlp", "fc_set_compaction_mode", "fc_set_streaming_sinks", "fc_set_score_mode", "fc_set_profiling", "fc_get_kernel_times",
+    "fc_compress_batch", "fc_compress_batch_var", "fc_append_batch", "fc_decode_attention",
+    "fc_mlp_set_weights", "fc_compress_batch_mlp", "fc_set_compaction_mode", "fc_set_streaming_sinks", "fc_set_score_mode", "fc_set_profiling", "fc_get_kernel_times",
     "fc_kernel_name", "fc_last_error",
     "fc_sched_create", "fc_sched_destroy", "fc_sched_submit", "fc_sched_pending",
     "fc_sched_batch_target", "fc_sched_ready", "fc_sched_form_batch", "fc_sched_adjust",
@@ -84,6 +85,8 @@ def load_library():
                                       ctypes.c_float, vp, vp, vp]
     lib.fc_compress_batch_var.argtypes = [vp, vp, i, i32p, vp, i32p, i32p, i32p, i32p, i,
                                           ctypes.c_float, vp, vp, vp]
+    lib.fc_append_batch.argtypes = [vp, vp, i, i32p, vp, i32p, i, vp]
+    lib.fc_decode_attention.argtypes = [vp, vp, i, i32p, vp, vp, i, ctypes.c_float, vp]
     lib.fc_mlp_set_weights.argtypes = [vp, ctypes.POINTER(McpWeights), vp]
     lib.fc_compress_batch_mlp.argtypes = [vp, vp, i, i32p, i32p, i32p, i32p, i, vp]
     lib.fc_set_score_mode.argtypes = [vp, i]
@@ -285,6 +288,45 @@ def fc_compress_batch_var(pool, block_tables, seq_lens, q_window, window, method
         _host_i32(method), _host_i32(budget), _host_i32(pool_kernel), n_req, float(scale),
         _dev_ptr(scores_out, torch.float32), _dev_ptr(kept_out, torch.int32),
         _stream_ptr(stream)))
+
+
+def fc_append_batch(pool, block_tables, seq_lens, new_kv, enable=None, stream=None):
+    """new_kv: fp16 device tensor [n_req][n_layers][2][n_heads][head_dim];
+    seq_lens (in/out), enable: int32 numpy arrays [n_req]."""
+    import torch
+    lib = load_library()
+    n_req = int(seq_lens.shape[0])
+    if block_tables.dim() != 2 or block_tables.shape[0] != n_req:
+        raise ValueError("block_tables must be [n_req][max_blocks]")
+    want = (n_req, pool.n_layers, 2, pool.n_heads, pool.head_dim)
+    if tuple(new_kv.shape) != want:
+        raise ValueError("new_kv must have shape %s" % (want,))
+    _check(lib.fc_append_batch(
+        pool.ptr, _dev_ptr(block_tables, torch.int32), int(block_tables.shape[1]),
+        _host_i32(seq_lens), _dev_ptr(new_kv, torch.float16),
+        _host_i32(enable) if enable is not None else None, n_req, _stream_ptr(stream)))
+
+
+def fc_decode_attention(pool, block_tables, seq_lens, q, out=None, scale=0.0, stream=None):
+    """q: fp16 device tensor [n_req][n_layers][n_heads][head_dim]; returns out,
+    fp32 device tensor of the same shape (created if None)."""
+    import torch
+    lib = load_library()
+    n_req = int(seq_lens.shape[0])
+    if block_tables.dim() != 2 or block_tables.shape[0] != n_req:
+        raise ValueError("block_tables must be [n_req][max_blocks]")
+    want = (n_req, pool.n_layers, pool.n_heads, pool.head_dim)
+    if tuple(q.shape) != want:
+        raise ValueError("q must have shape %s" % (want,))
+    if out is None:
+        out = torch.empty(want, dtype=torch.float32, device=q.device)
+    elif tuple(out.shape) != want:
+        raise ValueError("out must have shape %s" % (want,))
+    _check(lib.fc_decode_attention(
+        pool.ptr, _dev_ptr(block_tables, torch.int32), int(block_tables.shape[1]),
+        _host_i32(seq_lens), _dev_ptr(q, torch.float16), _dev_ptr(out, torch.float32), n_req,
+        float(scale), _stream_ptr(stream)))
+    return out
 
 
 def fc_mlp_set_weights(pool, k, w1, b1, w2, b2, stream=None):

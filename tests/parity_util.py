@@ -85,7 +85,7 @@ class SideBySide:
             wl, lambda n: fc.fc_pool_alloc(self.pool, n),
             lambda ids: fc.fc_pool_free(self.pool, ids),
             lambda ids, ix: ids[torch.from_numpy(ix).to(self.dev)].contiguous())
-        mb = wl.max_blocks
+        mb = wl.max_blocks + int(wl.extra.get("table_slack", 0))  # room for caches that grow
         self.bt_host = np.full((wl.n_req, mb), -1, dtype=np.int32)
         self.bt_dev = torch.full((wl.n_req, mb), -1, dtype=torch.int32, device=self.dev)
         for r in range(wl.n_req):
