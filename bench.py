@@ -329,6 +329,74 @@ def bench_replay(args):
         "rates": out}), flush=True)
 
 
+def bench_decode(args, wl):
+    """Decode-side traffic on the config-4 batch: the single-query attention of
+    one decode step over the paged cache before and after the batch is
+    compressed (same kernel, same pool; after compression every head's kept
+    rows are dense in the new blocks), and the one-token append."""
+    import numpy as np
+    import torch
+    from paper_2503_08461_amd import fastcache as fc
+    from paper_2503_08461_amd.device_setup import DeviceWorkload
+    wl.name += "_decode"
+    dw = DeviceWorkload(wl, verbose=True)
+    n_lh = wl.n_layers * wl.n_heads
+    d = wl.head_dim
+    gen = torch.Generator(device=dw.dev)
+    gen.manual_seed(wl.seed + 6000)
+    q = torch.randn((wl.n_req, wl.n_layers, wl.n_heads, d), generator=gen, device=dw.dev).half()
+    new_kv = torch.randn((wl.n_req, wl.n_layers, 2, wl.n_heads, d), generator=gen,
+                         device=dw.dev).half()
+    out = torch.empty((wl.n_req, wl.n_layers, wl.n_heads, d), dtype=torch.float32, device=dw.dev)
+    fc.fc_set_profiling(dw.pool, True)
+
+    def timed_attention():
+        for _ in range(args.warmup):
+            fc.fc_decode_attention(dw.pool, dw.bt, dw.lens, q, out)
+        fc.fc_set_profiling(dw.pool, True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fc.fc_decode_attention(dw.pool, dw.bt, dw.lens, q, out)
+        torch.cuda.synchronize()
+        sec = (time.perf_counter() - t0) / args.steps
+        ms = fc.fc_get_kernel_times(dw.pool)["decode_attention"]
+        tokens = int(dw.lens.astype(np.int64).sum())
+        bytes_ = tokens * n_lh * 4 * d                    # every K and V row once
+        return {"tokens": tokens, "ms_per_step": sec * 1e3, "kernel_ms": ms,
+                "algorithmic_bytes": bytes_, "kernel_GBps": bytes_ / (ms * 1e-3) / 1e9,
+                "frac_of_hbm_peak": bytes_ / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+
+    before = timed_attention()
+    dw.compress()
+    torch.cuda.synchronize()
+    after = timed_attention()
+    # the append: one step (every further step would move the lengths)
+    lens = dw.lens.copy()
+    fc.fc_set_profiling(dw.pool, True)
+    fc.fc_append_batch(dw.pool, dw.bt, lens, new_kv)
+    torch.cuda.synchronize()
+    app_ms = fc.fc_get_kernel_times(dw.pool)["append"]
+    app_bytes = wl.n_req * n_lh * 2 * d * 2 * 2          # rows read and written
+    print(json.dumps({
+        "metric": "cached tokens attended/sec in one decode step (all layers x heads), "
+                  "after compression",
+        "value": after["tokens"] / (after["ms_per_step"] * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": after["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": wl.name, "n_req": wl.n_req, "pool_GiB": round(wl.pool_bytes() / 2**30, 1)},
+        "decode_attention_before_compression": before,
+        "decode_attention_after_compression": after,
+        "append": {"kernel_ms": app_ms, "algorithmic_bytes": app_bytes,
+                   "kernel_GBps": app_bytes / (app_ms * 1e-3) / 1e9},
+        "roofline": {"kernel": "decode_attention", "bound": "hbm",
+                     "achieved": after["kernel_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": after["frac_of_hbm_peak"], "traffic": None},
+    }), flush=True)
+    dw.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -336,7 +404,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="config4",
                     choices=["config2", "config3", "config4", "config4_streaming", "config4_mlp",
-                             "replay"],
+                             "config4_decode", "replay"],
                     help="config4_streaming: the config-4 batch with every request using the "
                          "score-free sinks + recent rule (gather and pool work only); "
                          "config4_mlp: the config-4 batch through the chunk-MLP compressor "
@@ -389,6 +457,9 @@ def main():
 
     if args.workload.endswith("_mlp"):
         bench_mlp(args, wl)
+        return
+    if args.workload.endswith("_decode"):
+        bench_decode(args, wl)
         return
     dw = DeviceWorkload(wl, verbose=True)
     fc.fc_set_score_mode(dw.pool, {"auto": 0, "two_pass": 1, "one_pass": 2}[args.score_mode])
