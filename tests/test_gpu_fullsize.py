@@ -107,3 +107,114 @@ def test_fullsize_batch(config, n_samples):
         assert worst < 2e-3
     finally:
         dw.close()
+
+
+def test_fullsize_chunk_mlp_config4():
+    """The chunk-MLP compressor on the config-4 batch exactly as bench.py runs
+    it (k = 5, hidden 256, image span = all but the first and last 64 tokens):
+    pool state bit-exact with the oracle's bookkeeping, sampled (request, layer,
+    head, K|V) units row by row against the oracle."""
+    import torch
+    from oracle import mlp_compressor_oracle as mo
+    from paper_2503_08461_amd import fastcache as fc
+    from paper_2503_08461_amd.device_setup import DeviceWorkload
+    wl = synth.make_workload(4)
+    total = torch.cuda.get_device_properties(0).total_memory
+    if wl.pool_bytes() + (10 << 30) > total:
+        pytest.skip("pool does not fit this device")
+    k, hidden, d = 5, 256, wl.head_dim
+    dw = DeviceWorkload(wl)
+    try:
+        gen = torch.Generator(device=dw.dev)
+        gen.manual_seed(wl.seed + 5000)
+        w1 = [(torch.randn((hidden, k * d), generator=gen, device=dw.dev) / (k * d) ** 0.5).half()
+              for _ in range(2)]
+        w2 = [(torch.randn((d, hidden), generator=gen, device=dw.dev) / hidden ** 0.5).half()
+              for _ in range(2)]
+        b1 = [0.1 * torch.randn(hidden, generator=gen, device=dw.dev) for _ in range(2)]
+        b2 = [0.1 * torch.randn(d, generator=gen, device=dw.dev) for _ in range(2)]
+        fc.fc_mlp_set_weights(dw.pool, k, w1, b1, w2, b2)
+        img_b = np.full(wl.n_req, 64, dtype=np.int32)
+        img_e = (wl.seq_lens - 64).astype(np.int32)
+        fc.fc_compress_batch_mlp(dw.pool, dw.bt, dw.lens, img_b, img_e)
+        torch.cuda.synchronize()
+
+        # pool state against the oracle's bookkeeping (zero-layer pool: no arithmetic)
+        st = fo.FreeStack(wl.n_blocks)
+        rows = synth.build_block_tables(wl, st.alloc, st.free, lambda ids, ix: ids[ix])
+        bt = np.full((wl.n_req, wl.max_blocks), -1, dtype=np.int32)
+        for r in range(wl.n_req):
+            bt[r, :rows[r].shape[0]] = rows[r]
+        bt0 = bt.copy()
+        lens = wl.seq_lens.copy()
+        skeleton = np.zeros((0, wl.n_blocks, 2, wl.n_heads, wl.block_size, d), np.float16)
+        weights = {"w1": [t.cpu().numpy() for t in w1], "b1": [t.cpu().numpy() for t in b1],
+                   "w2": [t.cpu().numpy() for t in w2], "b2": [t.cpu().numpy() for t in b2]}
+        assert mo.compress_batch_mlp(skeleton, st, bt, lens, img_b, img_e,
+                                     np.ones(wl.n_req, np.int32), weights, k) is None
+        stack_g, top_g = fc.fc_pool_export_state(dw.pool)
+        assert top_g == st.top and (stack_g[:top_g] == st.stack[:top_g]).all()
+        assert (dw.lens == lens).all()
+        bt_g = dw.bt.cpu().numpy()
+        for r in range(wl.n_req):
+            n = fo.blocks_for(int(lens[r]), 16)
+            assert (bt_g[r, :n] == bt[r, :n]).all() and (bt_g[r, n:] == -1).all()
+
+        rng = np.random.Generator(np.random.PCG64(404))
+        reqs = [int(np.argmax(wl.seq_lens)), int(np.argmin(wl.seq_lens))]
+        worst = 0.0
+        for i in range(10):
+            r = reqs[i] if i < len(reqs) else int(rng.integers(wl.n_req))
+            l, h, c = int(rng.integers(wl.n_layers)), int(rng.integers(wl.n_heads)), i % 2
+            L = int(wl.seq_lens[r])
+            old = torch.from_numpy(bt0[r, :fo.blocks_for(L, 16)].astype(np.int64)).to(dw.dev)
+            src = dw.kv[l, old, c, h].cpu().numpy().reshape(-1, d)[:L].astype(np.float64)
+            plan = mo.chunk_plan(L, int(img_b[r]), int(img_e[r]), k)
+            want = mo.compress_rows(src, plan, weights, k).astype(np.float64)
+            new = torch.from_numpy(bt[r, :fo.blocks_for(len(plan), 16)].astype(np.int64)).to(dw.dev)
+            got = dw.kv[l, new, c, h].cpu().numpy().reshape(-1, d)[:len(plan)].astype(np.float64)
+            err = np.abs(got - want)
+            assert (err <= 2e-3 * np.abs(want) + 1e-3).all(), (r, l, h, c, float(err.max()))
+            worst = max(worst, float(err.max()))
+        print("chunk-MLP full size: max abs error %.2e over 10 sampled units" % worst, flush=True)
+    finally:
+        dw.close()
+
+
+def test_fullsize_decode_attention_config4_after_compression():
+    """The decode step's attention over the compressed config-4 batch, as
+    bench.py runs it: sampled (request, layer, head) units against the oracle."""
+    import torch
+    from oracle import decode_oracle as do
+    from paper_2503_08461_amd import fastcache as fc
+    from paper_2503_08461_amd.device_setup import DeviceWorkload
+    wl = synth.make_workload(4)
+    total = torch.cuda.get_device_properties(0).total_memory
+    if wl.pool_bytes() + (10 << 30) > total:
+        pytest.skip("pool does not fit this device")
+    dw = DeviceWorkload(wl)
+    try:
+        d = wl.head_dim
+        dw.compress()
+        gen = torch.Generator(device=dw.dev)
+        gen.manual_seed(wl.seed + 6000)
+        q = torch.randn((wl.n_req, wl.n_layers, wl.n_heads, d), generator=gen, device=dw.dev).half()
+        out = fc.fc_decode_attention(dw.pool, dw.bt, dw.lens, q)
+        torch.cuda.synchronize()
+        bt_g = dw.bt.cpu().numpy()
+        rng = np.random.Generator(np.random.PCG64(405))
+        for i in range(24):
+            r, l, h = int(rng.integers(wl.n_req)), int(rng.integers(wl.n_layers)), \
+                int(rng.integers(wl.n_heads))
+            L = int(dw.lens[r])
+            n = fo.blocks_for(L, 16)
+            ids = torch.from_numpy(bt_g[r, :n].astype(np.int64)).to(dw.dev)
+            mini = np.zeros((1, n, 2, 1, 16, d), dtype=np.float16)
+            mini[0, :, :, 0] = dw.kv[l, ids, :, h].cpu().numpy()
+            want = do.decode_attention(mini, np.arange(n)[None, :], np.array([L]),
+                                       q[r, l, h].cpu().numpy()[None, None, None, :])[0, 0, 0]
+            got = out[r, l, h].cpu().numpy().astype(np.float64)
+            err = np.abs(got - want)
+            assert (err <= 1e-3 * np.abs(want) + 1e-4).all(), (r, l, h, float(err.max()))
+    finally:
+        dw.close()
