@@ -70,3 +70,26 @@ def decode_attention(kv_pool, block_tables, seq_lens, q, scale=None):
                 p /= p.sum()
                 out[r, l, h] = p @ vals
     return out
+
+
+def decode_attention_kept(kv_pool, block_tables, seq_lens, kept, q, scale=None):
+    """The same attention over a pruned but uncompacted cache: request r, layer
+    l, head h attends over the tokens kept[r][l, h] (ascending indices into
+    its uncompressed cache).  kept[r]: int array [n_layers][n_heads][B_r]."""
+    n_layers, _, _, n_heads, bs, d = kv_pool.shape
+    if scale is None or scale <= 0:
+        scale = 1.0 / np.sqrt(d)
+    out = np.zeros((len(seq_lens), n_layers, n_heads, d), dtype=np.float64)
+    for r, L in enumerate(int(x) for x in seq_lens):
+        for l in range(n_layers):
+            for h in range(n_heads):
+                idx = np.asarray(kept[r][l, h], dtype=np.int64)
+                if idx.size == 0:
+                    continue
+                keys = fetch_rows(kv_pool, l, block_tables[r], 0, h, L)[idx]
+                vals = fetch_rows(kv_pool, l, block_tables[r], 1, h, L)[idx]
+                z = scale * (keys @ q[r, l, h].astype(np.float64))
+                p = np.exp(z - z.max())
+                p /= p.sum()
+                out[r, l, h] = p @ vals
+    return out

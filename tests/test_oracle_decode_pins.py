@@ -95,3 +95,33 @@ def test_decode_attention_closed_forms():
                 kv2[0, bt[0, t // bs], c, hh, t % bs] = rows[t]
     assert np.allclose(do.decode_attention(kv2, bt, lens, q)[0], do.decode_attention(kv, bt, lens, q)[0],
                        rtol=1e-12, atol=1e-14)
+
+
+def test_attention_over_kept_lists_equals_attention_after_compaction():
+    """Pruning without compaction must attend to exactly what the compacted
+    cache holds: compress a batch with the pruning oracle, then compare the
+    attention over its kept lists on the ORIGINAL pool with the plain attention
+    on the compacted pool; and with every token kept it is the plain attention."""
+    rng = np.random.default_rng(6)
+    n_layers, n_heads, bs, d, nb = 2, 2, 4, 8, 40
+    kv = _pool(rng, n_layers, nb, n_heads, bs, d)
+    st = fo.FreeStack(nb)
+    lens0 = np.array([21, 9, 14], dtype=np.int32)
+    bt = np.full((3, 6), -1, dtype=np.int32)
+    for r in range(3):
+        n = fo.blocks_for(int(lens0[r]), bs)
+        bt[r, :n] = st.alloc(n)
+    kv0, bt0 = kv.copy(), bt.copy()
+    method = np.array([fo.METHOD_SNAPKV, fo.METHOD_KNORM, fo.METHOD_STREAMING])
+    budget = np.array([9, 4, 6])
+    qw = rng.standard_normal((3, n_layers, n_heads, 4, d)).astype(np.float16)
+    lens = lens0.copy()
+    status, _, kept = fo.compress_batch(kv, st, bt, lens, qw, 4, method, budget, 3)
+    assert status is None
+    q = rng.standard_normal((3, n_layers, n_heads, d)).astype(np.float16)
+    a = do.decode_attention_kept(kv0, bt0, lens0, kept, q)
+    b = do.decode_attention(kv, bt, lens, q)
+    assert np.allclose(a, b, rtol=1e-13, atol=1e-15)
+    everything = [np.tile(np.arange(L), (n_layers, n_heads, 1)) for L in lens0]
+    assert np.allclose(do.decode_attention_kept(kv0, bt0, lens0, everything, q),
+                       do.decode_attention(kv0, bt0, lens0, q), rtol=1e-13, atol=1e-15)
