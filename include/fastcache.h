@@ -306,6 +306,24 @@ int fc_decode_attention(fc_pool* pool, const int32_t* dev_block_tables, int max_
                         int n_req, float scale, void* stream);
 
 /*
+ * The same attention over a cache that was pruned but NOT compacted (tokens
+ * evicted in place leave holes, so no block can be returned to the pool and
+ * every kept row is read from where it lies): request r, layer l, head h
+ * attends over the host_budget[r] tokens listed, in ascending order, in
+ *   dev_kept   dev, int32, packed [r][layer][head][host_budget[r]] in batch
+ *              order (the layout of fc_compress_batch's dev_kept_out),
+ * read through the request's UNCOMPRESSED block table and length.  It is the
+ * counterfactual that the compaction copy of the stage is measured against
+ * (same result as fc_decode_attention on the compacted cache); indices outside
+ * 0..L_r-1 are clamped.  FC_EINVAL additionally for a budget outside 0..L_r.
+ */
+int fc_decode_attention_kept(fc_pool* pool, const int32_t* dev_block_tables,
+                             int max_blocks_per_req, const int32_t* host_seq_lens,
+                             const int32_t* host_budget, const int32_t* dev_kept,
+                             const void* dev_q, float* dev_out, int n_req, float scale,
+                             void* stream);
+
+/*
  * Host-side scheduler of the compress queue (Algorithm 1, ServeRequests:
  * AccumulateRequests, the |Q| >= B_min / WaitTimeExceeded test, FormBatch(Q,
  * B_max), AdjustBatch; "Memory-Aware Scheduling" paragraph: all pending

@@ -879,7 +879,7 @@ int fc_append_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_re
       return fail(FC_EINVAL, "request %d: length %d outside 0..%d", r, L, FC_MAX_SEQ_LEN - 1);
     if (L / FC_BLOCK_SIZE >= max_blocks_per_req)
       return fail(FC_EINVAL, "request %d: its table row is full", r);
-    DecodeReq q = {r, L, (L % FC_BLOCK_SIZE == 0) ? n_pop++ : -1, 0};
+    DecodeReq q = {r, L, (L % FC_BLOCK_SIZE == 0) ? n_pop++ : -1, 0, 0};
     reqs.push_back(q);
   }
   if (reqs.empty()) return FC_OK;
@@ -897,9 +897,11 @@ int fc_append_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_re
   return FC_OK;
 }
 
-int fc_decode_attention(fc_pool* p, const int32_t* dev_block_tables, int max_blocks_per_req,
-                        const int32_t* host_seq_lens, const void* dev_q, float* dev_out, int n_req,
-                        float scale, void* stream_) {
+static int decode_attention_impl(fc_pool* p, const int32_t* dev_block_tables,
+                                 int max_blocks_per_req, const int32_t* host_seq_lens,
+                                 const int32_t* host_budget, const int32_t* dev_kept,
+                                 const void* dev_q, float* dev_out, int n_req, float scale,
+                                 void* stream_) {
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   if (!p) return fail(FC_EINVAL, "pool is NULL");
   if (n_req < 0) return fail(FC_EINVAL, "n_req < 0");
@@ -908,18 +910,29 @@ int fc_decode_attention(fc_pool* p, const int32_t* dev_block_tables, int max_blo
     return fail(FC_EINVAL, "NULL argument");
   if (reinterpret_cast<uintptr_t>(dev_q) & 15) return fail(FC_EINVAL, "dev_q must be 16-byte aligned");
   if (max_blocks_per_req < 1) return fail(FC_EINVAL, "max_blocks_per_req < 1");
+  const size_t n_lh = (size_t)p->n_layers * p->n_heads;
   std::vector<DecodeReq> reqs(n_req);
+  size_t kept_off = 0;
   for (int r = 0; r < n_req; ++r) {
     const int L = host_seq_lens[r];
     if (L < 0 || L > FC_MAX_SEQ_LEN)
       return fail(FC_EINVAL, "request %d: length %d outside 0..%d", r, L, FC_MAX_SEQ_LEN);
     if ((L + FC_BLOCK_SIZE - 1) / FC_BLOCK_SIZE > max_blocks_per_req)
       return fail(FC_EINVAL, "request %d: %d tokens exceed max_blocks_per_req", r, L);
-    reqs[r] = {r, L, -1, 0};
+    DecodeReq q = {r, L, -1, 0, 0};
+    if (dev_kept) {
+      const int B = host_budget[r];
+      if (B < 0 || B > L) return fail(FC_EINVAL, "request %d: budget %d outside 0..%d", r, B, L);
+      q.pop_index = B;
+      q.kept_off = (int64_t)kept_off;
+      kept_off += n_lh * (size_t)B;
+    }
+    reqs[r] = q;
   }
   // longest first, so that the tail of the launch is made of short units
-  std::stable_sort(reqs.begin(), reqs.end(),
-                   [](const DecodeReq& a, const DecodeReq& b) { return a.seq_len > b.seq_len; });
+  std::stable_sort(reqs.begin(), reqs.end(), [&](const DecodeReq& a, const DecodeReq& b) {
+    return (dev_kept ? a.pop_index > b.pop_index : a.seq_len > b.seq_len);
+  });
   int rc;
   if ((rc = upload_decode_reqs(p, reqs, stream)) != FC_OK) return rc;
   DecodeParams dp = decode_params(p);
@@ -928,11 +941,28 @@ int fc_decode_attention(fc_pool* p, const int32_t* dev_block_tables, int max_blo
   dp.n_req = n_req;
   dp.q = static_cast<const _Float16*>(dev_q);
   dp.out = dev_out;
+  dp.kept = dev_kept;
   const float sc = (scale > 0.f) ? scale : 1.0f / sqrtf((float)p->head_dim);
   dp.scale_log2e = sc * 1.44269504088896340736f;
   FC_HIP(run_profiled(p, K_DECODE_ATTENTION, stream,
                       [&] { return launch_decode_attention(dp, stream); }));
   return FC_OK;
+}
+
+int fc_decode_attention(fc_pool* p, const int32_t* dev_block_tables, int max_blocks_per_req,
+                        const int32_t* host_seq_lens, const void* dev_q, float* dev_out, int n_req,
+                        float scale, void* stream) {
+  return decode_attention_impl(p, dev_block_tables, max_blocks_per_req, host_seq_lens, nullptr,
+                               nullptr, dev_q, dev_out, n_req, scale, stream);
+}
+
+int fc_decode_attention_kept(fc_pool* p, const int32_t* dev_block_tables, int max_blocks_per_req,
+                             const int32_t* host_seq_lens, const int32_t* host_budget,
+                             const int32_t* dev_kept, const void* dev_q, float* dev_out, int n_req,
+                             float scale, void* stream) {
+  if (n_req > 0 && (!host_budget || !dev_kept)) return fail(FC_EINVAL, "NULL argument");
+  return decode_attention_impl(p, dev_block_tables, max_blocks_per_req, host_seq_lens, host_budget,
+                               dev_kept, dev_q, dev_out, n_req, scale, stream);
 }
 
 }  // extern "C"

@@ -60,7 +60,11 @@ hipError_t launch_append(const DecodeParams& p, hipStream_t s) {
 // (running max, sum, and this lane's 8 output channels) per lane group.  The
 // 4 * (512 / D) states of the workgroup are merged through LDS at the end.
 // ---------------------------------------------------------------------------
-template <int D>
+//
+// kIndexed: the counterfactual of a cache that was pruned WITHOUT compaction:
+// the unit attends over the budget_r tokens of its kept list, read where they
+// lie in the uncompacted cache (every row its own 2*D contiguous bytes).
+template <int D, bool kIndexed>
 __global__ __launch_bounds__(kThreads) void decode_attention_kernel(DecodeParams p) {
   constexpr int LPR = D / 8;        // lanes per row
   constexpr int RPI = 64 / LPR;     // rows per wavefront load instruction
@@ -72,7 +76,9 @@ __global__ __launch_bounds__(kThreads) void decode_attention_kernel(DecodeParams
   const int lh = unit - (unit / n_lh) * n_lh;
   const int layer = lh / p.n_heads;
   const int head = lh - layer * p.n_heads;
-  const int L = rq.seq_len;
+  const int L = kIndexed ? rq.pop_index : rq.seq_len;  // indexed: pop_index holds the budget
+  const int32_t* kept =
+      kIndexed ? p.kept + rq.kept_off + (size_t)lh * L : nullptr;  // ascending token indices
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int grp = lane / LPR;    // which row of a load instruction
@@ -90,17 +96,30 @@ __global__ __launch_bounds__(kThreads) void decode_attention_kernel(DecodeParams
   const size_t blk_stride = (size_t)2 * p.n_heads * 16 * D;
   const size_t v_off = (size_t)p.n_heads * 16 * D;
   const _Float16* base = p.kv + (size_t)layer * p.n_blocks * blk_stride + (size_t)head * 16 * D +
-                         (size_t)grp * D + piece * 8;
+                         (kIndexed ? 0 : (size_t)grp * D) + piece * 8;
 
   float m = -INFINITY, z = 0.f, acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   const int nb = (L + 15) >> 4;
   for (int b = wave; b < nb; b += kWaves) {
-    const _Float16* kp = base + (size_t)clamp_block(row[b], p.n_blocks) * blk_stride;
     half8 k[IPB], v[IPB];
+    if (kIndexed) {
+      // 16 kept tokens at a time, each fetched from its own block and slot
 #pragma unroll
-    for (int i = 0; i < IPB; ++i) {
-      k[i] = load_half8(kp + (size_t)i * RPI * D);
-      v[i] = load_half8(kp + v_off + (size_t)i * RPI * D);
+      for (int i = 0; i < IPB; ++i) {
+        const int j = b * 16 + i * RPI + grp;
+        const int tok = min(max(kept[min(j, L - 1)], 0), rq.seq_len - 1);
+        const _Float16* kp = base + (size_t)clamp_block(row[tok >> 4], p.n_blocks) * blk_stride +
+                             (size_t)(tok & 15) * D;
+        k[i] = load_half8(kp);
+        v[i] = load_half8(kp + v_off);
+      }
+    } else {
+      const _Float16* kp = base + (size_t)clamp_block(row[b], p.n_blocks) * blk_stride;
+#pragma unroll
+      for (int i = 0; i < IPB; ++i) {
+        k[i] = load_half8(kp + (size_t)i * RPI * D);
+        v[i] = load_half8(kp + v_off + (size_t)i * RPI * D);
+      }
     }
 #pragma unroll
     for (int i = 0; i < IPB; ++i) {
@@ -149,10 +168,15 @@ __global__ __launch_bounds__(kThreads) void decode_attention_kernel(DecodeParams
 hipError_t launch_decode_attention(const DecodeParams& p, hipStream_t s) {
   if (p.n_req == 0) return hipSuccess;
   const unsigned grid = (unsigned)p.n_req * p.n_layers * p.n_heads;
-  if (p.head_dim == 128)
-    decode_attention_kernel<128><<<grid, kThreads, 0, s>>>(p);
+  const bool indexed = p.kept != nullptr;
+  if (p.head_dim == 128 && !indexed)
+    decode_attention_kernel<128, false><<<grid, kThreads, 0, s>>>(p);
+  else if (p.head_dim == 128)
+    decode_attention_kernel<128, true><<<grid, kThreads, 0, s>>>(p);
+  else if (p.head_dim == 64 && !indexed)
+    decode_attention_kernel<64, false><<<grid, kThreads, 0, s>>>(p);
   else if (p.head_dim == 64)
-    decode_attention_kernel<64><<<grid, kThreads, 0, s>>>(p);
+    decode_attention_kernel<64, true><<<grid, kThreads, 0, s>>>(p);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();

@@ -59,8 +59,10 @@ struct MlpParams {
 struct DecodeReq {
   int32_t table_row;  // row of dev_block_tables, of new_kv, q and out
   int32_t seq_len;    // tokens cached before the step
-  int32_t pop_index;  // append: which pop of this call gives the request its new block, -1 = none
+  int32_t pop_index;  // append: which pop of this call gives the request its new block, -1 = none;
+                      // attention over a kept list: the request's budget
   int32_t pad_;
+  int64_t kept_off;   // attention over a kept list: start of [layer][head][budget] in `kept`
 };
 
 struct DecodeParams {
@@ -75,6 +77,7 @@ struct DecodeParams {
   const _Float16* new_kv;  // append: [row][layer][2][head][d]
   const _Float16* q;       // attention: [row][layer][head][d]
   float* out;              // attention: [row][layer][head][d]
+  const int32_t* kept;     // attention over kept lists of an uncompacted cache, else NULL
   float scale_log2e;
 };
 

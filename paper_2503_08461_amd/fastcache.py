@@ -26,6 +26,7 @@ EXPORTS = [
     "fc_pool_num_free", "fc_pool_export_state", "fc_pool_import_state",
     "fc_pool_import_state_dev",
     "fc_compress_batch", "fc_compress_batch_var", "fc_append_batch", "fc_decode_attention",
+    "fc_decode_attention_kept",
     "fc_mlp_set_weights", "fc_compress_batch_mlp", "fc_set_compaction_mode", "fc_set_streaming_sinks", "fc_set_score_mode", "fc_set_profiling", "fc_get_kernel_times",
     "fc_kernel_name", "fc_last_error",
     "fc_sched_create", "fc_sched_destroy", "fc_sched_submit", "fc_sched_pending",
@@ -87,6 +88,8 @@ def load_library():
                                           ctypes.c_float, vp, vp, vp]
     lib.fc_append_batch.argtypes = [vp, vp, i, i32p, vp, i32p, i, vp]
     lib.fc_decode_attention.argtypes = [vp, vp, i, i32p, vp, vp, i, ctypes.c_float, vp]
+    lib.fc_decode_attention_kept.argtypes = [vp, vp, i, i32p, i32p, vp, vp, vp, i, ctypes.c_float,
+                                             vp]
     lib.fc_mlp_set_weights.argtypes = [vp, ctypes.POINTER(McpWeights), vp]
     lib.fc_compress_batch_mlp.argtypes = [vp, vp, i, i32p, i32p, i32p, i32p, i, vp]
     lib.fc_set_score_mode.argtypes = [vp, i]
@@ -326,6 +329,31 @@ def fc_decode_attention(pool, block_tables, seq_lens, q, out=None, scale=0.0, st
         pool.ptr, _dev_ptr(block_tables, torch.int32), int(block_tables.shape[1]),
         _host_i32(seq_lens), _dev_ptr(q, torch.float16), _dev_ptr(out, torch.float32), n_req,
         float(scale), _stream_ptr(stream)))
+    return out
+
+
+def fc_decode_attention_kept(pool, block_tables, seq_lens, budget, kept, q, out=None, scale=0.0,
+                             stream=None):
+    """Attention over the kept tokens of an uncompacted cache; kept: int32
+    device tensor packed [r][layer][head][budget_r] (fc_compress_batch's kept_out)."""
+    import torch
+    lib = load_library()
+    n_req = int(seq_lens.shape[0])
+    if block_tables.dim() != 2 or block_tables.shape[0] != n_req or budget.shape[0] != n_req:
+        raise ValueError("block_tables must be [n_req][max_blocks], budget [n_req]")
+    want = (n_req, pool.n_layers, pool.n_heads, pool.head_dim)
+    if tuple(q.shape) != want:
+        raise ValueError("q must have shape %s" % (want,))
+    need = int(budget.astype(np.int64).sum()) * pool.n_layers * pool.n_heads
+    if kept.numel() < need:
+        raise ValueError("kept holds fewer than %d entries" % need)
+    if out is None:
+        out = torch.empty(want, dtype=torch.float32, device=q.device)
+    _check(lib.fc_decode_attention_kept(
+        pool.ptr, _dev_ptr(block_tables, torch.int32), int(block_tables.shape[1]),
+        _host_i32(seq_lens), _host_i32(budget), _dev_ptr(kept, torch.int32),
+        _dev_ptr(q, torch.float16), _dev_ptr(out, torch.float32), n_req, float(scale),
+        _stream_ptr(stream)))
     return out
 
 

@@ -117,3 +117,45 @@ def test_append_errors_leave_everything_untouched():
         sbs.compare_state()
     finally:
         sbs.close()
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_attention_over_kept_lists_of_an_uncompacted_cache(d):
+    """fc_decode_attention_kept on the uncompressed pool with the kept lists
+    that a compression of a COPY of the batch produced: equal (to tolerance) to
+    the oracle over those lists, and to the plain attention on the compacted copy."""
+    import torch
+    from paper_2503_08461_amd import fastcache as fc
+    lens = [700, 64, 129, 2050, 16, 333]
+    sbs, wl = _setup(lens, d=d, n_heads=2, n_layers=2, spare=240)
+    try:
+        rng = np.random.default_rng(10)
+        n_lh = wl.n_layers * wl.n_heads
+        methods = np.array([fo.METHOD_SNAPKV, fo.METHOD_KNORM, fo.METHOD_STREAMING,
+                            fo.METHOD_SNAPKV, fo.METHOD_KNORM, fo.METHOD_SNAPKV], np.int32)
+        budgets = np.array([140, 64, 17, 410, 1, 100], np.int32)
+        q = rng.standard_normal((len(lens), wl.n_layers, wl.n_heads, d)).astype(np.float16)
+        q_dev = torch.from_numpy(q).to(sbs.dev)
+        bt_before, lens_before = sbs.bt_dev.clone(), sbs.lens_g.copy()
+        kv_before = sbs.kv_host.copy()
+        bt_host_before = sbs.bt_host.copy()
+        kept_dev = torch.empty(int(budgets.sum()) * n_lh, dtype=torch.int32, device=sbs.dev)
+        fc.fc_compress_batch(sbs.pool, sbs.bt_dev, sbs.lens_g, sbs.q_dev, wl.window, methods,
+                             budgets, 7, 0.0, None, kept_dev)
+        torch.cuda.synchronize()
+        # the old blocks still hold the uncompressed caches (compaction writes only free blocks)
+        got = fc.fc_decode_attention_kept(sbs.pool, bt_before, lens_before, budgets, kept_dev,
+                                          q_dev).cpu().numpy().astype(np.float64)
+        after = fc.fc_decode_attention(sbs.pool, sbs.bt_dev, sbs.lens_g,
+                                       q_dev).cpu().numpy().astype(np.float64)
+        kept_host = kept_dev.cpu().numpy()
+        kept, off = [], 0
+        for r in range(len(lens)):
+            B = int(budgets[r])
+            kept.append(kept_host[off:off + n_lh * B].reshape(wl.n_layers, wl.n_heads, B))
+            off += n_lh * B
+        want = do.decode_attention_kept(kv_before, bt_host_before, lens_before, kept, q)
+        assert (np.abs(got - want) <= RTOL * np.abs(want) + ATOL).all()
+        assert (np.abs(after - want) <= RTOL * np.abs(want) + ATOL).all()
+    finally:
+        sbs.close()
