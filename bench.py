@@ -368,9 +368,31 @@ def bench_decode(args, wl):
                 "frac_of_hbm_peak": bytes_ / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
 
     before = timed_attention()
-    dw.compress()
+    kept = torch.empty(int(wl.budgets.astype(np.int64).sum()) * n_lh, dtype=torch.int32,
+                       device=dw.dev)
+    dw.compress(None, kept)
     torch.cuda.synchronize()
     after = timed_attention()
+
+    # the counterfactual: the same kept tokens read in place from the uncompacted
+    # cache (the old blocks are intact: compaction writes only into free blocks)
+    def timed_kept():
+        call = lambda: fc.fc_decode_attention_kept(dw.pool, dw.bt0, wl.seq_lens, wl.budgets, kept,
+                                                   q, out)
+        for _ in range(args.warmup):
+            call()
+        fc.fc_set_profiling(dw.pool, True)
+        torch.cuda.synchronize()
+        for _ in range(args.steps):
+            call()
+        torch.cuda.synchronize()
+        ms = fc.fc_get_kernel_times(dw.pool)["decode_attention"]
+        bytes_ = after["algorithmic_bytes"]
+        return {"tokens": after["tokens"], "kernel_ms": ms, "algorithmic_bytes": bytes_,
+                "kernel_GBps": bytes_ / (ms * 1e-3) / 1e9,
+                "frac_of_hbm_peak": bytes_ / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+
+    uncompacted = timed_kept()
     # the append: one step (every further step would move the lengths)
     lens = dw.lens.copy()
     fc.fc_set_profiling(dw.pool, True)
@@ -388,6 +410,7 @@ def bench_decode(args, wl):
         "config": {"workload": wl.name, "n_req": wl.n_req, "pool_GiB": round(wl.pool_bytes() / 2**30, 1)},
         "decode_attention_before_compression": before,
         "decode_attention_after_compression": after,
+        "decode_attention_kept_tokens_without_compaction": uncompacted,
         "append": {"kernel_ms": app_ms, "algorithmic_bytes": app_bytes,
                    "kernel_GBps": app_bytes / (app_ms * 1e-3) / 1e9},
         "roofline": {"kernel": "decode_attention", "bound": "hbm",
