@@ -377,12 +377,12 @@ static size_t mlp_lds_bytes() {
 }
 
 // Column tiles per wavefront: with a hidden width of 256 one column tile
-// already needs 128 accumulator registers.
-#ifndef FC_MLP_NT_WIDE
-#define FC_MLP_NT_WIDE 1
-#endif
+// already needs 128 accumulator registers, so a wavefront takes one (eight
+// wavefronts, two per SIMD, 256 registers each); with 128 it takes two (four
+// wavefronts).  Two tiles at width 256 (four wavefronts with 512 registers)
+// measured slower: nothing covers the stalls of a lone wavefront on its SIMD.
 template <int HID>
-constexpr int mlp_nt() { return HID >= 256 ? FC_MLP_NT_WIDE : 2; }
+constexpr int mlp_nt() { return HID >= 256 ? 1 : 2; }
 
 template <int D, int HID>
 static hipError_t mlp_setup_one() {
