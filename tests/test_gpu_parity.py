@@ -450,3 +450,43 @@ def test_per_request_sizes_errors_and_one_pass_restriction():
         sbs.compare_state()
     finally:
         sbs.close()
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_batches_with_per_request_sizes(seed):
+    """Seeded random batches through fc_compress_batch_var: any window 1..64 and
+    any odd pooling width per SnapKV request, all four methods and pass-through
+    requests mixed, fresh-block and in-place compaction, fused and separate
+    scheduling."""
+    rng = np.random.Generator(np.random.PCG64(7000 + seed))
+    R = int(rng.integers(2, 8))
+    d = int(rng.choice([64, 128]))
+    n_layers, n_heads = int(rng.integers(1, 3)), int(rng.integers(1, 4))
+    lens, methods, budgets, windows, pools = [], [], [], [], []
+    for _ in range(R):
+        m = int(rng.choice([fo.METHOD_SNAPKV, fo.METHOD_KNORM, fo.METHOD_STREAMING, fo.METHOD_NONE],
+                           p=[0.55, 0.2, 0.15, 0.1]))
+        W = int(rng.integers(1, 65))
+        lo = W if m == fo.METHOD_SNAPKV else 1
+        L = int(rng.integers(lo, 2500)) if rng.random() < 0.7 else int(rng.integers(lo, lo + 30))
+        B = int(rng.integers(lo, L + 1))
+        lens.append(L); methods.append(m); budgets.append(B); windows.append(W)
+        pools.append(int(rng.choice([1, 3, 5, 7, 9, 15, 31, 63])))
+    methods, budgets = np.array(methods, np.int32), np.array(budgets, np.int32)
+    windows, pools = np.array(windows, np.int32), np.array(pools, np.int32)
+    wl = _custom(lens, budgets, methods, W=16, d=d, n_heads=n_heads, n_layers=n_layers,
+                 seed=300 + seed)
+    q_list = [rng.standard_normal((n_layers, n_heads, int(windows[r]), d)).astype(np.float16)
+              if methods[r] == fo.METHOD_SNAPKV else None for r in range(R)]
+    mode, in_place = int(rng.integers(0, 2)), bool(rng.integers(0, 2))
+    print("seed", seed, "lens", lens, "methods", methods.tolist(), "budgets", budgets.tolist(),
+          "windows", windows.tolist(), "pools", pools.tolist(), "d", d, "mode", mode,
+          "in_place", in_place, flush=True)
+    from parity_util import SideBySide
+    sbs = SideBySide(wl, score_mode=mode, in_place=in_place)
+    try:
+        stats = sbs.compress_and_compare(methods, budgets, windows, pools, q_list=q_list,
+                                         n_sink=int(rng.integers(0, 6)))
+    finally:
+        sbs.close()
+    assert stats["max_rel_err"] < 2e-3
