@@ -88,11 +88,12 @@ hipError_t launch_mlp_permute_weights(const _Float16* w1, const _Float16* w2, _F
 }
 
 // tanh form of GELU, v/2 * (1 + tanh(u)) with u = sqrt(2/pi) * (v + 0.044715 v^3),
-// written as v / (1 + exp(-2u)): one exp2 and one reciprocal per value (the
-// erf form costs about 40 VALU instructions per value, more than the MFMAs)
+// written as v / (1 + exp(-2u)) = v / (1 + exp2(v * (A + B v^2))) with the
+// constants folded (A = -2 log2(e) sqrt(2/pi), B = 0.044715 A): one exp2, one
+// reciprocal and five other operations per value (the erf form costs about 40
+// VALU instructions per value, more than the MFMAs)
 __device__ __forceinline__ float gelu_tanh(float v) {
-  const float u = 0.7978845608028654f * (v + 0.044715f * v * v * v);
-  const float e = __builtin_amdgcn_exp2f(-2.8853900817779268f * u);  // exp(-2u)
+  const float e = __builtin_amdgcn_exp2f(v * fmaf(v * v, -0.10294324f, -2.3022082f));
   return v * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
