@@ -133,7 +133,7 @@ def bench_mlp(args, wl):
     import torch
     from paper_2503_08461_amd import fastcache as fc
     from paper_2503_08461_amd.device_setup import DeviceWorkload
-    k, hidden, d = 5, 256, wl.head_dim
+    k, hidden, d = 5, args.mlp_hidden, wl.head_dim
     wl.name += "_mlp"
     dw = DeviceWorkload(wl, verbose=True)
     gen = torch.Generator(device=dw.dev)
@@ -432,6 +432,8 @@ def main():
                          "score-free sinks + recent rule (gather and pool work only); "
                          "config4_mlp: the config-4 batch through the chunk-MLP compressor "
                          "(k = 5, hidden 256, synthetic weights)")
+    ap.add_argument("--mlp-hidden", type=int, default=256, choices=[128, 256],
+                    help="hidden width of the chunk-MLP workload")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="CPU time budget of the oracle baseline (0 = skip)")
     ap.add_argument("--score-mode", default="auto", choices=["auto", "two_pass", "one_pass"],

@@ -114,6 +114,7 @@ __global__ __launch_bounds__(mlp_threads(NT), 1) void mlp_compress_kernel(BatchP
   constexpr int PPG = GO * 64 / kMlpThreads;  // 16-byte pieces of a W1 group per thread
   constexpr int AR = 4;                       // A operands in flight from LDS
   constexpr int XR = NT == 1 ? 2 : 1;         // tokens of B operands held in registers
+  constexpr int WD = 2;                       // W1 groups in flight in registers (4 measured slower)
   constexpr int RT = 8 + XR;                  // rows of the per-lane token table
   static_assert(GO % AR == 0 && PPG >= 1, "tiling");
   extern __shared__ __align__(16) unsigned char smem[];
@@ -246,7 +247,7 @@ __global__ __launch_bounds__(mlp_threads(NT), 1) void mlp_compress_kernel(BatchP
       for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[mt][nt][r] = 0.f;
-    half8 xq[XR][NT][SPT], wq[2][PPG], ar[AR];
+    half8 xq[XR][NT][SPT], wq[WD][PPG], ar[AR];
 #pragma unroll
     for (int u = 0; u < XR; ++u)
 #pragma unroll
@@ -255,15 +256,15 @@ __global__ __launch_bounds__(mlp_threads(NT), 1) void mlp_compress_kernel(BatchP
 #pragma unroll
         for (int j = 0; j < SPT; ++j) xq[u][nt][j] = load_x(nt, ri, j);
       }
-    // groups 0 and 1 go straight to LDS; wq[i] holds the next unwritten group congruent to i
+    // groups 0 and 1 go straight to LDS; wq[i] holds the next unwritten group congruent to i mod WD
 #pragma unroll
     for (int g = 0; g < 2; ++g)
 #pragma unroll
       for (int i = 0; i < PPG; ++i) sm_w1[g * GO * 64 + i * kMlpThreads + tid] = load_w(g, i);
 #pragma unroll
-    for (int g = 0; g < 2; ++g)
+    for (int g = 0; g < WD; ++g)
 #pragma unroll
-      for (int i = 0; i < PPG; ++i) wq[g][i] = load_w(2 + g, i);
+      for (int i = 0; i < PPG; ++i) wq[(2 + g) % WD][i] = load_w(2 + g, i);
     __syncthreads();  // W2, biases and groups 0, 1 of W1 are in LDS
 #pragma unroll
     for (int n = 0; n < AR; ++n) ar[n] = sm_w1[n * 64 + lane];
@@ -281,8 +282,8 @@ __global__ __launch_bounds__(mlp_threads(NT), 1) void mlp_compress_kernel(BatchP
         half8* w1n = sm_w1 + ((jj + 2) % GPT) * GO * 64;
 #pragma unroll
         for (int i = 0; i < PPG; ++i) {
-          w1n[i * kMlpThreads + tid] = wq[jj % 2][i];
-          wq[jj % 2][i] = load_w(GPT * t + jj + 4, i);
+          w1n[i * kMlpThreads + tid] = wq[(GPT * u + jj + 2) % WD][i];
+          wq[(GPT * u + jj + 2) % WD][i] = load_w(GPT * t + jj + 2 + WD, i);
         }
         const half8* w1s = sm_w1 + jj * GO * 64;
         const half8* w1f = sm_w1 + ((jj + 1) % GPT) * GO * 64;  // visible since the last barrier
@@ -382,12 +383,12 @@ static size_t mlp_lds_bytes() {
 // wavefronts, two per SIMD, 256 registers each); with 128 it takes two (four
 // wavefronts).  Two tiles at width 256 (four wavefronts with 512 registers)
 // measured slower: nothing covers the stalls of a lone wavefront on its SIMD.
-template <int HID>
-constexpr int mlp_nt() { return HID >= 256 ? 1 : 2; }
+template <int D, int HID>
+constexpr int mlp_nt() { return (D / 64) * (HID / 32) * 64 >= 512 ? 1 : 2; }
 
 template <int D, int HID>
 static hipError_t mlp_setup_one() {
-  constexpr int NT = mlp_nt<HID>();
+  constexpr int NT = mlp_nt<D, HID>();
   return hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_compress_kernel<D, HID, NT>),
                              hipFuncAttributeMaxDynamicSharedMemorySize,
                              (int)mlp_lds_bytes<D, HID, NT>());
@@ -403,7 +404,7 @@ hipError_t mlp_one_time_setup() {
 
 template <int D, int HID>
 static hipError_t mlp_launch_one(const BatchParams& p, const MlpParams& mp, hipStream_t s) {
-  constexpr int NT = mlp_nt<HID>();
+  constexpr int NT = mlp_nt<D, HID>();
   mlp_compress_kernel<D, HID, NT><<<std::min(mp.n_tiles, mp.max_grid), mlp_threads(NT),
                                     mlp_lds_bytes<D, HID, NT>(), s>>>(p, mp);
   return hipGetLastError();
