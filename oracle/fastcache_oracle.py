@@ -26,6 +26,12 @@ but prints none of their formulas; the readings taken here are:
     (keys before the window) are max-pooled with an odd kernel, stride 1,
     same length, neighbours outside the prefix ignored; window tokens get
     score +inf so they are always kept;
+  * SnapKV-style score with the row normalisers handed in: a caller whose
+    attention kernel already produced, for every window query, the natural
+    logarithm of the sum of exp(logit) over its visible keys (the "log-sum-exp"
+    that fused attention kernels return) passes it in, and row i of the
+    soft-max is then exp(logit - lse_i); with the exact log-sum-exp this is the
+    same number as above;
   * key-norm score: minus the Euclidean norm of the key, so that keeping the
     best scores keeps the lowest norms; no pooling, no forced tokens;
   * streaming (StreamingLLM-style, one of the baselines the paper runs): no
@@ -102,6 +108,40 @@ def snapkv_scores(keys, q_window, scale, pool_kernel):
     return np.concatenate([prefix, np.full(W, np.inf)])
 
 
+def window_logits(keys, q_window, scale):
+    """Logits of the window queries against every key, -inf where key j lies
+    after query i (query i sits at position L-W+i).  [W][L] fp64."""
+    L = keys.shape[0]
+    W = q_window.shape[0]
+    assert 1 <= W <= L
+    logits = scale * (q_window @ keys.T)
+    q_pos = L - W + np.arange(W)
+    visible = np.arange(L)[None, :] <= q_pos[:, None]
+    return np.where(visible, logits, -np.inf)
+
+
+def window_lse(keys, q_window, scale):
+    """Natural log of the soft-max denominator of every window row:
+    lse_i = log(sum over visible keys j of exp(logit_ij)).  fp64 [W]."""
+    logits = window_logits(keys, q_window, scale)
+    row_max = logits.max(axis=1)
+    return row_max + np.log(np.exp(logits - row_max[:, None]).sum(axis=1))
+
+
+def snapkv_scores_given_lse(keys, q_window, scale, pool_kernel, lse):
+    """The SnapKV-style score when the caller supplies the rows' log-sum-exp:
+    p_ij = exp(logit_ij - lse_i); column sums, pooling and the forced window
+    as in snapkv_scores.  lse: [W]."""
+    L = keys.shape[0]
+    W = q_window.shape[0]
+    lse = np.asarray(lse, dtype=np.float64)
+    assert lse.shape == (W,)
+    p = np.exp(window_logits(keys, q_window, scale) - lse[:, None])   # exp(-inf) = 0
+    col = p.sum(axis=0)
+    prefix = maxpool_same(col[:L - W], pool_kernel) if L > W else col[:0]
+    return np.concatenate([prefix, np.full(W, np.inf)])
+
+
 def knorm_scores(keys):
     """Key-norm score: minus the L2 norm of each key row.  keys: [L][d]."""
     return -np.sqrt((keys * keys).sum(axis=1))
@@ -120,8 +160,10 @@ def streaming_scores(n_tokens, budget, n_sink):
 
 
 def unit_scores(kv_pool, layer, table_row, head, n_tokens, method,
-                q_window_unit=None, scale=None, pool_kernel=7, budget=None, n_sink=4):
-    """Scores of one (request, layer, head) unit read through its block table."""
+                q_window_unit=None, scale=None, pool_kernel=7, budget=None, n_sink=4,
+                lse_unit=None):
+    """Scores of one (request, layer, head) unit read through its block table.
+    lse_unit: the window rows' log-sum-exp, if the caller supplies it."""
     if method == METHOD_STREAMING:
         return streaming_scores(n_tokens, budget, n_sink)
     keys = fetch_rows(kv_pool, layer, table_row, 0, head, n_tokens)
@@ -129,8 +171,10 @@ def unit_scores(kv_pool, layer, table_row, head, n_tokens, method,
         d = keys.shape[1]
         if scale is None or scale <= 0:
             scale = 1.0 / np.sqrt(d)
-        return snapkv_scores(keys, np.asarray(q_window_unit, dtype=np.float64),
-                             scale, pool_kernel)
+        q = np.asarray(q_window_unit, dtype=np.float64)
+        if lse_unit is not None:
+            return snapkv_scores_given_lse(keys, q, scale, pool_kernel, lse_unit)
+        return snapkv_scores(keys, q, scale, pool_kernel)
     if method == METHOD_KNORM:
         return knorm_scores(keys)
     raise ValueError("unknown method")
@@ -196,6 +240,25 @@ def copy_rows(kv_pool, layer, head, old_row, new_row, kept):
                 kv_pool[layer, old_row[idx // bs], kv, head, idx % bs, :]
 
 
+def window_lse_batch(kv_pool, block_tables, seq_lens, q_window, window, method, scale=None):
+    """Log-sum-exp of the window rows of every SnapKV request of a batch:
+    fp64 [n_req][n_layers][n_heads][window], zero for the other requests."""
+    n_layers, _, _, n_heads, _, d = kv_pool.shape
+    n_req = len(seq_lens)
+    if scale is None or scale <= 0:
+        scale = 1.0 / np.sqrt(d)
+    out = np.zeros((n_req, n_layers, n_heads, int(window)), dtype=np.float64)
+    for r in range(n_req):
+        if int(method[r]) != METHOD_SNAPKV:
+            continue
+        for l in range(n_layers):
+            for h in range(n_heads):
+                keys = fetch_rows(kv_pool, l, block_tables[r], 0, h, int(seq_lens[r]))
+                out[r, l, h] = window_lse(keys, np.asarray(q_window[r][l, h], dtype=np.float64),
+                                          scale)
+    return out
+
+
 def per_request(value, n_req):
     """An int (the same for every request) or a sequence of n_req ints."""
     if np.ndim(value) == 0:
@@ -236,7 +299,7 @@ def validate_batch(stack, block_tables, seq_lens, window, method, budget,
 
 def compress_batch(kv_pool, stack, block_tables, seq_lens, q_window, window,
                    method, budget, pool_kernel=7, scale=None, kept_override=None, n_sink=4,
-                   in_place=False):
+                   in_place=False, lse_window=None):
     """The whole stage for one batch, in place.
 
     kv_pool      float16 [n_layers][n_blocks][2][n_heads][block_size][d]
@@ -250,6 +313,8 @@ def compress_batch(kv_pool, stack, block_tables, seq_lens, q_window, window,
     window, pool_kernel  one int for the batch, or int arrays [n_req]
     method, budget  int arrays [n_req]
     n_sink       attention sinks kept by METHOD_STREAMING requests
+    lse_window   optional [n_req][n_layers][n_heads][window]: the log-sum-exp of
+                 every window row, supplied by the caller (SnapKV requests)
     in_place     compact inside the request's own blocks: the kept rows move to
                  slots 0..B-1 of its first ceil(B/bs) blocks (in ascending
                  order, which never overwrites a row still to be read because
@@ -287,8 +352,10 @@ def compress_batch(kv_pool, stack, block_tables, seq_lens, q_window, window,
         for l in range(n_layers):
             for h in range(n_heads):
                 qw = q_window[r][l, h] if m == METHOD_SNAPKV else None
+                lse = (lse_window[r][l, h] if m == METHOD_SNAPKV and lse_window is not None
+                       else None)
                 s = unit_scores(kv_pool, l, block_tables[r], h, L, m, qw, scale,
-                                pool_kernel[r], B, n_sink)
+                                pool_kernel[r], B, n_sink, lse)
                 scores[r][l, h] = s
                 if kept_override is not None:
                     kept[r][l, h] = kept_override[r][l, h]

@@ -521,3 +521,104 @@ def test_per_request_window_and_pool_kernel_equal_separate_uniform_calls():
     wbad[3] = 10                                  # window above the budget
     assert fo.compress_batch(kv.copy(), st4, bt4, lens0.copy(), q, wbad, method, budget,
                              pools)[0] == "EINVAL" and st4.top == top4
+
+
+# ---------------------------------------------------------------- row log-sum-exp handed in
+
+def test_window_lse_hand_example_and_closed_forms():
+    """The normalisers of the hand-worked example (Z in the fixture) and the
+    uniform closed form: all-zero queries give lse_i = log(number of visible keys)."""
+    g = read_golden("snapkv_hand_example.txt")
+    K = np.array(g["K"], dtype=np.float64)
+    Q = np.array(g["Q"], dtype=np.float64)
+    lse = fo.window_lse(K, Q, 1.0)
+    np.testing.assert_allclose(np.exp(lse), g["Z"][0], rtol=1e-7)
+    np.testing.assert_allclose(lse, [math.log(math.e + math.e ** 2 + 5), math.log(math.e + 7)],
+                               rtol=1e-14)
+    rng = np.random.default_rng(11)
+    for L, W, d in [(8, 2, 2), (40, 5, 8), (33, 32, 4), (7, 7, 3)]:
+        lse0 = fo.window_lse(rng.standard_normal((L, d)), np.zeros((W, d)), 0.3)
+        np.testing.assert_allclose(lse0, [math.log(L - W + i + 1) for i in range(W)], rtol=1e-14)
+
+
+def test_window_lse_is_library_logsumexp_of_the_visible_logits():
+    from scipy.special import logsumexp
+    rng = np.random.default_rng(12)
+    L, W, d, scale = 37, 6, 8, 0.41
+    K, Q = rng.standard_normal((L, d)) * 3, rng.standard_normal((W, d)) * 3
+    lse = fo.window_lse(K, Q, scale)
+    for i in range(W):
+        vis = L - W + i + 1                      # keys 0 .. position of query i
+        assert abs(lse[i] - logsumexp(scale * (K[:vis] @ Q[i]))) < 1e-12
+
+
+@pytest.mark.parametrize("L,W,d,kernel,seed", [(24, 4, 4, 1, 0), (50, 7, 8, 7, 1), (19, 19, 4, 3, 2),
+                                               (64, 16, 16, 5, 3)])
+def test_scores_given_exact_lse_equal_the_plain_definition(L, W, d, kernel, seed):
+    rng = np.random.default_rng(seed)
+    K, Q = rng.standard_normal((L, d)) * 2, rng.standard_normal((W, d)) * 2
+    scale = 1.0 / math.sqrt(d)
+    a = fo.snapkv_scores(K, Q, scale, kernel)
+    b = fo.snapkv_scores_given_lse(K, Q, scale, kernel, fo.window_lse(K, Q, scale))
+    np.testing.assert_allclose(b[:L - W], a[:L - W], rtol=1e-12)
+    assert np.isposinf(b[L - W:]).all()
+
+
+def test_scores_given_lse_scale_with_exp_of_minus_the_shift():
+    """A row whose log-sum-exp is handed in too large by t contributes exp(-t)
+    times its soft-max row: with one window query the whole score scales, with
+    two the columns are the weighted sum of the two soft-max rows."""
+    rng = np.random.default_rng(13)
+    L, d = 30, 8
+    K, Q = rng.standard_normal((L, d)), rng.standard_normal((2, d))
+    lse1 = fo.window_lse(K, Q[1:], 0.5)
+    base = fo.snapkv_scores(K, Q[1:], 0.5, 1)
+    got = fo.snapkv_scores_given_lse(K, Q[1:], 0.5, 1, lse1 + 0.75)
+    np.testing.assert_allclose(got[:L - 1], math.exp(-0.75) * base[:L - 1], rtol=1e-12)
+    # two rows, written out densely a second way
+    lse = fo.window_lse(K, Q, 0.5)
+    got2 = fo.snapkv_scores_given_lse(K, Q, 0.5, 1, lse + np.array([0.2, -0.4]))
+    rows = []
+    for i in range(2):
+        vis = L - 2 + i + 1
+        z = 0.5 * (K[:vis] @ Q[i])
+        p = np.exp(z - z.max())
+        p /= p.sum()
+        rows.append(np.concatenate([p, np.zeros(L - vis)]))
+    expect = math.exp(-0.2) * rows[0] + math.exp(0.4) * rows[1]
+    np.testing.assert_allclose(got2[:L - 2], expect[:L - 2], rtol=1e-12)
+
+
+def test_compress_batch_with_lse_equals_without_and_lse_batch_layout():
+    rng = np.random.default_rng(14)
+    n_layers, n_heads, bs, d, n_blocks = 2, 2, 4, 8, 40
+    kv = rng.standard_normal((n_layers, n_blocks, 2, n_heads, bs, d)).astype(np.float16)
+    lens = np.array([21, 9, 14])
+    methods = np.array([fo.METHOD_SNAPKV, fo.METHOD_KNORM, fo.METHOD_SNAPKV])
+    budgets = np.array([8, 4, 6])
+    W = 3
+    q = rng.standard_normal((3, n_layers, n_heads, W, d)).astype(np.float16)
+
+    def fresh():
+        st = fo.FreeStack(n_blocks)
+        bt = np.full((3, 8), -1, dtype=np.int32)
+        for r in range(3):
+            nb = fo.blocks_for(int(lens[r]), bs)
+            bt[r, :nb] = st.alloc(nb)
+        return kv.copy(), st, bt, lens.copy()
+
+    kv_a, st_a, bt_a, lens_a = fresh()
+    lse = fo.window_lse_batch(kv_a, bt_a, lens_a, q, W, methods)
+    assert lse.shape == (3, n_layers, n_heads, W) and (lse[1] == 0).all()
+    keys = fo.fetch_rows(kv_a, 1, bt_a[2], 0, 0, 14)
+    np.testing.assert_allclose(lse[2, 1, 0],
+                               fo.window_lse(keys, q[2, 1, 0].astype(np.float64), 1 / math.sqrt(d)))
+    status, s_a, k_a = fo.compress_batch(kv_a, st_a, bt_a, lens_a, q, W, methods, budgets, 3)
+    kv_b, st_b, bt_b, lens_b = fresh()
+    status_b, s_b, k_b = fo.compress_batch(kv_b, st_b, bt_b, lens_b, q, W, methods, budgets, 3,
+                                           lse_window=lse)
+    assert status is None and status_b is None
+    for r in range(3):
+        np.testing.assert_allclose(s_b[r], s_a[r], rtol=1e-12)
+        assert (k_b[r] == k_a[r]).all()
+    assert (kv_a == kv_b).all() and (bt_a == bt_b).all() and st_a.top == st_b.top
