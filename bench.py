@@ -426,9 +426,12 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="config4",
-                    choices=["config2", "config3", "config4", "config4_streaming", "config4_mlp",
-                             "config4_decode", "replay"],
-                    help="config4_streaming: the config-4 batch with every request using the "
+                    choices=["config2", "config3", "config4", "config3_lse", "config4_lse",
+                             "config4_streaming", "config4_mlp", "config4_decode", "replay"],
+                    help="configN_lse: the batch of config N with the window rows' log-sum-exp "
+                         "supplied as an input (computed before the timed region, as the "
+                         "prefill's attention kernel would have), one pass over K; "
+                         "config4_streaming: the config-4 batch with every request using the "
                          "score-free sinks + recent rule (gather and pool work only); "
                          "config4_mlp: the config-4 batch through the chunk-MLP compressor "
                          "(k = 5, hidden 256, synthetic weights)")
@@ -489,6 +492,12 @@ def main():
     dw = DeviceWorkload(wl, verbose=True)
     fc.fc_set_score_mode(dw.pool, {"auto": 0, "two_pass": 1, "one_pass": 2}[args.score_mode])
     fc.fc_set_profiling(dw.pool, True)
+    lse_ms = None
+    if args.workload.endswith("_lse"):
+        wl.name += "_lse_supplied"
+        dw.compute_lse()
+        dw.compute_lse()
+        lse_ms = fc.fc_get_kernel_times(dw.pool)["window_lse"]
     for _ in range(args.warmup):
         dw.rewind()
         dw.compress()
@@ -555,6 +564,9 @@ def main():
             else None,
         },
     }
+    if lse_ms is not None:
+        out["config"]["lse_input"] = ("fc_window_lse before the timed region, %.3f ms "
+                                      "(not part of value)" % lse_ms)
     if args.cpu_seconds > 0:
         out["cpu_baseline"] = cpu_baseline(dw, args.cpu_seconds)
     dw.close()

@@ -176,6 +176,52 @@ int fc_compress_batch_var(fc_pool* pool, int32_t* dev_block_tables, int max_bloc
                           void* stream);
 
 /*
+ * The pruning stage (Algorithm 1, "Batch compression") when the caller already
+ * has the soft-max denominators of the observation-window rows.  The prefill
+ * that comes right before the stage in Algorithm 1 (M.Prefill) runs attention
+ * for exactly these queries over exactly these keys, and fused attention
+ * kernels return, per query row, the natural logarithm of the sum of
+ * exp(logit) over the keys the row sees.  With that number the score of key j,
+ * sum_i exp(scale * q_i . k_j - lse_i), needs one pass over K instead of two.
+ *
+ * dev_lse_window    dev, fp32 [n_req][n_layers][n_heads][window], 4-byte
+ *                   aligned; entry i of a unit = log(sum over keys j at
+ *                   positions <= L - window + i of exp(scale * q_i . k_j)),
+ *                   with the same scale as this call.  Read for SNAPKV requests
+ *                   only.  The library does not check it: a row whose entry is
+ *                   off by t contributes exp(-t) times its soft-max row.
+ * Everything else, including errors, as for fc_compress_batch; additionally
+ * FC_EINVAL if a SNAPKV request is present and dev_lse_window is NULL, or if
+ * the scheduling is FC_SCORE_ONE_PASS (which is itself a way to read K once).
+ */
+int fc_compress_batch_lse(fc_pool* pool, int32_t* dev_block_tables, int max_blocks_per_req,
+                          int32_t* host_seq_lens, const void* dev_q_window,
+                          const float* dev_lse_window, int window, const int32_t* host_method,
+                          const int32_t* host_budget, int n_req, int pool_kernel, float scale,
+                          float* dev_scores_out, int32_t* dev_kept_out, void* stream);
+
+/*
+ * The row log-sum-exp that fc_compress_batch_lse takes, computed from the pool
+ * (one pass over K; the first half of what fc_compress_batch does for a SNAPKV
+ * request), for callers whose attention kernel does not return it.  Reads the
+ * pool, changes nothing: no allocation, tables and lengths untouched.
+ *
+ * dev_block_tables, max_blocks_per_req, host_seq_lens, dev_q_window, window,
+ * scale             as for fc_compress_batch (host_seq_lens is read only).
+ * host_method       host, int32 [n_req] or NULL: rows are computed for requests
+ *                   with FC_METHOD_SNAPKV (all requests if NULL).
+ * dev_lse_out       dev, fp32 [n_req][n_layers][n_heads][window]; rows of the
+ *                   other requests are left as they are.
+ * FC_EINVAL: window outside 1..FC_MAX_WINDOW, a computed request with L < window,
+ * L > FC_MAX_SEQ_LEN or ceil(L/16) > max_blocks_per_req, NULL or misaligned
+ * buffers.  Asynchronous on `stream`.
+ */
+int fc_window_lse(fc_pool* pool, const int32_t* dev_block_tables, int max_blocks_per_req,
+                  const int32_t* host_seq_lens, const void* dev_q_window, int window,
+                  const int32_t* host_method, int n_req, float scale, float* dev_lse_out,
+                  void* stream);
+
+/*
  * The paper's own compressor shape ("Multimodal Compressor" section): the cache
  * is split at the modality boundary, every run of k consecutive tokens of one
  * modality is reshaped into one vector of k*head_dim numbers and mapped to ONE
@@ -266,7 +312,7 @@ int fc_set_score_mode(fc_pool* pool, int mode);
  * fc_kernel_name(i) names slot i.  fc_set_profiling(pool, 1) restarts the
  * average.
  */
-#define FC_N_KERNELS 10
+#define FC_N_KERNELS 11
 int fc_set_profiling(fc_pool* pool, int enable);
 int fc_get_kernel_times(fc_pool* pool, float* host_ms);
 const char* fc_kernel_name(int i);

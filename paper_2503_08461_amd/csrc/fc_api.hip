@@ -40,7 +40,7 @@ int fail(int code, const char* fmt, ...) {
 const char* const kKernelNames[K_COUNT] = {"plan_alloc", "snapkv_score", "knorm_score",
                                            "select",     "gather",       "reclaim",
                                            "fused_unit", "mlp_compress", "append",
-                                           "decode_attention"};
+                                           "decode_attention", "window_lse"};
 
 size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -308,6 +308,7 @@ int fc_pool_import_state_dev(fc_pool* p, const int32_t* dev_stack, int top, void
 // NULL for the call that takes one size for the whole batch.
 static int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_req,
                                int32_t* host_seq_lens, const void* dev_q_window,
+                               const float* dev_lse_window, bool need_lse,
                                const int32_t* host_window, int window,
                                const int32_t* host_method, const int32_t* host_budget, int n_req,
                                const int32_t* host_pool_kernel, int pool_kernel, float scale,
@@ -361,6 +362,10 @@ static int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_bl
         return fail(FC_EINVAL, "request %d: SnapKV needs length and budget >= window", r);
       if (!dev_q_window || (reinterpret_cast<uintptr_t>(dev_q_window) & 15))
         return fail(FC_EINVAL, "dev_q_window must be a 16-byte aligned device pointer");
+      if (need_lse && (!dev_lse_window || (reinterpret_cast<uintptr_t>(dev_lse_window) & 3)))
+        return fail(FC_EINVAL, "dev_lse_window must be a 4-byte aligned device pointer");
+      if (need_lse && p->score_mode == FC_SCORE_ONE_PASS)
+        return fail(FC_EINVAL, "the one-pass scheduling takes no log-sum-exp input");
       window_lo = window_lo == 0 ? win : std::min(window_lo, win);
       window_hi = std::max(window_hi, win);
     }
@@ -472,7 +477,8 @@ static int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_bl
   // heaviest first: bytes a unit moves (K once or twice, kept K/V read and written)
   auto weight = [&](int i) {
     const ReqDesc& d = descs[i];
-    const int passes = d.method == FC_METHOD_SNAPKV ? 2 : d.method == FC_METHOD_KNORM ? 1 : 0;
+    const int passes = d.method == FC_METHOD_SNAPKV ? (need_lse ? 1 : 2)
+                                                    : d.method == FC_METHOD_KNORM ? 1 : 0;
     return (int64_t)d.seq_len * passes + (int64_t)d.budget * 4;
   };
   std::stable_sort(sorted.begin(), sorted.end(),
@@ -534,6 +540,8 @@ static int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_bl
   bp.old_ids = p->ids;
   bp.new_ids = p->ids + total_old;
   bp.q_window = static_cast<const _Float16*>(dev_q_window);
+  bp.lse_window = need_lse ? dev_lse_window : nullptr;
+  bp.lse_out = nullptr;
   bp.window = window_hi;
   bp.n_sink = p->n_sink;
   bp.in_place = in_place ? 1 : 0;
@@ -609,8 +617,107 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
                       int pool_kernel, float scale, float* dev_scores_out, int32_t* dev_kept_out,
                       void* stream) {
   return compress_batch_impl(p, dev_block_tables, max_blocks_per_req, host_seq_lens, dev_q_window,
-                             nullptr, window, host_method, host_budget, n_req, nullptr,
-                             pool_kernel, scale, dev_scores_out, dev_kept_out, stream);
+                             nullptr, false, nullptr, window, host_method, host_budget, n_req,
+                             nullptr, pool_kernel, scale, dev_scores_out, dev_kept_out, stream);
+}
+
+int fc_compress_batch_lse(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_req,
+                          int32_t* host_seq_lens, const void* dev_q_window,
+                          const float* dev_lse_window, int window, const int32_t* host_method,
+                          const int32_t* host_budget, int n_req, int pool_kernel, float scale,
+                          float* dev_scores_out, int32_t* dev_kept_out, void* stream) {
+  return compress_batch_impl(p, dev_block_tables, max_blocks_per_req, host_seq_lens, dev_q_window,
+                             dev_lse_window, true, nullptr, window, host_method, host_budget,
+                             n_req, nullptr, pool_kernel, scale, dev_scores_out, dev_kept_out,
+                             stream);
+}
+
+int fc_window_lse(fc_pool* p, const int32_t* dev_block_tables, int max_blocks_per_req,
+                  const int32_t* host_seq_lens, const void* dev_q_window, int window,
+                  const int32_t* host_method, int n_req, float scale, float* dev_lse_out,
+                  void* stream_) {
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  if (!p) return fail(FC_EINVAL, "pool is NULL");
+  if (n_req < 0) return fail(FC_EINVAL, "n_req < 0");
+  if (n_req == 0) return FC_OK;
+  if (!dev_block_tables || !host_seq_lens || !dev_q_window || !dev_lse_out)
+    return fail(FC_EINVAL, "NULL argument");
+  if (reinterpret_cast<uintptr_t>(dev_q_window) & 15)
+    return fail(FC_EINVAL, "dev_q_window must be 16-byte aligned");
+  if (reinterpret_cast<uintptr_t>(dev_lse_out) & 3)
+    return fail(FC_EINVAL, "dev_lse_out must be 4-byte aligned");
+  if (max_blocks_per_req < 1) return fail(FC_EINVAL, "max_blocks_per_req < 1");
+  if (window < 1 || window > FC_MAX_WINDOW)
+    return fail(FC_EINVAL, "window %d outside 1..%d", window, FC_MAX_WINDOW);
+  const size_t n_lh = (size_t)p->n_layers * p->n_heads;
+  std::vector<ReqDesc> descs;
+  for (int r = 0; r < n_req; ++r) {
+    if (host_method && host_method[r] != FC_METHOD_SNAPKV) continue;
+    const int L = host_seq_lens[r];
+    if (L < window || L > FC_MAX_SEQ_LEN)
+      return fail(FC_EINVAL, "request %d: length %d outside %d..%d", r, L, window, FC_MAX_SEQ_LEN);
+    ReqDesc d = {};
+    d.window = window;
+    d.pool_kernel = 1;
+    d.seq_len = L;
+    d.budget = L;
+    d.method = FC_METHOD_SNAPKV;
+    d.table_row = r;
+    d.n_old = (L + FC_BLOCK_SIZE - 1) / FC_BLOCK_SIZE;
+    if (d.n_old > max_blocks_per_req)
+      return fail(FC_EINVAL, "request %d: %d blocks exceed max_blocks_per_req %d", r, d.n_old,
+                  max_blocks_per_req);
+    d.q_off = (int64_t)((size_t)r * n_lh * window * p->head_dim);
+    descs.push_back(d);
+  }
+  if (descs.empty()) return FC_OK;
+  // longest first, so that the tail of the launch is made of short units
+  std::stable_sort(descs.begin(), descs.end(),
+                   [](const ReqDesc& a, const ReqDesc& b) { return a.seq_len > b.seq_len; });
+  const int n = (int)descs.size();
+  const size_t desc_bytes = round_up((size_t)n * sizeof(ReqDesc), 16);
+  const size_t meta_bytes = desc_bytes + round_up((size_t)n * sizeof(int32_t), 16);
+  int rc;
+  if ((rc = grow_meta(p, meta_bytes)) != FC_OK) return rc;
+  if (p->meta_pending) {
+    FC_HIP(hipEventSynchronize(p->meta_event));
+    p->meta_pending = false;
+  }
+  memcpy(p->host_meta, descs.data(), (size_t)n * sizeof(ReqDesc));
+  int32_t* order = reinterpret_cast<int32_t*>(p->host_meta + desc_bytes);
+  for (int i = 0; i < n; ++i) order[i] = i;
+  FC_HIP(hipMemcpyAsync(p->dev_meta, p->host_meta, meta_bytes, hipMemcpyHostToDevice, stream));
+  FC_HIP(hipEventRecord(p->meta_event, stream));
+  p->meta_pending = true;
+
+  BatchParams bp = {};
+  bp.kv = p->kv;
+  bp.n_blocks = p->n_blocks;
+  bp.n_layers = p->n_layers;
+  bp.n_heads = p->n_heads;
+  bp.head_dim = p->head_dim;
+  bp.descs = reinterpret_cast<const ReqDesc*>(p->dev_meta);
+  bp.order_snap = reinterpret_cast<const int32_t*>(p->dev_meta + desc_bytes);
+  bp.n_snap = n;
+  bp.block_tables = const_cast<int32_t*>(dev_block_tables);  // read only on this path
+  bp.max_blocks = max_blocks_per_req;
+  bp.q_window = static_cast<const _Float16*>(dev_q_window);
+  bp.lse_out = dev_lse_out;
+  bp.window = window;
+  const float sc = (scale > 0.f) ? scale : 1.0f / sqrtf((float)p->head_dim);
+  bp.scale_log2e = sc * 1.44269504088896340736f;
+  const int ring = p->prof_calls % kProfRing;
+  if (p->profiling) {
+    for (int k = 0; k < K_COUNT; ++k) p->timed[ring][k] = false;
+    ++p->prof_calls;
+    FC_HIP(hipEventRecord(p->ev[ring][K_WINDOW_LSE][0], stream));
+  }
+  FC_HIP(launch_snapkv_score(bp, stream));
+  if (p->profiling) {
+    FC_HIP(hipEventRecord(p->ev[ring][K_WINDOW_LSE][1], stream));
+    p->timed[ring][K_WINDOW_LSE] = true;
+  }
+  return FC_OK;
 }
 
 int fc_compress_batch_var(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_req,
@@ -621,8 +728,8 @@ int fc_compress_batch_var(fc_pool* p, int32_t* dev_block_tables, int max_blocks_
                           void* stream) {
   if (n_req > 0 && (!host_window || !host_pool_kernel)) return fail(FC_EINVAL, "NULL argument");
   return compress_batch_impl(p, dev_block_tables, max_blocks_per_req, host_seq_lens, dev_q_window,
-                             host_window, 0, host_method, host_budget, n_req, host_pool_kernel, 0,
-                             scale, dev_scores_out, dev_kept_out, stream);
+                             nullptr, false, host_window, 0, host_method, host_budget, n_req,
+                             host_pool_kernel, 0, scale, dev_scores_out, dev_kept_out, stream);
 }
 
 int fc_mlp_set_weights(fc_pool* p, const fc_mlp_weights* w, void* stream_) {

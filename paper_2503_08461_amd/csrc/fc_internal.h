@@ -103,6 +103,9 @@ struct BatchParams {
   int32_t* old_ids;            // [total_old] saved pre-compression ids
   int32_t* new_ids;            // [total_new]
   const _Float16* q_window;
+  const float* lse_window;     // nullable: natural log-sum-exp of every window row, packed like
+                               // q_window without the channel axis; pass 1 is skipped
+  float* lse_out;              // nullable: write that quantity (from pass 1) and stop
   int32_t window;              // a bound on the windows of this launch's SnapKV units (picks the
                                // number of 16-row query tiles); the unit's own is in its descriptor
   int32_t n_sink;              // leading tokens kept by streaming requests
@@ -128,7 +131,8 @@ enum KernelSlot {
   K_MLP = 7,
   K_APPEND = 8,
   K_DECODE_ATTENTION = 9,
-  K_COUNT = 10
+  K_WINDOW_LSE = 10,
+  K_COUNT = 11
 };
 
 // Launchers (fc_kernels.hip).  Each returns the hipError_t of the launch.

@@ -133,6 +133,16 @@ __device__ __forceinline__ void snapkv_unit(const BatchParams& p, const ReqDesc&
     for (int ks = 0; ks < KS; ++ks) k[ks] = load_half8(kp + ks * 32);
   };
 
+  // log2 of every row's soft-max denominator goes to sh.fin: handed in by the
+  // caller (natural log, from its attention kernel), or pass 1 below
+  const size_t lse_off = (size_t)(rd.q_off / D) + (size_t)lh * W;
+  if (p.lse_window != nullptr) {  // uniform
+    if (threadIdx.x < 64)
+      sh.fin[threadIdx.x] = (int)threadIdx.x < W
+                                ? p.lse_window[lse_off + threadIdx.x] * 1.44269504088896340736f
+                                : INFINITY;  // padded rows contribute exp2(-inf) = 0
+    __syncthreads();
+  } else {
   // ---- pass 1: row maxima and normalisers --------------------------------
   float m[NT], z[NT];
 #pragma unroll
@@ -200,6 +210,12 @@ __device__ __forceinline__ void snapkv_unit(const BatchParams& p, const ReqDesc&
     sh.fin[row] = out;
   }
   __syncthreads();
+  }
+  if (p.lse_out != nullptr) {  // uniform: the caller asked for the denominators only
+    if ((int)threadIdx.x < W)
+      p.lse_out[lse_off + threadIdx.x] = sh.fin[threadIdx.x] * 0.69314718055994530942f;
+    return;
+  }
 
   // ---- pass 2: column sums of the soft-maxed rows over the prefix ---------
   const int n_prefix = L - W;
@@ -245,7 +261,10 @@ __global__ __launch_bounds__(kThreads) void snapkv_score_kernel(BatchParams p) {
   const int lh = blockIdx.x - slot * n_lh;
   const ReqDesc rd = p.descs[p.order_snap[slot]];
   float* raw = p.raw_scores + rd.raw_off + (size_t)lh * rd.seq_len;
-  snapkv_unit<D, NT>(p, rd, lh, p.old_ids + rd.old_off, sh, [&](int j, float v) { raw[j] = v; });
+  // the denominators-only call runs outside a compression: no saved ids, the table row itself
+  const int32_t* ids = p.lse_out != nullptr ? p.block_tables + (size_t)rd.table_row * p.max_blocks
+                                            : p.old_ids + rd.old_off;
+  snapkv_unit<D, NT>(p, rd, lh, ids, sh, [&](int j, float v) { raw[j] = v; });
 }
 
 // ---------------------------------------------------------------------------

@@ -16,6 +16,7 @@ class DeviceWorkload:
         if verbose:
             print("[setup] %s: pool %.1f GiB, %d requests, %d tokens" % (
                 wl.name, wl.pool_bytes() / 2**30, wl.n_req, wl.total_tokens), flush=True)
+        self.lse = None
         self.kv = torch.empty(wl.pool_shape(), dtype=torch.float16, device=self.dev)
         synth.fill_pool_device(wl, self.kv)
         self.q = synth.fill_q_window_device(wl, self.dev)
@@ -50,8 +51,23 @@ class DeviceWorkload:
 
     def compress(self, scores_out=None, kept_out=None):
         wl = self.wl
+        if self.lse is not None:
+            fc.fc_compress_batch_lse(self.pool, self.bt, self.lens, self.q, self.lse, wl.window,
+                                     wl.methods, wl.budgets, wl.pool_kernel, 0.0, scores_out,
+                                     kept_out)
+            return
         fc.fc_compress_batch(self.pool, self.bt, self.lens, self.q, wl.window, wl.methods,
                              wl.budgets, wl.pool_kernel, 0.0, scores_out, kept_out)
+
+    def compute_lse(self):
+        """The window rows' log-sum-exp (what a prefill attention kernel would
+        hand over), computed by the library; compress() then takes it as input."""
+        wl = self.wl
+        lse = self.torch.zeros((wl.n_req, wl.n_layers, wl.n_heads, wl.window),
+                               dtype=self.torch.float32, device=self.dev)
+        fc.fc_window_lse(self.pool, self.bt, self.lens, self.q, wl.window, wl.methods, lse)
+        self.torch.cuda.synchronize()
+        self.lse = lse
 
     def close(self):
         fc.fc_pool_destroy(self.pool)

@@ -15,7 +15,7 @@ FC_OK, FC_EINVAL, FC_ENOMEM, FC_EDEVICE = 0, -1, -2, -3
 FC_METHOD_NONE, FC_METHOD_SNAPKV, FC_METHOD_KNORM, FC_METHOD_STREAMING = 0, 1, 2, 3
 FC_DTYPE_F16 = 0
 FC_BLOCK_SIZE = 16
-FC_N_KERNELS = 10
+FC_N_KERNELS = 11
 FC_SCORE_AUTO, FC_SCORE_TWO_PASS, FC_SCORE_ONE_PASS = 0, 1, 2
 FC_COMPACT_FRESH, FC_COMPACT_IN_PLACE = 0, 1
 
@@ -25,7 +25,8 @@ EXPORTS = [
     "fc_pool_create", "fc_pool_destroy", "fc_pool_alloc", "fc_pool_free",
     "fc_pool_num_free", "fc_pool_export_state", "fc_pool_import_state",
     "fc_pool_import_state_dev",
-    "fc_compress_batch", "fc_compress_batch_var", "fc_append_batch", "fc_decode_attention",
+    "fc_compress_batch", "fc_compress_batch_var", "fc_compress_batch_lse", "fc_window_lse",
+    "fc_append_batch", "fc_decode_attention",
     "fc_decode_attention_kept",
     "fc_mlp_set_weights", "fc_compress_batch_mlp", "fc_set_compaction_mode", "fc_set_streaming_sinks", "fc_set_score_mode", "fc_set_profiling", "fc_get_kernel_times",
     "fc_kernel_name", "fc_last_error",
@@ -86,6 +87,9 @@ def load_library():
                                       ctypes.c_float, vp, vp, vp]
     lib.fc_compress_batch_var.argtypes = [vp, vp, i, i32p, vp, i32p, i32p, i32p, i32p, i,
                                           ctypes.c_float, vp, vp, vp]
+    lib.fc_compress_batch_lse.argtypes = [vp, vp, i, i32p, vp, vp, i, i32p, i32p, i, i,
+                                          ctypes.c_float, vp, vp, vp]
+    lib.fc_window_lse.argtypes = [vp, vp, i, i32p, vp, i, i32p, i, ctypes.c_float, vp, vp]
     lib.fc_append_batch.argtypes = [vp, vp, i, i32p, vp, i32p, i, vp]
     lib.fc_decode_attention.argtypes = [vp, vp, i, i32p, vp, vp, i, ctypes.c_float, vp]
     lib.fc_decode_attention_kept.argtypes = [vp, vp, i, i32p, i32p, vp, vp, vp, i, ctypes.c_float,
@@ -256,6 +260,65 @@ def fc_compress_batch(pool, block_tables, seq_lens, q_window, window, method, bu
         _host_i32(method), _host_i32(budget), n_req, int(pool_kernel), float(scale),
         _dev_ptr(scores_out, torch.float32), _dev_ptr(kept_out, torch.int32),
         _stream_ptr(stream)))
+
+
+def fc_compress_batch_lse(pool, block_tables, seq_lens, q_window, lse_window, window, method,
+                          budget, pool_kernel=7, scale=0.0, scores_out=None, kept_out=None,
+                          stream=None):
+    """As fc_compress_batch, with lse_window: fp32 device tensor
+    [n_req][n_layers][n_heads][window], the log-sum-exp of every window row."""
+    import torch
+    lib = load_library()
+    n_req = int(seq_lens.shape[0])
+    if block_tables.dim() != 2 or block_tables.shape[0] != n_req:
+        raise ValueError("block_tables must be [n_req][max_blocks]")
+    if method.shape[0] != n_req or budget.shape[0] != n_req:
+        raise ValueError("method / budget must have n_req entries")
+    if q_window is not None:
+        want = (n_req, pool.n_layers, pool.n_heads, window, pool.head_dim)
+        if tuple(q_window.shape) != want:
+            raise ValueError("q_window must have shape %s" % (want,))
+    if lse_window is not None and tuple(lse_window.shape) != (n_req, pool.n_layers, pool.n_heads,
+                                                              window):
+        raise ValueError("lse_window must be [n_req][n_layers][n_heads][window]")
+    comp = method != FC_METHOD_NONE
+    if scores_out is not None:
+        need = int((seq_lens[comp].astype(np.int64)).sum()) * pool.n_layers * pool.n_heads
+        if scores_out.numel() < need:
+            raise ValueError("scores_out too small")
+    if kept_out is not None:
+        need = int((budget[comp].astype(np.int64)).sum()) * pool.n_layers * pool.n_heads
+        if kept_out.numel() < need:
+            raise ValueError("kept_out too small")
+    _check(lib.fc_compress_batch_lse(
+        pool.ptr, _dev_ptr(block_tables, torch.int32), int(block_tables.shape[1]),
+        _host_i32(seq_lens), _dev_ptr(q_window, torch.float16),
+        _dev_ptr(lse_window, torch.float32), int(window), _host_i32(method), _host_i32(budget),
+        n_req, int(pool_kernel), float(scale), _dev_ptr(scores_out, torch.float32),
+        _dev_ptr(kept_out, torch.int32), _stream_ptr(stream)))
+
+
+def fc_window_lse(pool, block_tables, seq_lens, q_window, window, method, lse_out, scale=0.0,
+                  stream=None):
+    """lse_out: fp32 device tensor [n_req][n_layers][n_heads][window], rows of the
+    SnapKV requests (all requests if method is None) are written."""
+    import torch
+    lib = load_library()
+    n_req = int(seq_lens.shape[0])
+    if block_tables.dim() != 2 or block_tables.shape[0] != n_req:
+        raise ValueError("block_tables must be [n_req][max_blocks]")
+    if method is not None and method.shape[0] != n_req:
+        raise ValueError("method must have n_req entries")
+    want = (n_req, pool.n_layers, pool.n_heads, window, pool.head_dim)
+    if q_window is not None and tuple(q_window.shape) != want:
+        raise ValueError("q_window must have shape %s" % (want,))
+    if lse_out is not None and tuple(lse_out.shape) != want[:4]:
+        raise ValueError("lse_out must be [n_req][n_layers][n_heads][window]")
+    _check(lib.fc_window_lse(
+        pool.ptr, _dev_ptr(block_tables, torch.int32), int(block_tables.shape[1]),
+        _host_i32(seq_lens), _dev_ptr(q_window, torch.float16), int(window),
+        _host_i32(method) if method is not None else None, n_req, float(scale),
+        _dev_ptr(lse_out, torch.float32), _stream_ptr(stream)))
 
 
 def fc_compress_batch_var(pool, block_tables, seq_lens, q_window, window, method, budget,

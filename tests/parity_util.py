@@ -104,8 +104,12 @@ class SideBySide:
         assert (stack_g[:top_g] == self.stack.stack[:top_g]).all(), "free stacks differ"
 
     def compress_and_compare(self, methods=None, budgets=None, window=None, pool_kernel=None,
-                             scale=0.0, n_sink=4, q_list=None):
+                             scale=0.0, n_sink=4, q_list=None, lse=None):
         """One fc_compress_batch on both sides + full comparison.  Returns stats.
+        lse = "oracle": the window rows' log-sum-exp comes from the oracle, is
+        rounded to fp32 and handed to both sides (fc_compress_batch_lse);
+        lse = "library": fc_window_lse computes it (checked against the oracle's)
+        and the oracle runs the plain two-pass definition.
         With q_list (per request: fp16 array [n_layers][n_heads][window_r][d] or
         None), window and pool_kernel are int32 arrays and the call is
         fc_compress_batch_var."""
@@ -124,7 +128,29 @@ class SideBySide:
         kept_dev = torch.full((max(n_kept, 1),), -7, dtype=torch.int32, device=self.dev)
         fc.fc_set_streaming_sinks(self.pool, n_sink)
         q_host = self.q_host
-        if q_list is None:
+        lse_host = None
+        if lse is not None:
+            assert q_list is None
+            lse_o = fo.window_lse_batch(self.kv_host, self.bt_host, lens_before, q_host, window,
+                                        methods, scale if scale > 0 else None)
+            if lse == "oracle":
+                lse_host = lse_o.astype(np.float32)
+                lse_dev = torch.from_numpy(lse_host).to(self.dev)
+            else:
+                lse_dev = torch.full(lse_o.shape, float("nan"), dtype=torch.float32,
+                                     device=self.dev)
+                fc.fc_window_lse(self.pool, self.bt_dev, lens_before, self.q_dev, window, methods,
+                                 lse_dev, scale)
+                got = lse_dev.cpu().numpy()
+                snap = methods == fo.METHOD_SNAPKV
+                assert np.isnan(got[~snap]).all(), "rows of other requests were written"
+                # same bar as the scores: exp(logit - lse) moves by the absolute error of lse
+                assert np.abs(got[snap] - lse_o[snap]).max() <= REL_TOL, "log-sum-exp differs"
+                lse_dev[torch.from_numpy(~snap).to(self.dev)] = 0.0
+            fc.fc_compress_batch_lse(self.pool, self.bt_dev, self.lens_g, self.q_dev, lse_dev,
+                                     window, methods, budgets, pool_kernel, scale, scores_dev,
+                                     kept_dev)
+        elif q_list is None:
             fc.fc_compress_batch(self.pool, self.bt_dev, self.lens_g, self.q_dev, window,
                                  methods, budgets, pool_kernel, scale, scores_dev, kept_dev)
         else:
@@ -144,7 +170,8 @@ class SideBySide:
         bt_a, lens_a = self.bt_host.copy(), self.lens_o.copy()
         status, scores_o, kept_o = fo.compress_batch(
             kv_a, st_a, bt_a, lens_a, q_host, window, methods, budgets, pool_kernel,
-            scale if scale > 0 else None, n_sink=n_sink, in_place=self.in_place)
+            scale if scale > 0 else None, n_sink=n_sink, in_place=self.in_place,
+            lse_window=lse_host)
         assert status is None, status
 
         # ... compared unit by unit
