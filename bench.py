@@ -28,6 +28,8 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 MEASURED_TRAFFIC_BYTES = {
     ("config3_batched_mixed", "fused_unit"): 25.95e9,
     ("config4_multi_image", "fused_unit"): 214.57e9,
+    # profiles/fused_unit_kernel_config4_lse.md
+    ("config4_multi_image_lse_supplied", "fused_unit"): 138.12e9,
     # profiles/mlp_compress_kernel_config4_mlp.md
     ("config4_multi_image_mlp", "mlp_compress"): 211.99e9,
 }
