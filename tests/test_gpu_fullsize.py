@@ -31,8 +31,12 @@ def _oracle_pool_replay(wl):
     return st, bt0, bt, lens
 
 
-@pytest.mark.parametrize("config,n_samples", [(2, 48), (3, 40), (4, 24)])
-def test_fullsize_batch(config, n_samples):
+@pytest.mark.parametrize("config,n_samples,lse", [(2, 48, False), (3, 40, False), (4, 24, False),
+                                                  (3, 16, True), (4, 16, True)])
+def test_fullsize_batch(config, n_samples, lse):
+    """lse: the window rows' log-sum-exp is produced by fc_window_lse and the
+    batch goes through fc_compress_batch_lse (what bench.py's configN_lse
+    workloads time); the result must still match the plain definition."""
     import torch
     from paper_2503_08461_amd import fastcache as fc
     from paper_2503_08461_amd.device_setup import DeviceWorkload
@@ -49,6 +53,8 @@ def test_fullsize_batch(config, n_samples):
         n_kept = int(wl.budgets.astype(np.int64).sum()) * n_lh
         scores = torch.empty(n_scores, dtype=torch.float32, device=dw.dev)
         kept = torch.empty(n_kept, dtype=torch.int32, device=dw.dev)
+        if lse:
+            dw.compute_lse()
         dw.compress(scores, kept)
         torch.cuda.synchronize()
         print("compressed", flush=True)
@@ -102,6 +108,13 @@ def test_fullsize_batch(config, n_samples):
                 wl.window, wl.pool_kernel, sg, kg, "(%s req %d layer %d head %d)" % (wl.name, r, l, h))
             worst = max(worst, err)
             same_cnt += int(same)
+            if lse and q is not None:
+                ids = torch.from_numpy(bt0_o[r, :n_old].astype(np.int64)).to(dw.dev)
+                keys = dw.kv[l, ids, 0, h].cpu().numpy().reshape(-1, wl.head_dim)[:L]
+                want = fo.window_lse(keys.astype(np.float64), q.astype(np.float64),
+                                     1.0 / np.sqrt(wl.head_dim))
+                got = dw.lse[r, l, h].cpu().numpy()
+                assert np.abs(got - want).max() <= 2e-3, "log-sum-exp (req %d)" % r
         print("sampled units: %d, kept identical: %d, max rel score err %.2e" % (
             n_samples, same_cnt, worst), flush=True)
         assert worst < 2e-3
