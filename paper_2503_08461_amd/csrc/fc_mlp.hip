@@ -19,7 +19,7 @@
 //     pre-permutation of W2.  The hidden activations therefore never leave
 //     registers.
 // A workgroup handles tiles of 256 rows (row = (layer, head, K|V) x chunk of
-// one request and one modality), 32 NT per wavefront; the kernel
+// one request and one modality), NT column tiles of 32 rows per wavefront; the kernel
 // is persistent (one workgroup per CU walks the tile list) so that W2 is loaded
 // into LDS once per modality change rather than once per tile.
 
@@ -168,7 +168,7 @@ __global__ __launch_bounds__(mlp_threads(NT), 1) void mlp_compress_kernel(BatchP
     const half8* w1g = reinterpret_cast<const half8*>(mp.w1p[m]);  // [S1][MT1][64]
     const int32_t* old_ids = p.old_ids + rd.old_off;
 
-    // this lane's two chunks (one per column tile): the pool rows of their
+    // this lane's chunks (one per column tile): the pool rows of their
     // tokens (units of D elements, -1 = no such row) and where they start
     int rows[NT];
     const _Float16* src_base[NT];
@@ -229,10 +229,9 @@ __global__ __launch_bounds__(mlp_threads(NT), 1) void mlp_compress_kernel(BatchP
       return w1g[(size_t)(g < k * GPT ? g : 0) * GO * 64 + i * kMlpThreads + tid];
     };
 
-    // ---- first product: H^T tile [HID x 64] per wavefront -------------------
-    // Each W1 operand read from LDS feeds two MFMAs (two column tiles), which
-    // halves the LDS traffic per flop.  The wavefront runs alone on its SIMD,
-    // so latency is hidden by software pipelining: W1 moves through registers
+    // ---- first product: H^T tile [HID x 32 NT] per wavefront -----------------
+    // Each W1 operand read from LDS feeds NT MFMAs (one per column tile).
+    // Latency is hidden by software pipelining: W1 moves through registers
     // (two groups in flight) into a ring of GPT groups in LDS, one barrier per
     // group; a group is visible one barrier before its turn, so A operands are
     // read AR ahead of their use, across group boundaries.  A scattered pool
