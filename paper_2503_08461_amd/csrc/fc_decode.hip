@@ -110,15 +110,15 @@ __global__ __launch_bounds__(kThreads) void decode_attention_kernel(DecodeParams
         const int tok = min(max(kept[min(j, L - 1)], 0), rq.seq_len - 1);
         const _Float16* kp = base + (size_t)clamp_block(row[tok >> 4], p.n_blocks) * blk_stride +
                              (size_t)(tok & 15) * D;
-        k[i] = load_half8(kp);
-        v[i] = load_half8(kp + v_off);
+        k[i] = load_half8_nt(kp);
+        v[i] = load_half8_nt(kp + v_off);
       }
     } else {
       const _Float16* kp = base + (size_t)clamp_block(row[b], p.n_blocks) * blk_stride;
 #pragma unroll
       for (int i = 0; i < IPB; ++i) {
-        k[i] = load_half8(kp + (size_t)i * RPI * D);
-        v[i] = load_half8(kp + v_off + (size_t)i * RPI * D);
+        k[i] = load_half8_nt(kp + (size_t)i * RPI * D);
+        v[i] = load_half8_nt(kp + v_off + (size_t)i * RPI * D);
       }
     }
 #pragma unroll

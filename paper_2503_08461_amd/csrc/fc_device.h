@@ -21,6 +21,18 @@ __device__ __forceinline__ half8 load_half8(const _Float16* p) {
   return *reinterpret_cast<const half8*>(p);
 }
 
+// The same accesses with the non-temporal hint, for data that this kernel will
+// not touch again: the line is the first to leave the caches, which keeps what
+// IS read again (K between the two passes of the SnapKV score, the rows that
+// the compaction re-reads) in L2 and in the memory-side cache for longer.
+__device__ __forceinline__ half8 load_half8_nt(const _Float16* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const half8*>(p));
+}
+
+__device__ __forceinline__ void store_half8_nt(_Float16* p, half8 v) {
+  __builtin_nontemporal_store(v, reinterpret_cast<half8*>(p));
+}
+
 __device__ __forceinline__ void store_half8(_Float16* p, half8 v) {
   *reinterpret_cast<half8*>(p) = v;
 }

@@ -126,6 +126,13 @@ __device__ __forceinline__ void snapkv_unit(const BatchParams& p, const ReqDesc&
   const int nb = (L + 15) >> 4;
   const int n_unmasked = (L - W) >> 4;  // blocks that lie wholly before the window
 
+  // last use of a block (second pass)
+  auto load_block_nt = [&](int b, half8 (&k)[KS]) {
+    const int blk = clamp_block(old_ids[b], p.n_blocks);
+    const _Float16* kp = kbase + (size_t)blk * blk_stride;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) k[ks] = load_half8_nt(kp + ks * 32);
+  };
   auto load_block = [&](int b, half8 (&k)[KS]) {
     const int blk = clamp_block(old_ids[b], p.n_blocks);
     const _Float16* kp = kbase + (size_t)blk * blk_stride;
@@ -227,11 +234,13 @@ __device__ __forceinline__ void snapkv_unit(const BatchParams& p, const ReqDesc&
     for (int r = 0; r < 4; ++r) mrow[nt][r] = sh.fin[nt * 16 + q4 * 4 + r];
 
   {
+    // from the end of the prefix backwards: the blocks that the first pass read
+    // last are the ones most likely to be still in a cache
     half8 kc[KS], kn[KS];
-    int b = wave;
-    if (b < nb2) load_block(b, kc);
-    for (; b < nb2; b += kWaves) {
-      if (b + kWaves < nb2) load_block(b + kWaves, kn);
+    int b = nb2 - 1 - wave;
+    if (b >= 0) load_block_nt(b, kc);
+    for (; b >= 0; b -= kWaves) {
+      if (b - kWaves >= 0) load_block_nt(b - kWaves, kn);
       float colsum = 0.f;
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
@@ -679,8 +688,8 @@ __device__ __forceinline__ void gather_unit(const BatchParams& p, const ReqDesc&
         const int idx = min(max(kept[t], 0), rd.seq_len - 1);
         const int sblk = clamp_block(old_ids[idx >> 4], p.n_blocks);
         const _Float16* src = base + (size_t)sblk * blk_stride + (size_t)(idx & 15) * D;
-        kk[k] = load_half8(src);
-        vv[k] = load_half8(src + v_off);
+        kk[k] = load_half8_nt(src);
+        vv[k] = load_half8_nt(src + v_off);
       }
     }
     if (p.in_place) __syncthreads();  // uniform: c0 and in_place are the same for all threads
@@ -691,8 +700,8 @@ __device__ __forceinline__ void gather_unit(const BatchParams& p, const ReqDesc&
       for (int k = 0; k < NI; ++k) {
         if (ok[k]) {
           const int row = k * RPI + row_in_instr;
-          store_half8(dst + (size_t)row * D, kk[k]);
-          store_half8(dst + (size_t)row * D + v_off, vv[k]);
+          store_half8_nt(dst + (size_t)row * D, kk[k]);
+          store_half8_nt(dst + (size_t)row * D + v_off, vv[k]);
         }
       }
     }
