@@ -26,8 +26,8 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 # 4 GiB copy (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000 on this chip); summary and
 # commands in profiles/fused_unit_kernel_config2_config3_config4.md.
 MEASURED_TRAFFIC_BYTES = {
-    ("config3_batched_mixed", "fused_unit"): 25.95e9,
-    ("config4_multi_image", "fused_unit"): 214.57e9,
+    ("config3_batched_mixed", "fused_unit"): 25.30e9,
+    ("config4_multi_image", "fused_unit"): 211.66e9,
     # profiles/fused_unit_kernel_config4_lse.md
     ("config4_multi_image_lse_supplied", "fused_unit"): 138.12e9,
     # profiles/mlp_compress_kernel_config4_mlp.md

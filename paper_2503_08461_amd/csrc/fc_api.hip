@@ -484,15 +484,29 @@ static int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_bl
   std::stable_sort(sorted.begin(), sorted.end(),
                    [&](int a, int b) { return weight(a) > weight(b); });
   const bool allow_fused = p->score_mode == FC_SCORE_AUTO;
+  auto fused = [&](const ReqDesc& d) {
+    // (streaming: no score, no LDS, so the fused kernel whatever the length)
+    return d.method == FC_METHOD_STREAMING || (allow_fused && d.seq_len <= kFusedMaxLen);
+  };
+  // Units without queries (key-norm, streaming) ride in the launch of the
+  // SnapKV class that has the most fused units, if there is one: one launch
+  // fills the chip better than two that each end in a tail.
+  int home_class = 0;
+  {
+    int count[kClasses] = {};
+    for (const ReqDesc& d : descs)
+      if (d.method == FC_METHOD_SNAPKV && fused(d)) ++count[(d.window + 15) / 16];
+    for (int c = 1; c < kClasses; ++c)
+      if (count[c] > count[home_class]) home_class = c;
+  }
   size_t raw_need = 0;
   for (int di : sorted) {
     const ReqDesc& d = descs[di];
     const bool snap = d.method == FC_METHOD_SNAPKV;
     const int cls = snap ? (d.window + 15) / 16 : 0;
     int li;
-    if (d.method == FC_METHOD_STREAMING || (allow_fused && d.seq_len <= kFusedMaxLen)) {
-      // (streaming: no score, no LDS, so the fused kernel whatever the length)
-      li = LIST_FUSED + cls;
+    if (fused(d)) {
+      li = LIST_FUSED + (snap ? cls : home_class);
     } else {
       // scores of these units travel through the library's scratch
       reinterpret_cast<ReqDesc*>(p->host_meta)[di].raw_off = (int64_t)raw_need;
@@ -502,7 +516,8 @@ static int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_bl
       max_len_list[LIST_ALL] = std::max(max_len_list[LIST_ALL], d.seq_len);
     }
     lists[li][n_list[li]++] = di;
-    max_len_list[li] = std::max(max_len_list[li], d.seq_len);
+    // (sizes the score buffer in LDS, which streaming units do not use)
+    if (d.method != FC_METHOD_STREAMING) max_len_list[li] = std::max(max_len_list[li], d.seq_len);
   }
   int ns = 0, n_fused = 0;
   for (int c = 0; c < kClasses; ++c) {

@@ -324,6 +324,20 @@ def test_streaming_method_mixed_with_scored_methods(n_sink, score_mode):
         s.close()
 
 
+def test_streaming_request_of_maximum_length_next_to_scored_ones():
+    """A streaming request needs no score buffer, whatever its length; key-norm
+    and streaming units share the launch of the SnapKV units."""
+    M = fo.METHOD_STREAMING
+    wl = _custom([32768, 500, 400, 31000], [5000, 100, 90, 31000],
+                 [M, fo.METHOD_SNAPKV, fo.METHOD_KNORM, M], W=33, d=64, n_heads=1)
+    s = _sbs(wl)
+    try:
+        st = s.compress_and_compare(n_sink=4)
+        assert st["units_kept_identical"] == st["units"]
+    finally:
+        s.close()
+
+
 def test_in_place_compaction(score_mode):
     """FC_COMPACT_IN_PLACE: same kept lists, rows moved inside the request's own
     blocks (chunked so that no row is overwritten before it is read), tail
