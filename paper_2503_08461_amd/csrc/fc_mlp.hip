@@ -46,6 +46,14 @@ __host__ __device__ constexpr int mlp_hidden_unit(int sl, int kh, int e) {
   return 32 * (sl / 2) + 16 * (sl % 2) + 8 * (e / 4) + 4 * kh + (e % 4);
 }
 
+// Output channel (within a 32-channel tile) that sits on row rho of the second
+// product's A operand.  The 32x32 result leaves rows 8g + 4kh + r (g = 0..3,
+// r = 0..3) in registers 4g + r of lane half kh; with this order a lane's
+// registers of g = 2gp and 2gp + 1 are 8 consecutive channels, one 16-byte store.
+__host__ __device__ constexpr int mlp_out_channel(int rho) {
+  return 16 * (rho / 16) + 8 * ((rho / 4) % 2) + 4 * ((rho / 8) % 2) + rho % 4;
+}
+
 size_t mlp_w1p_elems(int head_dim, int hidden, int k) { return (size_t)hidden * k * head_dim; }
 size_t mlp_w2p_elems(int head_dim, int hidden) { return (size_t)hidden * head_dim; }
 
@@ -53,7 +61,7 @@ size_t mlp_w2p_elems(int head_dim, int hidden) { return (size_t)hidden * head_di
 // first product is channel 16*j + 8*kh + e of token t of the chunk: the two
 // lane halves read neighbouring 16-byte pieces of a row.
 // w1p[s][mt][lane][e] = w1[mt*32 + lane%32][t*D + 16*j + 8*(lane/32) + e]
-// w2p[sl][ot][lane][e] = w2[ot*32 + lane%32][mlp_hidden_unit(sl, lane/32, e)]
+// w2p[sl][ot][lane][e] = w2[ot*32 + mlp_out_channel(lane%32)][mlp_hidden_unit(sl, lane/32, e)]
 __global__ void mlp_permute_kernel(const _Float16* w1, const _Float16* w2, _Float16* w1p,
                                    _Float16* w2p, int head_dim, int hidden, int k) {
   const int kd = k * head_dim;
@@ -74,7 +82,8 @@ __global__ void mlp_permute_kernel(const _Float16* w1, const _Float16* w2, _Floa
     const size_t rest = i >> 9;
     const int mt2 = head_dim / 32;
     const int ot = rest % mt2, sl = rest / mt2;
-    w2p[i] = w2[(size_t)(ot * 32 + (lane & 31)) * hidden + mlp_hidden_unit(sl, lane >> 5, e)];
+    w2p[i] = w2[(size_t)(ot * 32 + mlp_out_channel(lane & 31)) * hidden +
+                mlp_hidden_unit(sl, lane >> 5, e)];
   }
 }
 
@@ -359,12 +368,14 @@ __global__ __launch_bounds__(mlp_threads(NT), 1) void mlp_compress_kernel(BatchP
 #pragma unroll
         for (int ot = 0; ot < MT2; ++ot)
 #pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const int c0 = 32 * ot + 8 * g + 4 * kh;
-            half4 y;
+          for (int gp = 0; gp < 2; ++gp) {
+            // registers 8gp .. 8gp+7 = rows 16gp + 4kh + {0..3} and 16gp + 8 + 4kh + {0..3}
+            // = channels 16gp + 8kh + {0..7} (mlp_out_channel)
+            const int c0 = 32 * ot + 16 * gp + 8 * kh;
+            half8 y;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) y[r] = (_Float16)(acc2[ot][nt][4 * g + r] + sm_b2[c0 + r]);
-            *reinterpret_cast<half4*>(dst + c0) = y;
+            for (int r = 0; r < 8; ++r) y[r] = (_Float16)(acc2[ot][nt][8 * gp + r] + sm_b2[c0 + r]);
+            store_half8(dst + c0, y);
           }
       }
     }
