@@ -33,6 +33,7 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 
 static constexpr int kMlpRowsPerTile = 256;
+static constexpr uint32_t kNoRow = 0xffffffffu;  // "no such token" in the table of pool rows
 // threads of a workgroup when a wavefront takes NT column tiles of 32 chunks
 constexpr int mlp_threads(int nt) { return kMlpRowsPerTile / (32 * nt) * 64; }
 
@@ -133,7 +134,7 @@ __global__ __launch_bounds__(mlp_threads(NT), 1) void mlp_compress_kernel(BatchP
   half8* sm_w2 = sm_w1 + GPT * GO * 64;                              // [S2][MT2][64]
   float* sm_b1 = reinterpret_cast<float*>(sm_w2 + S2 * MT2 * 64);    // [HID]
   float* sm_b2 = sm_b1 + HID;                                        // [D]
-  int* sm_rows = reinterpret_cast<int*>(sm_b2 + D);                  // [RT][NT][threads]
+  uint32_t* sm_rows = reinterpret_cast<uint32_t*>(sm_b2 + D);        // [RT][NT][threads]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -147,25 +148,121 @@ __global__ __launch_bounds__(mlp_threads(NT), 1) void mlp_compress_kernel(BatchP
   const size_t blk_stride = 2 * v_off;
   const int blk_rows = 2 * p.n_heads * 16;  // blk_stride in rows of D elements
 
-  // persistent: a workgroup walks tiles blockIdx.x, blockIdx.x + gridDim.x, ...
-  int cur_m = -1;
-  int cur_job = 0, next_start = 0;  // next_start = 0 forces the first lookup
-  MlpJob job = mp.jobs[0];
-  ReqDesc rd = p.descs[job.desc];
-  for (int tile = blockIdx.x; tile < mp.n_tiles; tile += gridDim.x) {
-    // which job does this tile belong to: jobs are sorted by tile_start and a
-    // workgroup visits tiles in increasing order, so a running index suffices
-    if (tile >= next_start) {  // uniform
-      while (cur_job + 1 < mp.n_jobs && mp.jobs[cur_job + 1].tile_start <= tile) ++cur_job;
-      job = mp.jobs[cur_job];
-      rd = p.descs[job.desc];
-      next_start = (cur_job + 1 < mp.n_jobs) ? mp.jobs[cur_job + 1].tile_start : 0x7fffffff;
-    }
-    const int m = job.modality;
+  // Persistent: a workgroup walks tiles blockIdx.x, blockIdx.x + gridDim.x, ...
+  // The walk is software-pipelined over tiles, because what a tile needs before
+  // its first MFMA (which job it belongs to, where its chunks start, the block
+  // ids of its rows, its first pool rows) is a chain of dependent memory
+  // accesses of several microseconds: while tile T runs its GELU, second
+  // product and store, in which nothing else is loaded, the chain of tile
+  // T + gridDim.x is walked, so that its first rows are on their way when it
+  // starts.
+  struct Lane {            // what a lane knows about its chunk of a tile (per column tile)
+    int row;               // row of the job (-1: no chunk)
+    int s0, n_valid;       // first token of the chunk, tokens it has (< k at a segment's end)
+    uint32_t base_row;     // pool row (units of D elements) of slot 0 of block 0 of its (layer, head, K|V)
+  };
+  auto find_job = [&](int tile, int& ji) {  // jobs are sorted by tile_start; ji only moves up
+    while (ji + 1 < mp.n_jobs && mp.jobs[ji + 1].tile_start <= tile) ++ji;
+  };
+  auto lane_of = [&](int tile, const MlpJob& job, const ReqDesc& rd, int nt) -> Lane {
+    Lane ln;
     const long long n_rows = (long long)n_units * job.chunks;
+    const long long row = (long long)(tile - job.tile_start) * kMlpRowsPerTile +
+                          wave * (32 * NT) + nt * 32 + col;
+    ln.row = row < n_rows ? (int)row : -1;
+    int unit = 0;
+    ln.s0 = 0;
+    ln.n_valid = 0;
+    if (row < n_rows) {
+      unit = (int)(row / job.chunks);
+      const int cl = (int)(row - (long long)unit * job.chunks);
+      int seg_end;
+      if (job.modality == 1) {
+        ln.s0 = rd.img_begin + cl * k;
+        seg_end = rd.img_end;
+      } else if (cl < rd.chunks_text0) {
+        ln.s0 = cl * k;
+        seg_end = rd.img_begin;
+      } else {
+        ln.s0 = rd.img_end + (cl - rd.chunks_text0) * k;
+        seg_end = rd.seq_len;
+      }
+      ln.n_valid = min(k, seg_end - ln.s0);
+    }
+    const int lh = unit >> 1;
+    const int layer = lh / p.n_heads;
+    // (the pool has fewer than 2^32 - 1 rows: checked by the launcher)
+    ln.base_row = (uint32_t)(layer * p.n_blocks) * (uint32_t)blk_rows +
+                  (uint32_t)((unit & 1) * (p.n_heads * 16) + (lh - layer * p.n_heads) * 16);
+    return ln;
+  };
+  // The pool rows of a chunk's tokens (absolute, in units of D elements,
+  // kNoRow = no such token) go to a table in LDS, each lane reading back only what it wrote: registers
+  // are needed for data in flight, and a lookup inside the pipelined loop would
+  // make every iteration wait for all loads in flight.  A chunk has at most 8
+  // tokens, so it lies in at most two blocks: bid[0], bid[1].
+  auto write_rows = [&](const Lane& ln, const int (&bid)[2], int nt) {
+#pragma unroll
+    for (int t = 0; t < RT; ++t) {
+      const int tok = ln.s0 + t;
+      const int blk = (tok >> 4) == (ln.s0 >> 4) ? bid[0] : bid[1];
+      sm_rows[(t * NT + nt) * kMlpThreads + tid] =
+          t < ln.n_valid ? ln.base_row + (uint32_t)clamp_block(blk, p.n_blocks) * (uint32_t)blk_rows +
+                               (uint32_t)(tok & 15)
+                         : kNoRow;
+    }
+  };
+  auto row_of = [&](int nt, int t) -> uint32_t {
+    return sm_rows[(t * NT + nt) * kMlpThreads + tid];
+  };
+
+  // Every load of the pipelined loop is unconditional (a load under a branch
+  // makes the compiler wait for ALL loads in flight at the next use): a token
+  // that does not exist (past the end of a chunk's segment, or a lane without
+  // a chunk) reads a row of zeros instead, and W1 groups past the end wrap to
+  // group 0, whose copy nobody uses.
+  // B operand of slab j of a token: 8 channels [(D/2)kh + 8j, +8) of its row
+  auto load_x = [&](uint32_t ri, int j) -> half8 {
+    const _Float16* row = ri != kNoRow ? p.kv + (size_t)ri * D : g_zero_row;
+    return load_half8(row + kh * 8 + j * 16);
+  };
+
+  int cur_m = -1;
+  int ji = 0;
+  find_job(blockIdx.x, ji);
+  MlpJob job = mp.jobs[ji];
+  ReqDesc rd = p.descs[job.desc];
+  half8 xq[XR][NT][SPT];
+  // the first tile's chain, not overlapped with anything
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const Lane ln = lane_of(blockIdx.x, job, rd, nt);
+    const int32_t* ids = p.old_ids + rd.old_off;
+    const int last = ln.s0 + max(ln.n_valid, 1) - 1;
+    const int bid[2] = {ids[ln.s0 >> 4], ids[last >> 4]};
+    write_rows(ln, bid, nt);
+  }
+#pragma unroll
+  for (int u = 0; u < XR; ++u)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const uint32_t ri = row_of(nt, u);
+#pragma unroll
+      for (int j = 0; j < SPT; ++j) xq[u][nt][j] = load_x(ri, j);
+    }
+
+  for (int tile = blockIdx.x; tile < mp.n_tiles; tile += gridDim.x) {
+    // the tile after this one (the last tile prefetches itself again: loads in
+    // bounds that nobody uses, so that nothing here sits under a branch)
+    const int tile_n = tile + (int)gridDim.x < mp.n_tiles ? tile + (int)gridDim.x : tile;
+    int ji_n = ji;
+    find_job(tile_n, ji_n);
+    const MlpJob job_n = mp.jobs[ji_n];
+    const ReqDesc rd_n = p.descs[job_n.desc];
 
     // weights of this modality: W2 and the biases stay in LDS across tiles and
     // are only reloaded when the modality changes
+    const int m = job.modality;
     if (m != cur_m) {  // uniform
       __syncthreads();  // the previous tile may still be reading them
       const half8* w2g = reinterpret_cast<const half8*>(mp.w2p[m]);
@@ -175,64 +272,6 @@ __global__ __launch_bounds__(mlp_threads(NT), 1) void mlp_compress_kernel(BatchP
       cur_m = m;
     }
     const half8* w1g = reinterpret_cast<const half8*>(mp.w1p[m]);  // [S1][MT1][64]
-    const int32_t* old_ids = p.old_ids + rd.old_off;
-
-    // this lane's chunks (one per column tile): the pool rows of their
-    // tokens (units of D elements, -1 = no such row) and where they start
-    int rows[NT];
-    const _Float16* src_base[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      const long long row = (long long)(tile - job.tile_start) * kMlpRowsPerTile +
-                            wave * (32 * NT) + nt * 32 + col;
-      rows[nt] = row < n_rows ? (int)row : -1;
-      int unit = 0, s0 = 0, n_valid = 0;
-      if (row < n_rows) {
-        unit = (int)(row / job.chunks);
-        const int cl = (int)(row - (long long)unit * job.chunks);
-        int seg_end;
-        if (m == 1) {
-          s0 = rd.img_begin + cl * k;
-          seg_end = rd.img_end;
-        } else if (cl < rd.chunks_text0) {
-          s0 = cl * k;
-          seg_end = rd.img_begin;
-        } else {
-          s0 = rd.img_end + (cl - rd.chunks_text0) * k;
-          seg_end = rd.seq_len;
-        }
-        n_valid = min(k, seg_end - s0);
-      }
-      const int lh = unit >> 1;
-      const int layer = lh / p.n_heads;
-      src_base[nt] = p.kv + (size_t)layer * p.n_blocks * blk_stride + (unit & 1) * v_off +
-                     (size_t)(lh - layer * p.n_heads) * chunk_el + kh * 8;
-      // looked up once: a lookup inside the pipelined loop would make every
-      // iteration wait for all loads in flight
-      // (kept in LDS, each lane reading back only what it wrote: registers are
-      // needed for data in flight)
-#pragma unroll
-      for (int t = 0; t < RT; ++t) {
-        int ri = -1;
-        if (t < n_valid) {
-          const int tok = s0 + t;
-          ri = clamp_block(old_ids[tok >> 4], p.n_blocks) * blk_rows + (tok & 15);
-        }
-        sm_rows[(t * NT + nt) * kMlpThreads + tid] = ri;
-      }
-    }
-    auto row_of = [&](int nt, int t) -> int { return sm_rows[(t * NT + nt) * kMlpThreads + tid]; };
-
-    // Every load of the pipelined loop is unconditional (a load under a branch
-    // makes the compiler wait for ALL loads in flight at the next use): a token
-    // that does not exist (past the end of a chunk's segment, or a lane without
-    // a chunk) reads a row of zeros instead, and W1 groups past the end wrap to
-    // group 0, whose copy nobody uses.
-    // B operand of slab j of a token: 8 channels [(D/2)kh + 8j, +8) of its row
-    auto load_x = [&](int nt, int ri, int j) -> half8 {
-      const _Float16* row = ri >= 0 ? src_base[nt] + (size_t)ri * D : g_zero_row + kh * 8;
-      return load_half8(row + j * 16);
-    };
     // piece i of this thread's share of W1 group g (operand order, contiguous)
     auto load_w = [&](int g, int i) -> half8 {
       return w1g[(size_t)(g < k * GPT ? g : 0) * GO * 64 + i * kMlpThreads + tid];
@@ -255,15 +294,7 @@ __global__ __launch_bounds__(mlp_threads(NT), 1) void mlp_compress_kernel(BatchP
       for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[mt][nt][r] = 0.f;
-    half8 xq[XR][NT][SPT], wq[WD][PPG], ar[AR];
-#pragma unroll
-    for (int u = 0; u < XR; ++u)
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        const int ri = row_of(nt, u);
-#pragma unroll
-        for (int j = 0; j < SPT; ++j) xq[u][nt][j] = load_x(nt, ri, j);
-      }
+    half8 wq[WD][PPG], ar[AR];
     // groups 0 and 1 go straight to LDS; wq[i] holds the next unwritten group congruent to i mod WD
 #pragma unroll
     for (int g = 0; g < 2; ++g)
@@ -281,7 +312,7 @@ __global__ __launch_bounds__(mlp_threads(NT), 1) void mlp_compress_kernel(BatchP
     for (int u = 0; u < XR; ++u) {
       const int t = t0 + u;
       if (t >= k) break;  // uniform
-      int ri_new[NT];
+      uint32_t ri_new[NT];
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) ri_new[nt] = row_of(nt, t + XR);
 #pragma unroll
@@ -313,14 +344,60 @@ __global__ __launch_bounds__(mlp_threads(NT), 1) void mlp_compress_kernel(BatchP
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
           for (int h = 0; h < GS; ++h)
-            xq[u][nt][GS * jj + h] = load_x(nt, ri_new[nt], GS * jj + h);
+            xq[u][nt][GS * jj + h] = load_x(ri_new[nt], GS * jj + h);
         __syncthreads();  // the new group is visible; nobody reads this one any more
       }
     }
     }
 
-    // ---- bias, gelu, fp16: each result tile becomes two B operands of the
-    // second product, Y^T tile [D x 64], and is consumed at once
+    // ---- the next tile's chain, first half: where its chunks are, their block ids
+    Lane ln_n[NT];
+    int bid_n[NT][2];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      ln_n[nt] = lane_of(tile_n, job_n, rd_n, nt);
+      const int32_t* ids = p.old_ids + rd_n.old_off;
+      const int last = ln_n[nt].s0 + max(ln_n[nt].n_valid, 1) - 1;
+      bid_n[nt][0] = ids[ln_n[nt].s0 >> 4];
+      bid_n[nt][1] = ids[last >> 4];
+    }
+
+    // ---- bias, gelu, fp16: each 32x32 result tile becomes two B operands of
+    // the second product and stays in registers.  Half-way through, when half
+    // of the accumulators are gone, the next tile's row table is written (this
+    // tile's is no longer read, and every lane only ever reads its own entries)
+    // and its first XR tokens are requested: they travel while the rest of the
+    // GELU, the second product and the store keep the other units busy.
+    half8 hb[S2][NT];
+    auto gelu_tile = [&](int mt) {
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        const int sl = 2 * mt + half;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const int u = mlp_hidden_unit(sl, kh, e);  // = 32mt + 16half + 8(e/4) + 4kh + e%4
+            hb[sl][nt][e] = (_Float16)gelu_tanh(acc[mt][nt][8 * half + e] + sm_b1[u]);
+          }
+      }
+    };
+#pragma unroll
+    for (int mt = 0; mt < MT1 / 2; ++mt) gelu_tile(mt);
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) write_rows(ln_n[nt], bid_n[nt], nt);
+#pragma unroll
+    for (int u = 0; u < XR; ++u)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const uint32_t ri = row_of(nt, u);
+#pragma unroll
+        for (int j = 0; j < SPT; ++j) xq[u][nt][j] = load_x(ri, j);
+      }
+#pragma unroll
+    for (int mt = MT1 / 2; mt < MT1; ++mt) gelu_tile(mt);
+
+    // ---- second product, Y^T tile [D x 32 NT]
     floatx16 acc2[MT2][NT];
 #pragma unroll
     for (int ot = 0; ot < MT2; ++ot)
@@ -329,34 +406,25 @@ __global__ __launch_bounds__(mlp_threads(NT), 1) void mlp_compress_kernel(BatchP
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc2[ot][nt][r] = 0.f;
 #pragma unroll
-    for (int mt = 0; mt < MT1; ++mt) {
+    for (int sl = 0; sl < S2; ++sl)
 #pragma unroll
-      for (int half = 0; half < 2; ++half) {
-        const int sl = 2 * mt + half;
-        half8 hb[NT];
+      for (int ot = 0; ot < MT2; ++ot) {
+        const half8 w = sm_w2[(sl * MT2 + ot) * 64 + lane];
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const int u = mlp_hidden_unit(sl, kh, e);  // = 32mt + 16half + 8(e/4) + 4kh + e%4
-            hb[nt][e] = (_Float16)gelu_tanh(acc[mt][nt][8 * half + e] + sm_b1[u]);
-          }
-#pragma unroll
-        for (int ot = 0; ot < MT2; ++ot) {
-          const half8 w = sm_w2[(sl * MT2 + ot) * 64 + lane];
-#pragma unroll
-          for (int nt = 0; nt < NT; ++nt)
-            acc2[ot][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(w, hb[nt], acc2[ot][nt], 0, 0, 0);
-        }
+          acc2[ot][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(w, hb[sl][nt], acc2[ot][nt], 0, 0, 0);
       }
-    }
 
     // ---- bias, fp16, store the rows into the request's new blocks -------------
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-      if (rows[nt] >= 0) {
-        const int unit = rows[nt] / job.chunks;
-        const int cl = rows[nt] - unit * job.chunks;
+      // (this tile's row again: cheaper than a register held across the loops)
+      const long long row_ll = (long long)(tile - job.tile_start) * kMlpRowsPerTile +
+                               wave * (32 * NT) + nt * 32 + col;
+      if (row_ll < (long long)n_units * job.chunks) {
+        const int row = (int)row_ll;
+        const int unit = row / job.chunks;
+        const int cl = row - unit * job.chunks;
         const int o = (m == 1) ? rd.chunks_text0 + cl
                                : (cl < rd.chunks_text0 ? cl : rd.chunks_image + cl);
         const int lh = unit >> 1;
@@ -379,6 +447,9 @@ __global__ __launch_bounds__(mlp_threads(NT), 1) void mlp_compress_kernel(BatchP
           }
       }
     }
+    job = job_n;
+    rd = rd_n;
+    ji = ji_n;
   }
 }
 
@@ -422,6 +493,9 @@ static hipError_t mlp_launch_one(const BatchParams& p, const MlpParams& mp, hipS
 
 hipError_t launch_mlp_compress(const BatchParams& p, const MlpParams& mp, hipStream_t s) {
   if (mp.n_tiles <= 0) return hipSuccess;
+  // the kernel addresses pool rows (head_dim elements each) with 32 bits
+  if ((unsigned long long)p.n_layers * p.n_blocks * 2 * p.n_heads * 16 >= kNoRow)
+    return hipErrorInvalidValue;
   if (p.head_dim == 128 && mp.hidden == 256) return mlp_launch_one<128, 256>(p, mp, s);
   if (p.head_dim == 128 && mp.hidden == 128) return mlp_launch_one<128, 128>(p, mp, s);
   if (p.head_dim == 64 && mp.hidden == 256) return mlp_launch_one<64, 256>(p, mp, s);
