@@ -428,9 +428,12 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="config4",
-                    choices=["config2", "config3", "config4", "config3_lse", "config4_lse",
+                    choices=["config2", "config3", "config4", "config3_precall70", "config3_lse",
+                             "config4_lse",
                              "config4_streaming", "config4_mlp", "config4_decode", "replay"],
-                    help="configN_lse: the batch of config N with the window rows' log-sum-exp "
+                    help="config3_precall70: the config-3 batch in a pool that is 70 %% full BEFORE "
+                         "the call, compressed as two half-batches (one call would need more "
+                         "free blocks than there are); configN_lse: the batch of config N with the window rows' log-sum-exp "
                          "supplied as an input (computed before the timed region, as the "
                          "prefill's attention kernel would have), one pass over K; "
                          "config4_streaming: the config-4 batch with every request using the "
@@ -475,6 +478,8 @@ def main():
         bench_replay(args)
         return
     wl = synth.make_workload(int(args.workload[6]))
+    if args.workload.endswith("_precall70"):
+        synth.precall_occupancy_variant(wl, 0.70)
     if args.workload.endswith("_streaming"):
         wl.methods[:] = synth.METHOD_STREAMING
         wl.name += "_streaming"
@@ -495,6 +500,8 @@ def main():
     fc.fc_set_score_mode(dw.pool, {"auto": 0, "two_pass": 1, "one_pass": 2}[args.score_mode])
     fc.fc_set_profiling(dw.pool, True)
     lse_ms = None
+    if args.workload.endswith("_precall70"):
+        dw.parts = 2
     if args.workload.endswith("_lse"):
         wl.name += "_lse_supplied"
         dw.compute_lse()
@@ -566,7 +573,9 @@ def main():
             else None,
         },
     }
-    if lse_ms is None and bool((wl.methods == synth.METHOD_SNAPKV).any()):
+    if dw.parts > 1:
+        out["config"]["calls_per_step"] = dw.parts
+    if lse_ms is None and dw.parts == 1 and bool((wl.methods == synth.METHOD_SNAPKV).any()):
         # the same batch when the caller hands over the window rows' log-sum-exp
         # (one pass over K); reported beside the headline value, never as it
         dw.compute_lse()

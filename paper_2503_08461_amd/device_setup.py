@@ -17,6 +17,7 @@ class DeviceWorkload:
             print("[setup] %s: pool %.1f GiB, %d requests, %d tokens" % (
                 wl.name, wl.pool_bytes() / 2**30, wl.n_req, wl.total_tokens), flush=True)
         self.lse = None
+        self.parts = 1      # > 1: compress() issues the batch as that many calls
         self.kv = torch.empty(wl.pool_shape(), dtype=torch.float16, device=self.dev)
         synth.fill_pool_device(wl, self.kv)
         self.q = synth.fill_q_window_device(wl, self.dev)
@@ -49,8 +50,21 @@ class DeviceWorkload:
         self.bt.copy_(self.bt0)
         self.lens[:] = self.wl.seq_lens
 
+    def compress_in_parts(self, n_parts):
+        """The batch as n_parts calls of consecutive requests (the others pass
+        through as FC_METHOD_NONE), for pools too full for one call."""
+        wl = self.wl
+        edges = np.linspace(0, wl.n_req, n_parts + 1).astype(int)
+        for a, b in zip(edges[:-1], edges[1:]):
+            m = np.zeros(wl.n_req, dtype=np.int32)
+            m[a:b] = wl.methods[a:b]
+            fc.fc_compress_batch(self.pool, self.bt, self.lens, self.q, wl.window, m,
+                                 wl.budgets, wl.pool_kernel, 0.0, None, None)
+
     def compress(self, scores_out=None, kept_out=None):
         wl = self.wl
+        if self.parts > 1:
+            return self.compress_in_parts(self.parts)
         if self.lse is not None:
             fc.fc_compress_batch_lse(self.pool, self.bt, self.lens, self.q, self.lse, wl.window,
                                      wl.methods, wl.budgets, wl.pool_kernel, 0.0, scores_out,

@@ -85,6 +85,18 @@ def _n_blocks_for_occupancy(seq_lens, budgets, occupancy, bs=BLOCK_SIZE):
     return int(np.ceil((old + new) / occupancy))
 
 
+def precall_occupancy_variant(wl, occupancy):
+    """The same batch in a pool whose occupancy BEFORE the call is `occupancy`
+    (the resident requests' blocks / n_blocks).  With a large kept fraction
+    the batch then no longer fits one call (new blocks are taken before old
+    ones come back) and has to be compressed in parts."""
+    old = sum(blocks_for(int(l), wl.block_size) for l in wl.seq_lens)
+    wl.n_blocks = int(np.ceil(old / occupancy))
+    wl.name += "_precall%d" % round(occupancy * 100)
+    wl.notes = "%d%% occupancy before the call" % round(occupancy * 100)
+    return wl
+
+
 def make_workload(config, n_layers=None, n_heads=None, n_req=None, seed=None,
                   max_len=None):
     """The five benchmark configurations (1-based), optionally shrunk in the

@@ -338,6 +338,35 @@ def test_streaming_request_of_maximum_length_next_to_scored_ones():
         s.close()
 
 
+def test_pool_70_percent_full_before_the_call_takes_two_half_batches():
+    """Config 3's lengths and budgets (keep 50 %) in a pool that is 70 % full
+    before the call: one call would need 35 % of the pool in new blocks and
+    only 30 % is free, so it is refused with nothing touched; the two halves
+    of the batch, one after the other, fit (the first half's old blocks are
+    back when the second asks) and match the oracle."""
+    from paper_2503_08461_amd import fastcache as fc
+    wl = synth.precall_occupancy_variant(synth.make_workload(3, n_layers=1, n_heads=2, n_req=8), 0.70)
+    s = _sbs(wl)
+    try:
+        free0 = fc.fc_pool_num_free(s.pool)
+        assert free0 < sum(synth.blocks_for(int(b)) for b in wl.budgets)
+        bt0, lens0 = s.bt_dev.clone(), s.lens_g.copy()
+        with pytest.raises(fc.FastCacheError) as e:
+            fc.fc_compress_batch(s.pool, s.bt_dev, s.lens_g, s.q_dev, wl.window, wl.methods,
+                                 wl.budgets, wl.pool_kernel)
+        assert e.value.code == fc.FC_ENOMEM
+        assert (s.bt_dev == bt0).all() and (s.lens_g == lens0).all()
+        assert fc.fc_pool_num_free(s.pool) == free0
+        for a, b in ((0, 4), (4, 8)):
+            m = np.zeros(8, dtype=np.int32)
+            m[a:b] = wl.methods[a:b]
+            st = s.compress_and_compare(methods=m)
+            assert st["max_rel_err"] < 2e-3
+        assert (s.lens_g == wl.budgets).all()
+    finally:
+        s.close()
+
+
 def test_in_place_compaction(score_mode):
     """FC_COMPACT_IN_PLACE: same kept lists, rows moved inside the request's own
     blocks (chunked so that no row is overwritten before it is read), tail
