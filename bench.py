@@ -526,6 +526,19 @@ def main():
     sec_per_step = (time.perf_counter() - t0) / args.steps
     kavg = fc.fc_get_kernel_times(dw.pool)  # HIP events around every kernel of those steps
 
+    # the same call timed one at a time (HIP events on the stream it runs on,
+    # metadata rewound outside the events): median and minimum
+    call_ms = []
+    for _ in range(args.steps):
+        dw.rewind()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        dw.compress()
+        e1.record()
+        torch.cuda.synchronize()
+        call_ms.append(e0.elapsed_time(e1))
+    call_ms.sort()
+
     comp = wl.methods != synth.METHOD_NONE
     tokens = int(wl.seq_lens[comp].astype(np.int64).sum())
     path_bytes = dw.algorithmic_bytes()
@@ -561,6 +574,8 @@ def main():
             "achieved_GBps": path_bytes / sec_per_step / 1e9,
             "frac_of_hbm_peak": path_bytes / sec_per_step / 1e9 / HBM_PEAK_GBPS,
         },
+        "call_ms": {"median": call_ms[len(call_ms) // 2], "min": call_ms[0],
+                    "note": "one call at a time, HIP events around it"},
         "kernel_ms": {k: round(v, 4) for k, v in kavg.items()},
         "roofline": {
             "kernel": dom,
