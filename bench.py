@@ -241,11 +241,17 @@ def bench_replay(args):
         nxt, done, peak_used, adm_waits = 0, 0, 0, 0
         admitted_at = {}
 
+        last_submit = [0]
+
         def admit(i, t):
             need = synth.blocks_for(int(lens[i]))
             if fc.fc_pool_num_free(pool) < need + RESERVE:
                 return False
             rows[i] = fc.fc_pool_alloc(pool, need)
+            # the compress queue takes submissions in time order: a request that
+            # arrived while an earlier one was being admitted enters right after it
+            t = max(t, last_submit[0])
+            last_submit[0] = t
             admitted_at[i] = t
             assert sched.submit(i, t, int(lens[i]), int(budgets[i]))
             return True
