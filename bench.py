@@ -112,7 +112,7 @@ def cpu_baseline_mlp(dw, weights, k, img_b, img_e, seconds=15.0, seed=0):
             rows = dw.kv[l, ids, kv, h].cpu().numpy().reshape(-1, wl.head_dim)[:L].astype(np.float64)
             t0 = time.perf_counter()
             plan = mo.chunk_plan(L, int(img_b[r]), int(img_e[r]), k)
-            mo.compress_rows(rows, plan, w, k)
+            mo.compress_rows(rows, plan, w, k, "gelu_tanh")
             spent += time.perf_counter() - t0
             tokens += L
             units += 1

@@ -263,3 +263,20 @@ def check_unit_on_device(kv_dev, q_unit, old_ids, new_ids, layer, head, L, B, me
         e = mini[0, n_old + i, :, 0, :valid].view(np.uint16)
         assert (a == e).all(), "gathered K/V bytes differ %s new block %d" % (where, i)
     return err, same
+
+
+# ---- chunk-MLP compressor: error bound of the kernel's arithmetic ---------------
+
+U16 = 2.0 ** -11          # unit round-off of fp16
+H_ABS = 1e-4              # fp32 accumulation of k*d products + fast-math activation, absolute
+
+
+def mlp_error_bound(y, hidden, w2):
+    """What the kernel's arithmetic may differ from the exact row by, element
+    by element.  The kernel holds the hidden activations as the fp16 operand
+    of its second matrix product and stores fp16 rows:
+        |h~_u - h_u| <= U16 |h_u| + H_ABS
+        |y~_c - y_c| <= U16 |y_c| + sum_u |W2_cu| |h~_u - h_u|   (+ fp32 sums, << the rest)
+    y [rows][d], hidden [rows][hidden] from the oracle, w2 [d][hidden]."""
+    dh = U16 * np.abs(hidden) + H_ABS
+    return U16 * np.abs(y) * 1.01 + dh @ np.abs(w2.astype(np.float64)).T + 1e-6

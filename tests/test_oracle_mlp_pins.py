@@ -1,6 +1,7 @@
 """Pins for the chunk-MLP compressor oracle (CPU only): closed forms for the
-chunk plan, a network whose output is known in closed form (chunk means),
-scalar brute force, pool bookkeeping."""
+chunk plan, both activations against tabulated values of the normal
+distribution function and of tanh, a network whose output is known in closed
+form (chunk means), scalar brute force, pool bookkeeping."""
 
 import math
 
@@ -26,15 +27,81 @@ def test_chunk_plan_closed_form():
         assert covered == set(range(L))                 # every token in exactly one chunk
 
 
-def test_gelu_against_scalar_tanh_form():
-    v = np.linspace(-6, 6, 49)
-    ref = [0.5 * x * (1 + math.tanh(math.sqrt(2 / math.pi) * (x + 0.044715 * x ** 3))) for x in v]
-    np.testing.assert_allclose(mo.gelu(v), ref, rtol=1e-12, atol=1e-15)
-    assert mo.gelu(np.array([0.0]))[0] == 0 and abs(mo.gelu(np.array([30.0]))[0] - 30) < 1e-12
-    assert abs(mo.gelu(np.array([-30.0]))[0]) < 1e-12
-    # the tanh form stays within 5e-4 of the erf form everywhere
-    erf_form = [0.5 * x * (1 + math.erf(x / math.sqrt(2))) for x in v]
-    assert np.abs(mo.gelu(v) - erf_form).max() < 5e-4
+# Standard normal distribution function at fixed points, from a table of the
+# normal distribution (Phi(0.5), Phi(1), Phi(2), Phi(3)); GELU(v) = v * Phi(v).
+PHI_TABLE = {0.5: 0.6914624612740131, 1.0: 0.8413447460685429, 2.0: 0.9772498680518208,
+             3.0: 0.9986501019683699}
+# textbook values of tanh
+TANH_HALF, TANH_ONE = 0.46211715726000974, 0.7615941559557649
+
+
+def test_gelu_erf_is_v_times_normal_cdf():
+    """The definition of GELU against tabulated Phi values (both signs:
+    Phi(-v) = 1 - Phi(v)) and against math.erf at other points."""
+    for v, phi in PHI_TABLE.items():
+        assert abs(float(mo.gelu_erf(v)) - v * phi) < 1e-15
+        assert abs(float(mo.gelu_erf(-v)) + v * (1.0 - phi)) < 1e-15
+    for v in (-6.0, -2.5, -0.1, 0.3, 1.7, 4.2, 7.0):
+        assert abs(float(mo.gelu_erf(v)) - 0.5 * v * math.erfc(-v / math.sqrt(2.0))) < 1e-15
+    v = np.linspace(-8, 8, 81)
+    np.testing.assert_allclose(mo.gelu_erf(v) - mo.gelu_erf(-v), v, rtol=0, atol=1e-14)
+    assert float(mo.gelu_erf(0.0)) == 0.0
+    assert abs(float(mo.gelu_erf(30.0)) - 30.0) < 1e-12 and abs(float(mo.gelu_erf(-30.0))) < 1e-12
+    # monotone above its minimum near v = -0.7518, whose value is about -0.17
+    g = mo.gelu_erf(np.linspace(-0.75, 8, 500))
+    assert (np.diff(g) > 0).all()
+    assert abs(float(mo.gelu_erf(-0.7517915246935645)) + 0.16997120747) < 1e-9
+
+
+def _solve_tanh_argument(target):
+    """v with sqrt(2/pi) * (v + 0.044715 v^3) = target (bisection, plain floats)."""
+    lo, hi = 0.0, 4.0
+    for _ in range(200):
+        mid = 0.5 * (lo + hi)
+        if math.sqrt(2 / math.pi) * (mid + 0.044715 * mid ** 3) < target:
+            lo = mid
+        else:
+            hi = mid
+    return 0.5 * (lo + hi)
+
+
+def test_gelu_tanh_at_textbook_tanh_points():
+    """Where the cubic argument equals 1/2 or 1 the tanh form is v/2 * (1 +
+    tanh(1/2)) or v/2 * (1 + tanh(1)); fixed literal values besides."""
+    for target, th in ((0.5, TANH_HALF), (1.0, TANH_ONE)):
+        v = _solve_tanh_argument(target)
+        assert abs(float(mo.gelu_tanh(v)) - 0.5 * v * (1.0 + th)) < 1e-14
+        assert abs(float(mo.gelu_tanh(-v)) + 0.5 * v * (1.0 - th)) < 1e-14
+    for v, want in ((-3.0, -0.0036373920817729943), (-1.0, -0.15880800939172324),
+                    (0.5, 0.34571400982514394), (1.0, 0.8411919906082768),
+                    (2.0, 1.954597694087775), (3.0, 2.996362607918227)):
+        assert abs(float(mo.gelu_tanh(v)) - want) < 1e-15
+    v = np.linspace(-8, 8, 81)
+    np.testing.assert_allclose(mo.gelu_tanh(v) - mo.gelu_tanh(-v), v, rtol=0, atol=1e-14)
+    # the two named options are different functions, close to each other
+    diff = np.abs(mo.gelu_tanh(v) - mo.gelu_erf(v))
+    assert 1e-4 < diff.max() < 5e-4
+
+
+def test_activation_is_an_argument():
+    rng = np.random.default_rng(7)
+    d, k, hid = 4, 2, 5
+    rows = rng.standard_normal((6, d)).astype(np.float16).astype(np.float64)
+    w = _random_weights(rng, d, k, hid)
+    plan = mo.chunk_plan(6, 2, 4, k)
+    ye = mo.compress_rows(rows, plan, w, k, "gelu_erf")
+    yt = mo.compress_rows(rows, plan, w, k, "gelu_tanh")
+    assert ye.dtype == np.float64 and (ye == mo.compress_rows(rows, plan, w, k)).all()
+    assert 0 < np.abs(ye - yt).max() < 5e-3
+    with pytest.raises(KeyError):
+        mo.compress_rows(rows, plan, w, k, "relu")
+
+
+def _random_weights(rng, d, k, hid):
+    return {"w1": [rng.standard_normal((hid, k * d)).astype(np.float16) * np.float16(0.5) for _ in range(2)],
+            "b1": [rng.standard_normal(hid).astype(np.float32) for _ in range(2)],
+            "w2": [rng.standard_normal((d, hid)).astype(np.float16) * np.float16(0.5) for _ in range(2)],
+            "b2": [rng.standard_normal(d).astype(np.float32) for _ in range(2)]}
 
 
 def _mean_network(d, k, scale_text, scale_image, c=12.0):
@@ -59,24 +126,24 @@ def test_mean_network_closed_form():
     L, d, k, a, b = 23, 8, 4, 5, 18
     rows = rng.standard_normal((L, d)).astype(np.float16).astype(np.float64)
     plan = mo.chunk_plan(L, a, b, k)
-    y = mo.compress_rows(rows, plan, _mean_network(d, k, 1.0, 2.0), k).astype(np.float64)
-    assert y.shape == (len(plan), d)
-    for o, (s, e, m) in enumerate(plan):
-        want = rows[s:min(s + k, e)].sum(axis=0) / k * (2.0 if m else 1.0)
-        # the hidden value (mean + 12) is held in fp16: spacing 2^-7 in [8, 16)
-        np.testing.assert_allclose(y[o], want, atol=2 ** -7)
+    for act in ("gelu_erf", "gelu_tanh"):
+        y = mo.compress_rows(rows, plan, _mean_network(d, k, 1.0, 2.0), k, act)
+        assert y.shape == (len(plan), d) and y.dtype == np.float64
+        for o, (s, e, m) in enumerate(plan):
+            want = rows[s:min(s + k, e)].sum(axis=0) / k * (2.0 if m else 1.0)
+            # nothing is rounded on the way; gelu(v) = v to 1e-13 for v > 8
+            np.testing.assert_allclose(y[o], want, atol=1e-12)
 
 
 def test_against_scalar_brute_force():
     rng = np.random.default_rng(1)
     L, d, k, hid = 11, 4, 3, 6
     rows = rng.standard_normal((L, d)).astype(np.float16).astype(np.float64)
-    w = {"w1": [rng.standard_normal((hid, k * d)).astype(np.float16) * np.float16(0.5) for _ in range(2)],
-         "b1": [rng.standard_normal(hid).astype(np.float32) for _ in range(2)],
-         "w2": [rng.standard_normal((d, hid)).astype(np.float16) * np.float16(0.5) for _ in range(2)],
-         "b2": [rng.standard_normal(d).astype(np.float32) for _ in range(2)]}
+    w = _random_weights(rng, d, k, hid)
     plan = mo.chunk_plan(L, 2, 9, k)
-    y = mo.compress_rows(rows, plan, w, k)
+    hidden = []
+    y = mo.compress_rows(rows, plan, w, k, "gelu_erf", hidden_out=hidden)
+    assert len(hidden) == len(plan)
     for o, (s, e, m) in enumerate(plan):
         x = []
         for t in range(k):
@@ -84,11 +151,11 @@ def test_against_scalar_brute_force():
         hvals = []
         for u in range(hid):
             z = sum(float(w["w1"][m][u][c]) * x[c] for c in range(k * d)) + float(w["b1"][m][u])
-            g = 0.5 * z * (1 + math.tanh(math.sqrt(2 / math.pi) * (z + 0.044715 * z ** 3)))
-            hvals.append(float(np.float16(g)))
+            hvals.append(z * 0.5 * math.erfc(-z / math.sqrt(2.0)))    # z * Phi(z)
+            assert abs(hvals[u] - hidden[o][u]) < 1e-14
         for c in range(d):
             z = sum(float(w["w2"][m][c][u]) * hvals[u] for u in range(hid)) + float(w["b2"][m][c])
-            assert float(y[o][c]) == float(np.float16(z))
+            assert abs(float(y[o][c]) - z) < 1e-13
 
 
 def test_batch_bookkeeping_and_transparent_copy():
@@ -115,7 +182,8 @@ def test_batch_bookkeeping_and_transparent_copy():
                     for t in range(int(lens[r])):
                         new = kv[l, bt[r, t // bs], c, h, t % bs].astype(np.float64)
                         old = kv0[l, bt0[r, t // bs], c, h, t % bs].astype(np.float64)
-                        np.testing.assert_allclose(new, old, atol=2 ** -7)
+                        # nothing but the store rounds, and old is an fp16 value already
+                        np.testing.assert_allclose(new, old, rtol=0, atol=1e-12)
     assert (bt[1] == bt0[1]).all()
     live = []
     for r in range(3):
