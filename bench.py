@@ -21,72 +21,145 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 
-# HBM bytes per launch of the dominant kernel, measured with rocprofv3 --pmc
-# FETCH_SIZE / WRITE_SIZE and scaled by what the same counters read for a plain
-# 4 GiB copy (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000 on this chip); summary and
-# commands in profiles/fused_unit_kernel_config2_config3_config4.md.
-MEASURED_TRAFFIC_BYTES = {
-    ("config3_batched_mixed", "fused_unit"): 25.30e9,
-    ("config4_multi_image", "fused_unit"): 211.66e9,
-    # profiles/fused_unit_kernel_config4_lse.md
-    ("config4_multi_image_lse_supplied", "fused_unit"): 138.12e9,
-    # profiles/mlp_compress_kernel_config4_mlp.md
-    ("config4_multi_image_mlp", "mlp_compress"): 210.6e9,
-}
+CSRC_DIR = os.path.join(ROOT, "paper_2503_08461_amd", "csrc")
+PROFILES_DIR = os.path.join(ROOT, "profiles")
+
+
+def csrc_digest():
+    """Short hash of every kernel and host source of the library: a traffic
+    figure measured with rocprofv3 belongs to the sources it was measured on."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(CSRC_DIR)):
+        if name.endswith((".hip", ".h", ".cpp")):
+            h.update(name.encode())
+            with open(os.path.join(CSRC_DIR, name), "rb") as f:
+                h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` on `workload` from the rocprofv3 counter
+    summaries under profiles/ (FETCH_SIZE and WRITE_SIZE, each scaled by what it
+    reads for a plain copy of known size).  A summary states its figure in a line
+      traffic-record: workload=<name> kernel=<name> bytes=<float> csrc=<digest> commit=<hash>
+    and the figure counts only while the library sources still hash to <digest>:
+    returns (bytes, where it comes from), or (None, why not)."""
+    import re
+    now = csrc_digest()
+    stale = None
+    for name in sorted(os.listdir(PROFILES_DIR)) if os.path.isdir(PROFILES_DIR) else []:
+        if not name.endswith((".md", ".txt")):
+            continue
+        with open(os.path.join(PROFILES_DIR, name)) as f:
+            for line in f:
+                m = re.match(r"\s*traffic-record:\s*workload=(\S+)\s+kernel=(\S+)\s+bytes=(\S+)"
+                             r"\s+csrc=(\S+)\s+commit=(\S+)", line)
+                if not m or m.group(1) != workload or m.group(2) != kernel:
+                    continue
+                if m.group(4) == now:
+                    return float(m.group(3)), "profiles/%s (commit %s, csrc %s)" % (
+                        name, m.group(5), now)
+                stale = "profiles/%s was measured on other sources (csrc %s, now %s)" % (
+                    name, m.group(4), now)
+    return None, stale or "no rocprofv3 counter summary for this kernel and workload"
+
+
+def _oracle_unit(job):
+    """Worker of the all-cores baseline: one (request, layer, head) unit through
+    the oracle, single-threaded.  Returns the unit's token count."""
+    import numpy as np
+    from threadpoolctl import threadpool_limits
+    from oracle import fastcache_oracle as fo
+    mini, q, L, window, method, budget, pool_kernel, n_old = job
+    st = fo.FreeStack(mini.shape[1])
+    bt = st.alloc(n_old)[None, :].copy()
+    lens = np.array([L], dtype=np.int32)
+    with threadpool_limits(limits=1):
+        status, _, _ = fo.compress_batch(mini, st, bt, lens, q, window,
+                                         np.array([method], np.int32),
+                                         np.array([budget], np.int32), pool_kernel)
+    assert status is None
+    return L
+
+
+def _worker_ready(_):
+    from oracle import fastcache_oracle  # noqa: F401  (import cost outside the timed region)
+    return os.getpid()
+
+
+def _sample_unit(dw, rng):
+    """Inputs of one random (request, layer, head) unit, downloaded from the
+    device pool as a one-layer, one-head pool of its own."""
+    import numpy as np
+    import torch
+    from oracle import fastcache_oracle as fo
+    wl = dw.wl
+    while True:
+        r = int(rng.integers(wl.n_req))
+        if wl.methods[r] != fo.METHOD_NONE:
+            break
+    l = int(rng.integers(wl.n_layers))
+    h = int(rng.integers(wl.n_heads))
+    L, B = int(wl.seq_lens[r]), int(wl.budgets[r])
+    n_old, n_new = fo.blocks_for(L, wl.block_size), fo.blocks_for(B, wl.block_size)
+    ids = torch.from_numpy(dw.bt0_host[r, :n_old].astype(np.int64)).to(dw.dev)
+    mini = np.zeros((1, n_old + n_new, 2, 1, wl.block_size, wl.head_dim), np.float16)
+    mini[0, :n_old, :, 0] = dw.kv[l, ids, :, h].cpu().numpy()
+    q = dw.q[r:r + 1, l:l + 1, h:h + 1].cpu().numpy()
+    return (mini, q, L, wl.window, int(wl.methods[r]), B, wl.pool_kernel, n_old)
 
 
 def cpu_baseline(dw, seconds=15.0, seed=0):
-    """The CPU oracle, as it stands, timed on a bounded random sample of
+    """The CPU oracle, as it stands, timed on bounded random samples of
     (request, layer, head) units of the same workload (bytes downloaded from
-    the device pool; the download is not timed).  One thread."""
+    the device pool; the download is not timed): first on one core, then on all
+    the cores this process may use, one single-threaded oracle per core over
+    independent units (a process pool; the time includes handing the units to
+    the workers).  `value` is the all-cores figure."""
+    import multiprocessing as mp
     import numpy as np
-    import torch
-    from threadpoolctl import threadpool_limits
-    from oracle import fastcache_oracle as fo
     wl = dw.wl
     rng = np.random.Generator(np.random.PCG64(seed))
     n_lh = wl.n_layers * wl.n_heads
-    bt0 = dw.bt0.cpu().numpy()
+    dw.bt0_host = dw.bt0.cpu().numpy()
+    # ---- one core
     spent, token_heads, units = 0.0, 0, 0
-    with threadpool_limits(limits=1):
-        while spent < seconds and units < 4096:
-            r = int(rng.integers(wl.n_req))
-            l = int(rng.integers(wl.n_layers))
-            h = int(rng.integers(wl.n_heads))
-            if wl.methods[r] == fo.METHOD_NONE:
-                continue
-            L, B = int(wl.seq_lens[r]), int(wl.budgets[r])
-            n_old, n_new = fo.blocks_for(L, wl.block_size), fo.blocks_for(B, wl.block_size)
-            ids = torch.from_numpy(bt0[r, :n_old].astype(np.int64)).to(dw.dev)
-            mini = np.zeros((1, n_old + n_new, 2, 1, wl.block_size, wl.head_dim), np.float16)
-            mini[0, :n_old, :, 0] = dw.kv[l, ids, :, h].cpu().numpy()
-            q = dw.q[r:r + 1, l:l + 1, h:h + 1].cpu().numpy()
-            st = fo.FreeStack(n_old + n_new)
-            bt = st.alloc(n_old)[None, :].copy()
-            lens = np.array([L], dtype=np.int32)
+    while spent < 0.4 * seconds and units < 4096:
+        job = _sample_unit(dw, rng)
+        t0 = time.perf_counter()
+        token_heads += _oracle_unit(job)
+        spent += time.perf_counter() - t0
+        units += 1
+    one = {"value": token_heads / n_lh / spent, "unit": "tokens/s", "cores": 1,
+           "sample": "%d units = %d token-heads in %.1f s" % (units, token_heads, spent)}
+    # ---- all cores (the GPU box gives a one-GPU job 16 of them, whatever nproc says)
+    n_workers = max(1, min(16, len(os.sched_getaffinity(0))))
+    spent, token_heads, units = 0.0, 0, 0
+    with mp.get_context("spawn").Pool(n_workers) as pool:
+        pool.map(_worker_ready, range(4 * n_workers), chunksize=1)
+        while spent < 0.6 * seconds and units < 16384:
+            jobs = [_sample_unit(dw, rng) for _ in range(3 * n_workers)]
             t0 = time.perf_counter()
-            status, _, _ = fo.compress_batch(mini, st, bt, lens, q, wl.window,
-                                             wl.methods[r:r + 1], wl.budgets[r:r + 1],
-                                             wl.pool_kernel)
+            token_heads += sum(pool.map(_oracle_unit, jobs, chunksize=1))
             spent += time.perf_counter() - t0
-            assert status is None
-            token_heads += L
-            units += 1
+            units += len(jobs)
     return {
         "value": token_heads / n_lh / spent,
         "unit": "tokens/s",
-        "cores": 1,
+        "cores": n_workers,
         "kind": "oracle",
-        "sample": "%d random (request, layer, head) units of %s = %d token-heads in %.1f s, "
-                  "scaled by 1/%d layer-heads per token" % (units, wl.name, token_heads, spent,
-                                                            n_lh),
+        "sample": "%d random (request, layer, head) units of %s = %d token-heads in %.1f s of "
+                  "wall time on %d single-threaded worker processes, scaled by 1/%d layer-heads "
+                  "per token" % (units, wl.name, token_heads, spent, n_workers, n_lh),
+        "one_core": one,
     }
 
 
 MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X published dense fp16 MFMA peak
 
 
-def cpu_baseline_mlp(dw, weights, k, img_b, img_e, seconds=15.0, seed=0):
+def cpu_baseline_mlp(dw, weights, k, img_b, img_e, activation, seconds=15.0, seed=0):
     """The chunk-MLP oracle, as it stands, timed on random (request, layer,
     head, K|V) units of the same workload.  One thread."""
     import numpy as np
@@ -112,7 +185,7 @@ def cpu_baseline_mlp(dw, weights, k, img_b, img_e, seconds=15.0, seed=0):
             rows = dw.kv[l, ids, kv, h].cpu().numpy().reshape(-1, wl.head_dim)[:L].astype(np.float64)
             t0 = time.perf_counter()
             plan = mo.chunk_plan(L, int(img_b[r]), int(img_e[r]), k)
-            mo.compress_rows(rows, plan, w, k, "gelu_tanh")
+            mo.compress_rows(rows, plan, w, k, activation)
             spent += time.perf_counter() - t0
             tokens += L
             units += 1
@@ -146,7 +219,8 @@ def bench_mlp(args, wl):
           for _ in range(2)]
     b1 = [0.1 * torch.randn(hidden, generator=gen, device=dw.dev) for _ in range(2)]
     b2 = [0.1 * torch.randn(d, generator=gen, device=dw.dev) for _ in range(2)]
-    fc.fc_mlp_set_weights(dw.pool, k, w1, b1, w2, b2)
+    act = {"gelu_erf": fc.FC_ACT_GELU_ERF, "gelu_tanh": fc.FC_ACT_GELU_TANH}[args.mlp_activation]
+    fc.fc_mlp_set_weights(dw.pool, k, w1, b1, w2, b2, act)
     img_b = np.full(wl.n_req, 64, dtype=np.int32)
     img_e = (wl.seq_lens - 64).astype(np.int32)
 
@@ -175,7 +249,8 @@ def bench_mlp(args, wl):
     if hbm_bound:
         roof = {"kernel": "mlp_compress", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": gbs / HBM_PEAK_GBPS,
-                "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, "mlp_compress"))}
+                "traffic": measured_traffic(wl.name, "mlp_compress")[0],
+                "traffic_source": measured_traffic(wl.name, "mlp_compress")[1]}
     else:
         roof = {"kernel": "mlp_compress", "bound": "mfma", "achieved": tf,
                 "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
@@ -186,7 +261,7 @@ def bench_mlp(args, wl):
         "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {"workload": wl.name, "n_req": wl.n_req, "tokens": tokens, "k": k,
-                   "hidden": hidden, "rows_out": chunks, "pool_GiB": round(wl.pool_bytes() / 2**30, 1)},
+                   "hidden": hidden, "activation": args.mlp_activation, "rows_out": chunks, "pool_GiB": round(wl.pool_bytes() / 2**30, 1)},
         "path": {"flops": flops, "algorithmic_bytes": bytes_,
                  "kernel_TFLOPs": tf, "mfma_frac": tf / MFMA_F16_PEAK_TFLOPS,
                  "kernel_GBps": gbs, "hbm_frac": gbs / HBM_PEAK_GBPS},
@@ -196,7 +271,8 @@ def bench_mlp(args, wl):
     if args.cpu_seconds > 0:
         dw.rewind()
         out["cpu_baseline"] = cpu_baseline_mlp(dw, {"w1": w1, "b1": b1, "w2": w2, "b2": b2}, k,
-                                               img_b, img_e, seconds=args.cpu_seconds)
+                                               img_b, img_e, args.mlp_activation,
+                                               seconds=args.cpu_seconds)
     dw.close()
     print(json.dumps(out), flush=True)
 
@@ -446,16 +522,27 @@ def main():
                          "score-free sinks + recent rule (gather and pool work only); "
                          "config4_mlp: the config-4 batch through the chunk-MLP compressor "
                          "(k = 5, hidden 256, synthetic weights)")
+    ap.add_argument("--mlp-activation", default="gelu_erf", choices=["gelu_erf", "gelu_tanh"],
+                    help="activation of the chunk-MLP workload")
     ap.add_argument("--mlp-hidden", type=int, default=256, choices=[128, 256],
                     help="hidden width of the chunk-MLP workload")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="CPU time budget of the oracle baseline (0 = skip)")
     ap.add_argument("--score-mode", default="auto", choices=["auto", "two_pass", "one_pass"],
                     help="which SnapKV score kernel the library uses")
+    ap.add_argument("--split-threshold", type=int, default=0,
+                    help="auto scheduling: SnapKV requests of at least this many tokens take "
+                         "the token-split one-pass score kernel (0, the library's default: none)")
+    ap.add_argument("--csrc-digest", action="store_true",
+                    help="print the hash of the library sources that a traffic-record line "
+                         "in profiles/ has to carry, and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of known size (reference for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
+    if args.csrc_digest:
+        print(csrc_digest())
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the stage has no collectives); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
@@ -502,8 +589,25 @@ def main():
     if args.workload.endswith("_decode"):
         bench_decode(args, wl)
         return
+    out = run_stage(args, wl, args.cpu_seconds)
+    if args.workload == "config4":
+        # the default run also carries config 3 (the benchmark spec sets its bar on both)
+        torch.cuda.empty_cache()
+        c3 = run_stage(args, synth.make_workload(3), 0.0, lse_variant=False)
+        out["config3"] = {k: c3[k] for k in ("value", "unit", "ms_per_step", "config", "path",
+                                             "call_ms", "kernel_ms", "roofline")}
+    print(json.dumps(out), flush=True)
+
+
+def run_stage(args, wl, cpu_seconds, lse_variant=True):
+    """Times fc_compress_batch on one workload; returns the result object."""
+    import numpy as np
+    import torch
+    from paper_2503_08461_amd import synth, fastcache as fc
+    from paper_2503_08461_amd.device_setup import DeviceWorkload
     dw = DeviceWorkload(wl, verbose=True)
     fc.fc_set_score_mode(dw.pool, {"auto": 0, "two_pass": 1, "one_pass": 2}[args.score_mode])
+    fc.fc_set_split_threshold(dw.pool, args.split_threshold)
     fc.fc_set_profiling(dw.pool, True)
     lse_ms = None
     if args.workload.endswith("_precall70"):
@@ -548,10 +652,13 @@ def main():
     comp = wl.methods != synth.METHOD_NONE
     tokens = int(wl.seq_lens[comp].astype(np.int64).sum())
     path_bytes = dw.algorithmic_bytes()
-    kbytes = dw.kernel_algorithmic_bytes(8192 if args.score_mode == "auto" else 0)
+    kbytes = dw.kernel_algorithmic_bytes(args.score_mode, args.split_threshold)
     # dominant kernel = the one with the largest average duration
     dom = max(kbytes, key=lambda k: kavg.get(k, 0.0))
     dom_gbps = kbytes[dom] / (kavg[dom] * 1e-3) / 1e9
+    traffic, traffic_source = measured_traffic(wl.name, dom)
+    if args.score_mode != "auto" or args.split_threshold != 0:
+        traffic, traffic_source = None, "counters are kept for the default scheduling only"
 
     out = {
         "metric": "KV tokens compressed/sec (all layers x heads), batched",
@@ -590,13 +697,14 @@ def main():
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": dom_gbps / HBM_PEAK_GBPS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, dom)) if args.score_mode == "auto"
-            else None,
+            "traffic": traffic,
+            "traffic_source": traffic_source,
         },
     }
     if dw.parts > 1:
         out["config"]["calls_per_step"] = dw.parts
-    if lse_ms is None and dw.parts == 1 and bool((wl.methods == synth.METHOD_SNAPKV).any()):
+    if lse_variant and lse_ms is None and dw.parts == 1 and args.score_mode != "one_pass" and \
+            bool((wl.methods == synth.METHOD_SNAPKV).any()):
         # the same batch when the caller hands over the window rows' log-sum-exp
         # (one pass over K); reported beside the headline value, never as it
         dw.compute_lse()
@@ -622,10 +730,11 @@ def main():
     if lse_ms is not None:
         out["config"]["lse_input"] = ("fc_window_lse before the timed region, %.3f ms "
                                       "(not part of value)" % lse_ms)
-    if args.cpu_seconds > 0:
-        out["cpu_baseline"] = cpu_baseline(dw, args.cpu_seconds)
+    if cpu_seconds > 0:
+        out["cpu_baseline"] = cpu_baseline(dw, cpu_seconds)
     dw.close()
-    print(json.dumps(out), flush=True)
+    del dw
+    return out
 
 
 if __name__ == "__main__":

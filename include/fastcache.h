@@ -164,9 +164,7 @@ int fc_compress_batch(fc_pool* pool, int32_t* dev_block_tables, int max_blocks_p
  * dev_q_window      dev, fp16, 16-byte aligned, packed in batch order over the
  *                   SnapKV requests only: request r contributes
  *                   [n_layers][n_heads][host_window[r]][head_dim].
- * Everything else, including errors, as for fc_compress_batch.  The one-pass
- * scheduling (FC_SCORE_ONE_PASS) takes one window size per batch: FC_EINVAL
- * otherwise.
+ * Everything else, including errors, as for fc_compress_batch.
  */
 int fc_compress_batch_var(fc_pool* pool, int32_t* dev_block_tables, int max_blocks_per_req,
                           int32_t* host_seq_lens, const void* dev_q_window,
@@ -226,16 +224,24 @@ int fc_window_lse(fc_pool* pool, const int32_t* dev_block_tables, int max_blocks
  * is split at the modality boundary, every run of k consecutive tokens of one
  * modality is reshaped into one vector of k*head_dim numbers and mapped to ONE
  * row by that modality's MLP, and the results are concatenated in the
- * original order.  The paper gives neither architecture nor weights; this
- * library takes  y = W2 . gelu(W1 . x + b1) + b2  (tanh-form GELU, one hidden layer)
- * with caller-supplied weights, shared by all layers, heads and by K and V.
- * fp16 rows and weights, fp32 accumulation, hidden activations rounded to
- * fp16 (they are the fp16 operand of the second MFMA product), output rounded
- * to fp16.  head_dim 64 or 128; hidden 128 or 256; k in 1..8.
+ * original order.  The paper gives neither architecture, activation nor
+ * weights; this library takes  y = W2 . act(W1 . x + b1) + b2  (one hidden
+ * layer) with caller-supplied weights, shared by all layers, heads and by K
+ * and V, and the activation as an argument:
+ *   FC_ACT_GELU_ERF   GELU by its definition, v * Phi(v) = v/2 (1 + erf(v/sqrt 2));
+ *   FC_ACT_GELU_TANH  its tanh approximation,
+ *                     v/2 (1 + tanh(sqrt(2/pi) (v + 0.044715 v^3))).
+ * Arithmetic: fp16 rows and weights, fp32 accumulation, the hidden activations
+ * are held in fp16, the output is stored in fp16 (the pool's type): a stored
+ * value y_c differs from the exact one by at most about
+ *   2^-11 |y_c| + sum_u |W2[c][u]| (2^-11 |h_u| + 1e-4).
+ * head_dim 64 or 128; hidden 128 or 256; k in 1..8.
  */
+enum { FC_ACT_GELU_ERF = 0, FC_ACT_GELU_TANH = 1 };
 typedef struct fc_mlp_weights {
   int k;              /* tokens per chunk = compression factor */
   int hidden;         /* hidden width */
+  int activation;     /* FC_ACT_* */
   const void* w1[2];  /* dev, fp16 [hidden][k*head_dim] row-major; [0] text, [1] image */
   const float* b1[2]; /* dev, fp32 [hidden] */
   const void* w2[2];  /* dev, fp16 [head_dim][hidden] row-major */
@@ -244,7 +250,8 @@ typedef struct fc_mlp_weights {
 
 /* Copies the weights into library-owned device memory in the operand order of
  * the kernel (the caller's buffers may be released after the stream has run
- * past this call).  FC_EINVAL for unsupported sizes or NULL pointers. */
+ * past this call).  FC_EINVAL for unsupported sizes, an unknown activation or
+ * NULL pointers. */
 int fc_mlp_set_weights(fc_pool* pool, const fc_mlp_weights* weights, void* stream);
 
 /*
@@ -285,22 +292,33 @@ int fc_set_streaming_sinks(fc_pool* pool, int n_sink);
 /*
  * How fc_compress_batch schedules the scoring.
  *   FC_SCORE_AUTO (default): every (request, layer, head) of at most 8192
- *     tokens is handled by one fused kernel (two-pass score -> select ->
- *     gather inside the workgroup that owns the head; scores stay in LDS);
- *     longer heads go through the separate two-pass score, select and gather
- *     kernels.
+ *     tokens is handled by one fused kernel (two-pass score -> select -> gather
+ *     inside the workgroup that owns the head; scores stay in LDS); longer
+ *     heads go through the separate two-pass score, select and gather kernels.
+ *     With fc_set_split_threshold, SnapKV requests from a given length on are
+ *     scored by the token-split kernel described under FC_SCORE_ONE_PASS.
  *   FC_SCORE_TWO_PASS: separate kernels for everything; SnapKV scoring streams
  *     K twice (row statistics, then column sums); workgroups never wait for
  *     each other; any length up to FC_MAX_SEQ_LEN.
- *   FC_SCORE_ONE_PASS: separate kernels; SnapKV scoring streams K once, the
- *     logits stay in registers and the workgroups that share a long head
- *     exchange row statistics.  Needs a device that can hold the kernel's grid
- *     co-resident; fc_compress_batch returns FC_EINVAL if that is not
- *     possible for the batch.  Slower than two-pass on MI355X as measured.
+ *   FC_SCORE_ONE_PASS: every SnapKV request is scored by the token-split
+ *     kernel: a head is shared by a team of workgroups that each keep a slice
+ *     of its keys in registers, exchange their rows' (max, sum of exp) pairs
+ *     and finish the column sums from the registers, so K is read from HBM
+ *     once; select and gather follow in one kernel per head.  It is a
+ *     persistent kernel that needs its grid co-resident (cooperative launch);
+ *     its waits between workgroups are bounded, and one that runs out is
+ *     reported as FC_EDEVICE by fc_pool_export_state.  FC_EINVAL if the device
+ *     cannot run it or a head has more than 15360 tokens.  As measured on
+ *     MI355X it is slower than reading K twice (the exchange between
+ *     workgroups costs more than the second pass).
  * All three produce the same scores up to fp32 rounding.
  */
 enum { FC_SCORE_AUTO = 0, FC_SCORE_TWO_PASS = 1, FC_SCORE_ONE_PASS = 2 };
 int fc_set_score_mode(fc_pool* pool, int mode);
+
+/* FC_SCORE_AUTO: SnapKV requests of at least min_tokens tokens take the
+ * token-split one-pass score kernel (0, the default: none does). */
+int fc_set_split_threshold(fc_pool* pool, int min_tokens);
 
 /*
  * Per-kernel timing for benchmarks.  With profiling enabled every kernel
@@ -312,7 +330,7 @@ int fc_set_score_mode(fc_pool* pool, int mode);
  * fc_kernel_name(i) names slot i.  fc_set_profiling(pool, 1) restarts the
  * average.
  */
-#define FC_N_KERNELS 11
+#define FC_N_KERNELS 12
 int fc_set_profiling(fc_pool* pool, int enable);
 int fc_get_kernel_times(fc_pool* pool, float* host_ms);
 const char* fc_kernel_name(int i);

@@ -40,7 +40,13 @@ int fail(int code, const char* fmt, ...) {
 const char* const kKernelNames[K_COUNT] = {"plan_alloc", "snapkv_score", "knorm_score",
                                            "select",     "gather",       "reclaim",
                                            "fused_unit", "mlp_compress", "append",
-                                           "decode_attention", "window_lse"};
+                                           "decode_attention", "window_lse", "select_gather"};
+
+// Team sizes of the token-split score kernel when a batch has more distinct
+// ones than launches are worth: a head takes the next size of this ladder.
+const int kTeamLadder[] = {1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 14, 16, 20, 24, 28, 32, 40, 48, 56, 64};
+constexpr int kSplitMaxTeam = 64;
+constexpr int kSplitMaxClasses = 12;
 
 size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -68,22 +74,21 @@ struct fc_pool {
   hipEvent_t meta_event = nullptr;
   bool meta_pending = false;
 
-  // one-pass SnapKV score kernel
-  int32_t* team_counters = nullptr;
-  size_t team_counters_cap = 0;
-  float* team_stats = nullptr;
-  size_t team_stats_cap = 0;
+  // token-split one-pass SnapKV score kernel
+  uint64_t* split_xchg = nullptr;
+  size_t split_xchg_cap = 0;      // 64-bit words
+  int split_min_len = 0;          // FC_SCORE_AUTO: heads at least this long take it (0: none)
   int32_t* error_flag = nullptr;  // device, one int, zero unless a bounded wait ran out
   int score_mode = FC_SCORE_AUTO;
   int n_sink = 4;
   int compact_mode = FC_COMPACT_FRESH;
   // chunk-MLP compressor weights in operand order (library-owned)
-  int mlp_k = 0, mlp_hidden = 0;
+  int mlp_k = 0, mlp_hidden = 0, mlp_activation = 0;
   _Float16* mlp_w1p[2] = {nullptr, nullptr};
   _Float16* mlp_w2p[2] = {nullptr, nullptr};
   float* mlp_b1[2] = {nullptr, nullptr};
   float* mlp_b2[2] = {nullptr, nullptr};
-  int team_grid[FC_MAX_WINDOW / 16 + 1] = {};  // co-resident grid per query-tile count, -1 = none
+  int split_grid[FC_MAX_WINDOW / 16 + 1] = {};  // co-resident grid per query-tile count, -1 = none
 
   bool profiling = false;
   // event ring: the last kProfRing profiled calls, [call][kernel][start, stop]
@@ -180,8 +185,7 @@ int fc_pool_destroy(fc_pool* p) {
   if (p->raw_scores) (void)hipFree(p->raw_scores);
   if (p->kept) (void)hipFree(p->kept);
   if (p->ids) (void)hipFree(p->ids);
-  if (p->team_counters) (void)hipFree(p->team_counters);
-  if (p->team_stats) (void)hipFree(p->team_stats);
+  if (p->split_xchg) (void)hipFree(p->split_xchg);
   if (p->error_flag) (void)hipFree(p->error_flag);
   for (int m = 0; m < 2; ++m) {
     if (p->mlp_w1p[m]) (void)hipFree(p->mlp_w1p[m]);  // w2p lies in the same allocation
@@ -270,6 +274,13 @@ int fc_set_score_mode(fc_pool* p, int mode) {
   return FC_OK;
 }
 
+int fc_set_split_threshold(fc_pool* p, int min_tokens) {
+  if (!p) return fail(FC_EINVAL, "pool is NULL");
+  if (min_tokens < 0) return fail(FC_EINVAL, "min_tokens < 0");
+  p->split_min_len = min_tokens;
+  return FC_OK;
+}
+
 int fc_set_profiling(fc_pool* p, int enable) {
   if (!p) return fail(FC_EINVAL, "pool is NULL");
   p->profiling = enable != 0;
@@ -333,7 +344,7 @@ static int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_bl
   const bool in_place = p->compact_mode == FC_COMPACT_IN_PLACE;
   int total_new = 0, total_old = 0, total_released = 0, max_len = 0;
   size_t score_off = 0, kept_off = 0, q_off = 0;
-  int window_lo = 0, window_hi = 0;  // over the SnapKV requests
+  int window_hi = 0;  // over the SnapKV requests
   for (int r = 0; r < n_req; ++r) {
     const int m = host_method[r];
     // queries are packed: with per-request windows only SnapKV requests have any
@@ -366,7 +377,6 @@ static int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_bl
         return fail(FC_EINVAL, "dev_lse_window must be a 4-byte aligned device pointer");
       if (need_lse && p->score_mode == FC_SCORE_ONE_PASS)
         return fail(FC_EINVAL, "the one-pass scheduling takes no log-sum-exp input");
-      window_lo = window_lo == 0 ? win : std::min(window_lo, win);
       window_hi = std::max(window_hi, win);
     }
     ReqDesc d = {};
@@ -400,46 +410,52 @@ static int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_bl
   if (total_new > p->top)
     return fail(FC_ENOMEM, "batch needs %d new blocks, %d free", total_new, p->top);
 
-  // ---- one-pass SnapKV scoring: team sizes, if the device can hold the grid --
+  // ---- token-split one-pass SnapKV scoring: which requests, which team sizes ----
+  // A request takes it if the scheduling asks for it (FC_SCORE_ONE_PASS: every
+  // SnapKV request; FC_SCORE_AUTO: those of at least split_min_len tokens, if set), the
+  // device can hold the kernel's grid co-resident and the head fits a team.
   int rc;
-  int team_grid = 0;
-  size_t n_team_counters = 0, n_team_stats = 0;
   bool any_snap = false;
   for (const ReqDesc& d : descs) any_snap |= d.method == FC_METHOD_SNAPKV;
-  // AUTO currently means two-pass: measured faster on MI355X for every benchmark shape
-  if (any_snap && p->score_mode == FC_SCORE_ONE_PASS) {
-    if (window_lo != window_hi)
-      return fail(FC_EINVAL, "one-pass scoring takes one window size per batch");
-    window = window_hi;
-    const int nt = (window + 15) / 16;
-    if (p->team_grid[nt] == 0) {
-      const int gsz = team_grid_size(p->head_dim, window);
-      p->team_grid[nt] = gsz > 0 ? gsz : -1;
-    }
-    team_grid = std::max(p->team_grid[nt], 0);
-    const int cap_blocks = team_capacity_tokens(window) / FC_BLOCK_SIZE;
-    for (ReqDesc& d : descs) {
-      d.team_size = 1;
-      d.team_counter = 0;
-      d.team_stats = 0;
-      if (d.method != FC_METHOD_SNAPKV || team_grid == 0) continue;
-      d.team_size = (d.n_old + cap_blocks - 1) / cap_blocks;
-      if (d.team_size > team_grid) {
-        team_grid = 0;  // some head does not fit the co-resident grid
+  std::vector<int> split_team(n_comp, 0);  // 0: not split
+  int n_split_req = 0;
+  if (any_snap && !need_lse && p->score_mode != FC_SCORE_TWO_PASS) {
+    const int cap = split_blocks_per_workgroup();
+    for (int i = 0; i < n_comp; ++i) {
+      const ReqDesc& d = descs[i];
+      if (d.method != FC_METHOD_SNAPKV) continue;
+      if (p->score_mode == FC_SCORE_AUTO && (p->split_min_len == 0 || d.seq_len < p->split_min_len))
         continue;
+      const int nt = (d.window + 15) / 16;
+      if (p->split_grid[nt] == 0) {
+        const int gsz = split_grid_size(p->head_dim, d.window);
+        p->split_grid[nt] = gsz > 0 ? gsz : -1;
       }
-      const int n_teams = team_grid / d.team_size;
-      d.team_counter = (int32_t)n_team_counters;
-      d.team_stats = (int64_t)n_team_stats;
-      n_team_counters += n_teams;
-      n_team_stats += (size_t)n_teams * 2 * d.team_size * 128;
+      const int g = (d.n_old + cap - 1) / cap;
+      if (p->split_grid[nt] > 0 && g <= kSplitMaxTeam && g <= p->split_grid[nt]) {
+        split_team[i] = g;
+        ++n_split_req;
+      } else if (p->score_mode == FC_SCORE_ONE_PASS) {
+        return fail(FC_EINVAL, "request %d: one-pass scoring is not possible on this device "
+                    "(no co-resident grid, or more than %d tokens)", d.table_row,
+                    kSplitMaxTeam * cap * FC_BLOCK_SIZE);
+      }
     }
-    if (team_grid == 0 && p->score_mode == FC_SCORE_ONE_PASS)
-      return fail(FC_EINVAL, "one-pass scoring is not possible for this batch on this device");
+    // few launches: with many distinct team sizes, round them up along the ladder
+    std::vector<int> sizes;
+    for (int g : split_team)
+      if (g > 0) sizes.push_back(g);
+    std::sort(sizes.begin(), sizes.end());
+    sizes.erase(std::unique(sizes.begin(), sizes.end()), sizes.end());
+    if ((int)sizes.size() > kSplitMaxClasses)
+      for (int& g : split_team)
+        if (g > 0) g = *std::lower_bound(std::begin(kTeamLadder), std::end(kTeamLadder), g);
   }
-  if (team_grid > 0) {
-    if ((rc = grow(&p->team_counters, &p->team_counters_cap, n_team_counters)) != FC_OK) return rc;
-    if ((rc = grow(&p->team_stats, &p->team_stats_cap, n_team_stats)) != FC_OK) return rc;
+  if (n_split_req > 0) {
+    int grid_max = 0;
+    for (int g : p->split_grid) grid_max = std::max(grid_max, g);
+    if ((rc = grow(&p->split_xchg, &p->split_xchg_cap, (size_t)2 * grid_max * 64)) != FC_OK)
+      return rc;
   }
 
   // ---- scratch and descriptors --------------------------------------------
@@ -455,7 +471,8 @@ static int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_bl
   // rest go through the separate kernels: SnapKV per class, key-norm, and one
   // list of all of them for select and gather.
   enum { kClasses = 5 };
-  enum { LIST_FUSED = 0, LIST_SNAP = kClasses, LIST_KNORM = 2 * kClasses, LIST_ALL, N_LISTS };
+  enum { LIST_FUSED = 0, LIST_SNAP = kClasses, LIST_KNORM = 2 * kClasses, LIST_ALL, LIST_SPLIT,
+         N_LISTS };
   const size_t meta_bytes = desc_bytes + N_LISTS * order_bytes;
   if ((rc = grow_meta(p, meta_bytes)) != FC_OK) return rc;
   if (p->meta_pending) {
@@ -484,9 +501,11 @@ static int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_bl
   std::stable_sort(sorted.begin(), sorted.end(),
                    [&](int a, int b) { return weight(a) > weight(b); });
   const bool allow_fused = p->score_mode == FC_SCORE_AUTO;
-  auto fused = [&](const ReqDesc& d) {
+  auto fused = [&](int i) {
+    const ReqDesc& d = descs[i];
     // (streaming: no score, no LDS, so the fused kernel whatever the length)
-    return d.method == FC_METHOD_STREAMING || (allow_fused && d.seq_len <= kFusedMaxLen);
+    return d.method == FC_METHOD_STREAMING ||
+           (allow_fused && split_team[i] == 0 && d.seq_len <= kFusedMaxLen);
   };
   // Units without queries (key-norm, streaming) ride in the launch of the
   // SnapKV class that has the most fused units, if there is one: one launch
@@ -494,8 +513,8 @@ static int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_bl
   int home_class = 0;
   {
     int count[kClasses] = {};
-    for (const ReqDesc& d : descs)
-      if (d.method == FC_METHOD_SNAPKV && fused(d)) ++count[(d.window + 15) / 16];
+    for (int i = 0; i < n_comp; ++i)
+      if (descs[i].method == FC_METHOD_SNAPKV && fused(i)) ++count[(descs[i].window + 15) / 16];
     for (int c = 1; c < kClasses; ++c)
       if (count[c] > count[home_class]) home_class = c;
   }
@@ -505,8 +524,14 @@ static int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_bl
     const bool snap = d.method == FC_METHOD_SNAPKV;
     const int cls = snap ? (d.window + 15) / 16 : 0;
     int li;
-    if (fused(d)) {
+    if (fused(di)) {
       li = LIST_FUSED + (snap ? cls : home_class);
+    } else if (split_team[di] > 0) {
+      // scores through the scratch; listed below, grouped by launch
+      reinterpret_cast<ReqDesc*>(p->host_meta)[di].raw_off = (int64_t)raw_need;
+      raw_need += n_lh * (size_t)d.seq_len;
+      max_len_list[LIST_SPLIT] = std::max(max_len_list[LIST_SPLIT], d.seq_len);
+      continue;
     } else {
       // scores of these units travel through the library's scratch
       reinterpret_cast<ReqDesc*>(p->host_meta)[di].raw_off = (int64_t)raw_need;
@@ -518,6 +543,27 @@ static int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_bl
     lists[li][n_list[li]++] = di;
     // (sizes the score buffer in LDS, which streaming units do not use)
     if (d.method != FC_METHOD_STREAMING) max_len_list[li] = std::max(max_len_list[li], d.seq_len);
+  }
+  // token-split launches: one per (team size, query-tile count), requests of a
+  // launch contiguous in LIST_SPLIT, heaviest first inside it
+  struct SplitLaunch {
+    int team, nt, first, count;
+  };
+  std::vector<SplitLaunch> split_launches;
+  if (n_split_req > 0) {
+    std::vector<int> idx;
+    for (int di : sorted)
+      if (split_team[di] > 0) idx.push_back(di);
+    auto key = [&](int i) { return split_team[i] * 8 + (descs[i].window + 15) / 16; };
+    std::stable_sort(idx.begin(), idx.end(), [&](int a, int b) { return key(a) > key(b); });
+    for (int di : idx) {
+      const int nt = (descs[di].window + 15) / 16;
+      if (split_launches.empty() || split_launches.back().team != split_team[di] ||
+          split_launches.back().nt != nt)
+        split_launches.push_back({split_team[di], nt, n_list[LIST_SPLIT], 0});
+      ++split_launches.back().count;
+      lists[LIST_SPLIT][n_list[LIST_SPLIT]++] = di;
+    }
   }
   int ns = 0, n_fused = 0;
   for (int c = 0; c < kClasses; ++c) {
@@ -550,6 +596,10 @@ static int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_bl
   // per launch: order_snap / n_snap, order_fused / n_fused, window (of the class)
   bp.order_snap = bp.order_fused = nullptr;
   bp.n_snap = bp.n_fused = 0;
+  bp.order_split = dev_list(LIST_SPLIT);
+  bp.n_split = n_list[LIST_SPLIT];
+  bp.split_team = 0;
+  bp.split_xchg = p->split_xchg;
   bp.block_tables = dev_block_tables;
   bp.max_blocks = max_blocks_per_req;
   bp.old_ids = p->ids;
@@ -565,8 +615,6 @@ static int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_bl
   bp.raw_scores = p->raw_scores;
   bp.scores_out = dev_scores_out;
   bp.kept = dev_kept_out ? dev_kept_out : p->kept;
-  bp.team_counters = p->team_counters;
-  bp.team_stats = p->team_stats;
   bp.error_flag = p->error_flag;
 
   // ---- the stage ------------------------------------------------------------
@@ -587,21 +635,32 @@ static int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_bl
     return e;
   };
   FC_HIP(run(K_PLAN_ALLOC, true, [&] { return launch_plan_alloc(bp, stream); }));
-  if (ns > 0 && team_grid > 0)
-    FC_HIP(launch_zero_ints(p->team_counters, (int)n_team_counters, stream));
-  FC_HIP(run(K_SNAPKV_SCORE, ns > 0, [&] {
+  FC_HIP(run(K_SNAPKV_SCORE, ns > 0 || !split_launches.empty(), [&] {
     hipError_t e = hipSuccess;
+    for (const SplitLaunch& sl : split_launches) {
+      if (e != hipSuccess) break;
+      const int grid = p->split_grid[sl.nt];
+      // (a fill kernel, not a memset: the call may be captured into a graph)
+      e = launch_zero_ints(reinterpret_cast<int32_t*>(p->split_xchg), 2 * grid * 64 * 2, stream);
+      BatchParams bc = bp;
+      bc.order_split = dev_list(LIST_SPLIT) + sl.first;
+      bc.n_split = sl.count;
+      bc.split_team = sl.team;
+      bc.window = 16 * sl.nt;
+      if (e == hipSuccess) e = launch_snapkv_split(bc, grid, stream);
+    }
     for (int c = 1; c < kClasses && e == hipSuccess; ++c) {
       if (n_list[LIST_SNAP + c] == 0) continue;
       BatchParams bc = bp;
       bc.order_snap = dev_list(LIST_SNAP + c);
       bc.n_snap = n_list[LIST_SNAP + c];
-      bc.window = team_grid > 0 ? window_hi : 16 * c;
-      e = team_grid > 0 ? launch_snapkv_score_team(bc, team_grid, stream)
-                        : launch_snapkv_score(bc, stream);
+      bc.window = 16 * c;
+      e = launch_snapkv_score(bc, stream);
     }
     return e;
   }));
+  FC_HIP(run(K_SELECT_GATHER, bp.n_split > 0,
+             [&] { return launch_select_gather(bp, max_len_list[LIST_SPLIT], stream); }));
   FC_HIP(run(K_KNORM_SCORE, nk > 0, [&] { return launch_knorm_score(bp, stream); }));
   FC_HIP(run(K_SELECT, bp.n_unfused > 0,
              [&] { return launch_select(bp, max_len_list[LIST_ALL], stream); }));
@@ -752,6 +811,8 @@ int fc_mlp_set_weights(fc_pool* p, const fc_mlp_weights* w, void* stream_) {
   if (!p || !w) return fail(FC_EINVAL, "NULL argument");
   if (w->k < 1 || w->k > 8) return fail(FC_EINVAL, "k must be in 1..8");
   if (w->hidden != 128 && w->hidden != 256) return fail(FC_EINVAL, "hidden must be 128 or 256");
+  if (w->activation != FC_ACT_GELU_ERF && w->activation != FC_ACT_GELU_TANH)
+    return fail(FC_EINVAL, "unknown activation %d", w->activation);
   for (int m = 0; m < 2; ++m)
     if (!w->w1[m] || !w->b1[m] || !w->w2[m] || !w->b2[m])
       return fail(FC_EINVAL, "NULL weight pointer");
@@ -782,6 +843,7 @@ int fc_mlp_set_weights(fc_pool* p, const fc_mlp_weights* w, void* stream_) {
   }
   p->mlp_k = w->k;
   p->mlp_hidden = w->hidden;
+  p->mlp_activation = w->activation;
   return FC_OK;
 }
 
@@ -895,6 +957,7 @@ int fc_compress_batch_mlp(fc_pool* p, int32_t* dev_block_tables, int max_blocks_
   }
   mp.k = k;
   mp.hidden = p->mlp_hidden;
+  mp.activation = p->mlp_activation;
   for (int m = 0; m < 2; ++m) {
     mp.w1p[m] = p->mlp_w1p[m];
     mp.w2p[m] = p->mlp_w2p[m];

@@ -8,8 +8,11 @@ namespace fc {
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-static constexpr int kThreads = 256;  // 4 wavefronts per workgroup
-static constexpr int kWaves = 4;
+#ifndef FC_WAVES
+#define FC_WAVES 4
+#endif
+static constexpr int kWaves = FC_WAVES;  // wavefronts per workgroup
+static constexpr int kThreads = 64 * kWaves;
 
 __device__ __forceinline__ int clamp_block(int blk, int n_blocks) {
   // Block ids come from caller-owned device memory; an id outside the pool

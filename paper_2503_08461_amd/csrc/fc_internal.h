@@ -23,16 +23,11 @@ struct ReqDesc {
   int64_t raw_off;    // same in the library's un-pooled score scratch (separate kernels only)
   int64_t kept_off;   // start of [layer][head][B_r] in the kept buffer
   int64_t q_off;      // start of [layer][head][window][d] in q_window
-  // one-pass SnapKV score kernel: workgroups that share one (layer, head)
-  int32_t team_size;     // g_r
-  int32_t team_counter;  // first of this request's n_wg/g_r team counters
-  int64_t team_stats;    // first float of this request's exchange buffers
   // chunk-MLP compressor: the image span and the chunk counts of the three segments
   int32_t img_begin, img_end;
   int32_t chunks_text0, chunks_image, chunks_text1;
   // SnapKV: this request's observation window and max-pool width
   int32_t window, pool_kernel;
-  int32_t pad_;
 };
 
 // One (request, modality) job of the chunk-MLP kernel: rows = units x chunks.
@@ -48,6 +43,7 @@ struct MlpParams {
   int32_t n_jobs, n_tiles;
   int32_t max_grid;    // workgroups to launch at most (as many as are resident)
   int32_t k, hidden;
+  int32_t activation;  // FC_ACT_*
   // weights in operand order, index 0 text / 1 image; w2p[m] starts where w1p[m] ends
   const _Float16* w1p[2];
   const _Float16* w2p[2];
@@ -97,7 +93,9 @@ struct BatchParams {
   const int32_t* order_snap;   // [n_snap]
   const int32_t* order_knorm;  // [n_knorm]
   const int32_t* order_fused;  // [n_fused] units handled by the fused kernel (both methods)
-  int32_t n_comp, n_snap, n_knorm, n_unfused, n_fused;
+  const int32_t* order_split;  // [n_split] SnapKV requests of a token-split score launch, or all
+                               // of them for the select + gather launch that follows
+  int32_t n_comp, n_snap, n_knorm, n_unfused, n_fused, n_split;
   int32_t* block_tables;       // caller's [n_req][max_blocks]
   int32_t max_blocks;
   int32_t* old_ids;            // [total_old] saved pre-compression ids
@@ -114,9 +112,9 @@ struct BatchParams {
   float* raw_scores;           // un-pooled scores of the units that take the separate kernels
   float* scores_out;           // nullable
   int32_t* kept;               // kept indices, packed
-  // one-pass SnapKV score kernel (persistent, co-resident grid)
-  int32_t* team_counters;      // zeroed before the launch
-  float* team_stats;           // (max, sum) exchange between team members
+  // token-split one-pass SnapKV score kernel (persistent, co-resident grid)
+  int32_t split_team;          // workgroups that share one (layer, head) in this launch
+  uint64_t* split_xchg;        // [2][grid][64] tagged (max, sum) pairs, zeroed before the launch
   int32_t* error_flag;         // set if a bounded wait ran out
 };
 
@@ -132,7 +130,8 @@ enum KernelSlot {
   K_APPEND = 8,
   K_DECODE_ATTENTION = 9,
   K_WINDOW_LSE = 10,
-  K_COUNT = 11
+  K_SELECT_GATHER = 11,
+  K_COUNT = 12
 };
 
 // Launchers (fc_kernels.hip).  Each returns the hipError_t of the launch.
@@ -141,13 +140,15 @@ hipError_t launch_pool_pop(const int32_t* stack, int top, int n, int32_t* out, h
 hipError_t launch_pool_push(int32_t* stack, int top, int n, const int32_t* ids, hipStream_t s);
 hipError_t launch_plan_alloc(const BatchParams& p, hipStream_t s);
 hipError_t launch_snapkv_score(const BatchParams& p, hipStream_t s);
-// One-pass variant.  team_capacity_tokens(head_dim, window) is how many tokens
-// one workgroup can hold; team_grid_size() is the co-resident grid (0 if the
-// device cannot run it); launch_zero_ints clears the team counters.
-int team_capacity_tokens(int window);
-int team_grid_size(int head_dim, int window);
+// Token-split one-pass variant (fc_score_split.hip).  split_blocks_per_workgroup()
+// is how many 16-token blocks of a head one workgroup can hold; split_grid_size()
+// is the co-resident grid (0 if the device cannot run it); launch_zero_ints
+// clears the exchange buffers; launch_select_gather finishes the heads scored so.
+int split_blocks_per_workgroup();
+int split_grid_size(int head_dim, int window);
 hipError_t launch_zero_ints(int32_t* p, int n, hipStream_t s);
-hipError_t launch_snapkv_score_team(const BatchParams& p, int grid, hipStream_t s);
+hipError_t launch_snapkv_split(const BatchParams& p, int grid, hipStream_t s);
+hipError_t launch_select_gather(const BatchParams& p, int max_seq_len, hipStream_t s);
 hipError_t launch_knorm_score(const BatchParams& p, hipStream_t s);
 hipError_t launch_select(const BatchParams& p, int max_seq_len, hipStream_t s);
 hipError_t launch_gather(const BatchParams& p, hipStream_t s);

@@ -768,14 +768,44 @@ __global__ __launch_bounds__(kThreads) void fused_unit_kernel(BatchParams p) {
 }
 
 // ---------------------------------------------------------------------------
+// select + gather of the heads whose scores came through the score scratch
+// (those of the token-split one-pass score kernel)
+// ---------------------------------------------------------------------------
+
+template <int D>
+__global__ __launch_bounds__(kThreads) void select_gather_kernel(BatchParams p) {
+  extern __shared__ uint32_t keys[];
+  __shared__ SelectShared sh;
+  __shared__ int32_t sm_ids[kFusedMaxLen / 16];
+  const int n_lh = p.n_layers * p.n_heads;
+  const int slot = blockIdx.x / n_lh;
+  const int lh = blockIdx.x - slot * n_lh;
+  const ReqDesc rd = p.descs[p.order_split[slot]];
+  const bool ids_in_lds = rd.n_old <= kFusedMaxLen / 16;
+  if (ids_in_lds)
+    for (int i = threadIdx.x; i < rd.n_old; i += kThreads)
+      sm_ids[i] = clamp_block(p.old_ids[rd.old_off + i], p.n_blocks);
+  select_unit<false>(p, rd, lh, keys, sh);
+  __syncthreads();  // the kept list (global memory, this workgroup's own) is complete
+  gather_unit<D>(p, rd, lh, ids_in_lds ? sm_ids : p.old_ids + rd.old_off);
+}
+
+// ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
 
 hipError_t kernels_one_time_setup() {
   // the select kernel may need more than the default 64 KiB of dynamic LDS
   // (the fused kernel never does: kFusedMaxLen * 4 = 32 KiB)
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, 32768 * 4);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, 32768 * 4);
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(select_gather_kernel<128>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 32768 * 4);
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(select_gather_kernel<64>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 32768 * 4);
+  return e;
 }
 
 hipError_t launch_stack_init(int32_t* stack, int n_blocks, hipStream_t s) {
@@ -874,6 +904,19 @@ hipError_t launch_gather(const BatchParams& p, hipStream_t s) {
     gather_kernel<128><<<grid, kThreads, 0, s>>>(p);
   else if (p.head_dim == 64)
     gather_kernel<64><<<grid, kThreads, 0, s>>>(p);
+  else
+    return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+hipError_t launch_select_gather(const BatchParams& p, int max_seq_len, hipStream_t s) {
+  if (p.n_split == 0) return hipSuccess;
+  const unsigned grid = (unsigned)p.n_split * p.n_layers * p.n_heads;
+  const size_t lds = (size_t)max_seq_len * sizeof(uint32_t);
+  if (p.head_dim == 128)
+    select_gather_kernel<128><<<grid, kThreads, lds, s>>>(p);
+  else if (p.head_dim == 64)
+    select_gather_kernel<64><<<grid, kThreads, lds, s>>>(p);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();

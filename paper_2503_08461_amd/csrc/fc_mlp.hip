@@ -1,5 +1,5 @@
 // Chunk-MLP compressor kernel for gfx950: every run of k consecutive tokens
-// of one modality becomes one row, y = W2 . gelu(W1 . x + b1) + b2 (tanh GELU).
+// of one modality becomes one row, y = W2 . act(W1 . x + b1) + b2 (GELU, erf or tanh form).
 //
 // This is the one dense contraction of the library that is MFMA-bound
 // (about 390 kflop per 1.3 KB chunk at k = 5, d = 128, hidden = 256), so it is
@@ -100,17 +100,39 @@ hipError_t launch_mlp_permute_weights(const _Float16* w1, const _Float16* w2, _F
 // tanh form of GELU, v/2 * (1 + tanh(u)) with u = sqrt(2/pi) * (v + 0.044715 v^3),
 // written as v / (1 + exp(-2u)) = v / (1 + exp2(v * (A + B v^2))) with the
 // constants folded (A = -2 log2(e) sqrt(2/pi), B = 0.044715 A): one exp2, one
-// reciprocal and five other operations per value (the erf form costs about 40
-// VALU instructions per value, more than the MFMAs)
+// reciprocal and five other operations per value
 __device__ __forceinline__ float gelu_tanh(float v) {
   const float e = __builtin_amdgcn_exp2f(v * fmaf(v * v, -0.10294324f, -2.3022082f));
   return v * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
+// GELU by its definition, v * Phi(v), Phi the standard normal distribution
+// function.  With x = |v| / sqrt(2): Phi(-|v|) = erfc(x) / 2, and erfc(x) =
+// t (a1 + t (a2 + t (a3 + t (a4 + t a5)))) exp(-x^2), t = 1 / (1 + p x), to
+// 1.5e-7 absolute (the rational approximation 7.1.26 of Abramowitz and Stegun's
+// handbook; the halves are folded into the coefficients, p / sqrt(2) into the
+// t).  One exp2, one reciprocal and about a dozen other operations per value;
+// the error is far below the fp16 rounding of the result.
+__device__ __forceinline__ float gelu_erf(float v) {
+  const float t = __builtin_amdgcn_rcpf(fmaf(fabsf(v), 0.23164189f, 1.0f));
+  const float e = __builtin_amdgcn_exp2f(v * v * -0.72134752f);  // exp(-v^2 / 2)
+  float q = fmaf(t, 0.5307027145f, -0.7265760135f);
+  q = fmaf(t, q, 0.7107068705f);
+  q = fmaf(t, q, -0.142248368f);
+  q = fmaf(t, q, 0.127414796f);
+  q = q * t * e;  // Phi(-|v|)
+  return v * (v < 0.f ? q : 1.0f - q);
+}
+
+template <int ACT>
+__device__ __forceinline__ float mlp_activation(float v) {
+  return ACT == 0 ? gelu_erf(v) : gelu_tanh(v);
+}
+
 // what the lanes of a chunk read for the tokens its segment does not have
 __device__ __align__(256) _Float16 g_zero_row[128];
 
-template <int D, int HID, int NT>
+template <int D, int HID, int NT, int ACT>
 __global__ __launch_bounds__(mlp_threads(NT), 1) void mlp_compress_kernel(BatchParams p,
                                                                       MlpParams mp) {
   constexpr int MT1 = HID / 32;               // 32-row tiles of hidden units
@@ -378,7 +400,7 @@ __global__ __launch_bounds__(mlp_threads(NT), 1) void mlp_compress_kernel(BatchP
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
             const int u = mlp_hidden_unit(sl, kh, e);  // = 32mt + 16half + 8(e/4) + 4kh + e%4
-            hb[sl][nt][e] = (_Float16)gelu_tanh(acc[mt][nt][8 * half + e] + sm_b1[u]);
+            hb[sl][nt][e] = (_Float16)mlp_activation<ACT>(acc[mt][nt][8 * half + e] + sm_b1[u]);
           }
       }
     };
@@ -470,9 +492,14 @@ constexpr int mlp_nt() { return (D / 64) * (HID / 32) * 64 >= 512 ? 1 : 2; }
 template <int D, int HID>
 static hipError_t mlp_setup_one() {
   constexpr int NT = mlp_nt<D, HID>();
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_compress_kernel<D, HID, NT>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                             (int)mlp_lds_bytes<D, HID, NT>());
+  hipError_t e = hipFuncSetAttribute(
+      reinterpret_cast<const void*>(mlp_compress_kernel<D, HID, NT, 0>),
+      hipFuncAttributeMaxDynamicSharedMemorySize, (int)mlp_lds_bytes<D, HID, NT>());
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_compress_kernel<D, HID, NT, 1>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)mlp_lds_bytes<D, HID, NT>());
+  return e;
 }
 
 hipError_t mlp_one_time_setup() {
@@ -486,8 +513,13 @@ hipError_t mlp_one_time_setup() {
 template <int D, int HID>
 static hipError_t mlp_launch_one(const BatchParams& p, const MlpParams& mp, hipStream_t s) {
   constexpr int NT = mlp_nt<D, HID>();
-  mlp_compress_kernel<D, HID, NT><<<std::min(mp.n_tiles, mp.max_grid), mlp_threads(NT),
-                                    mlp_lds_bytes<D, HID, NT>(), s>>>(p, mp);
+  const unsigned grid = (unsigned)std::min(mp.n_tiles, mp.max_grid);
+  if (mp.activation == 0)
+    mlp_compress_kernel<D, HID, NT, 0><<<grid, mlp_threads(NT), mlp_lds_bytes<D, HID, NT>(), s>>>(
+        p, mp);
+  else
+    mlp_compress_kernel<D, HID, NT, 1><<<grid, mlp_threads(NT), mlp_lds_bytes<D, HID, NT>(), s>>>(
+        p, mp);
   return hipGetLastError();
 }
 

@@ -15,9 +15,10 @@ FC_OK, FC_EINVAL, FC_ENOMEM, FC_EDEVICE = 0, -1, -2, -3
 FC_METHOD_NONE, FC_METHOD_SNAPKV, FC_METHOD_KNORM, FC_METHOD_STREAMING = 0, 1, 2, 3
 FC_DTYPE_F16 = 0
 FC_BLOCK_SIZE = 16
-FC_N_KERNELS = 11
+FC_N_KERNELS = 12
 FC_SCORE_AUTO, FC_SCORE_TWO_PASS, FC_SCORE_ONE_PASS = 0, 1, 2
 FC_COMPACT_FRESH, FC_COMPACT_IN_PLACE = 0, 1
+FC_ACT_GELU_ERF, FC_ACT_GELU_TANH = 0, 1
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libfastcache.so")
 
@@ -28,7 +29,7 @@ EXPORTS = [
     "fc_compress_batch", "fc_compress_batch_var", "fc_compress_batch_lse", "fc_window_lse",
     "fc_append_batch", "fc_decode_attention",
     "fc_decode_attention_kept",
-    "fc_mlp_set_weights", "fc_compress_batch_mlp", "fc_set_compaction_mode", "fc_set_streaming_sinks", "fc_set_score_mode", "fc_set_profiling", "fc_get_kernel_times",
+    "fc_mlp_set_weights", "fc_compress_batch_mlp", "fc_set_compaction_mode", "fc_set_streaming_sinks", "fc_set_score_mode", "fc_set_split_threshold", "fc_set_profiling", "fc_get_kernel_times",
     "fc_kernel_name", "fc_last_error",
     "fc_sched_create", "fc_sched_destroy", "fc_sched_submit", "fc_sched_pending",
     "fc_sched_batch_target", "fc_sched_ready", "fc_sched_form_batch", "fc_sched_adjust",
@@ -37,9 +38,9 @@ EXPORTS = [
 _lib = None
 
 
-class McpWeights(ctypes.Structure):
+class MlpWeights(ctypes.Structure):
     """struct fc_mlp_weights"""
-    _fields_ = [("k", ctypes.c_int), ("hidden", ctypes.c_int),
+    _fields_ = [("k", ctypes.c_int), ("hidden", ctypes.c_int), ("activation", ctypes.c_int),
                 ("w1", ctypes.c_void_p * 2), ("b1", ctypes.c_void_p * 2),
                 ("w2", ctypes.c_void_p * 2), ("b2", ctypes.c_void_p * 2)]
 
@@ -94,9 +95,10 @@ def load_library():
     lib.fc_decode_attention.argtypes = [vp, vp, i, i32p, vp, vp, i, ctypes.c_float, vp]
     lib.fc_decode_attention_kept.argtypes = [vp, vp, i, i32p, i32p, vp, vp, vp, i, ctypes.c_float,
                                              vp]
-    lib.fc_mlp_set_weights.argtypes = [vp, ctypes.POINTER(McpWeights), vp]
+    lib.fc_mlp_set_weights.argtypes = [vp, ctypes.POINTER(MlpWeights), vp]
     lib.fc_compress_batch_mlp.argtypes = [vp, vp, i, i32p, i32p, i32p, i32p, i, vp]
     lib.fc_set_score_mode.argtypes = [vp, i]
+    lib.fc_set_split_threshold.argtypes = [vp, i]
     lib.fc_set_streaming_sinks.argtypes = [vp, i]
     lib.fc_set_compaction_mode.argtypes = [vp, i]
     lib.fc_set_profiling.argtypes = [vp, i]
@@ -420,9 +422,10 @@ def fc_decode_attention_kept(pool, block_tables, seq_lens, budget, kept, q, out=
     return out
 
 
-def fc_mlp_set_weights(pool, k, w1, b1, w2, b2, stream=None):
+def fc_mlp_set_weights(pool, k, w1, b1, w2, b2, activation=FC_ACT_GELU_ERF, stream=None):
     """w1, b1, w2, b2: pairs (text, image) of device tensors: w1 fp16
-    [hidden][k*head_dim], b1 fp32 [hidden], w2 fp16 [head_dim][hidden], b2 fp32 [head_dim]."""
+    [hidden][k*head_dim], b1 fp32 [hidden], w2 fp16 [head_dim][hidden], b2 fp32 [head_dim];
+    activation: FC_ACT_GELU_ERF or FC_ACT_GELU_TANH."""
     import torch
     lib = load_library()
     hidden = int(w1[0].shape[0])
@@ -431,8 +434,8 @@ def fc_mlp_set_weights(pool, k, w1, b1, w2, b2, stream=None):
                 tuple(w2[m].shape) != (pool.head_dim, hidden) or \
                 tuple(b1[m].shape) != (hidden,) or tuple(b2[m].shape) != (pool.head_dim,):
             raise ValueError("weight shapes do not match k, hidden and head_dim")
-    w = McpWeights()
-    w.k, w.hidden = int(k), hidden
+    w = MlpWeights()
+    w.k, w.hidden, w.activation = int(k), hidden, int(activation)
     for m in range(2):
         w.w1[m] = _dev_ptr(w1[m], torch.float16).value
         w.b1[m] = _dev_ptr(b1[m], torch.float32).value
@@ -465,6 +468,10 @@ def fc_set_streaming_sinks(pool, n_sink):
 
 def fc_set_score_mode(pool, mode):
     _check(load_library().fc_set_score_mode(pool.ptr, int(mode)))
+
+
+def fc_set_split_threshold(pool, min_tokens):
+    _check(load_library().fc_set_split_threshold(pool.ptr, int(min_tokens)))
 
 
 def fc_set_profiling(pool, enable):

@@ -11,7 +11,6 @@ from oracle import fastcache_oracle as fo
 from paper_2503_08461_amd import synth
 from parity_util import mlp_error_bound
 
-MLP_ACTIVATION = "gelu_tanh"   # what the kernel computes
 
 pytestmark = pytest.mark.gpu
 
@@ -125,7 +124,8 @@ def test_fullsize_batch(config, n_samples, lse):
         dw.close()
 
 
-def test_fullsize_chunk_mlp_config4():
+@pytest.mark.parametrize("MLP_ACTIVATION", ["gelu_erf", "gelu_tanh"])
+def test_fullsize_chunk_mlp_config4(MLP_ACTIVATION):
     """The chunk-MLP compressor on the config-4 batch exactly as bench.py runs
     it (k = 5, hidden 256, image span = all but the first and last 64 tokens):
     pool state bit-exact with the oracle's bookkeeping, sampled (request, layer,
@@ -149,7 +149,9 @@ def test_fullsize_chunk_mlp_config4():
               for _ in range(2)]
         b1 = [0.1 * torch.randn(hidden, generator=gen, device=dw.dev) for _ in range(2)]
         b2 = [0.1 * torch.randn(d, generator=gen, device=dw.dev) for _ in range(2)]
-        fc.fc_mlp_set_weights(dw.pool, k, w1, b1, w2, b2)
+        fc.fc_mlp_set_weights(dw.pool, k, w1, b1, w2, b2,
+                              {"gelu_erf": fc.FC_ACT_GELU_ERF,
+                               "gelu_tanh": fc.FC_ACT_GELU_TANH}[MLP_ACTIVATION])
         img_b = np.full(wl.n_req, 64, dtype=np.int32)
         img_e = (wl.seq_lens - 64).astype(np.int32)
         fc.fc_compress_batch_mlp(dw.pool, dw.bt, dw.lens, img_b, img_e)

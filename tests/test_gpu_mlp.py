@@ -24,7 +24,7 @@ def make_weights(d, k, hidden, seed):
 
 
 def run_case(lens, img_b, img_e, enable, d, k, hidden, n_layers=1, n_heads=2, seed=0,
-             activation="gelu_tanh"):
+             activation="gelu_erf", row_scale=1.0):
     import torch
     from paper_2503_08461_amd import fastcache as fc
     lens = np.array(lens, dtype=np.int32)
@@ -32,6 +32,8 @@ def run_case(lens, img_b, img_e, enable, d, k, hidden, n_layers=1, n_heads=2, se
     wl = synth.Workload("mlp", n_layers, n_heads, d, nb, 16, 7, lens, np.zeros(len(lens), np.int32),
                         np.ones(len(lens), np.int32), seed, False, True)
     kv_host = synth.fill_pool_host(wl)
+    if row_scale != 1.0:
+        kv_host = (kv_host.astype(np.float32) * row_scale).astype(np.float16)
     w = make_weights(d, k, hidden, seed + 1)
     dev = torch.device("cuda:0")
     kv_dev = torch.from_numpy(kv_host.copy()).to(dev)
@@ -49,7 +51,8 @@ def run_case(lens, img_b, img_e, enable, d, k, hidden, n_layers=1, n_heads=2, se
             bt_o[r, :rows_o[r].shape[0]] = rows_o[r]
             bt_g[r, :rows_g[r].shape[0]] = rows_g[r]
         tw = {key: [torch.from_numpy(a).to(dev) for a in w[key]] for key in w}
-        fc.fc_mlp_set_weights(pool, k, tw["w1"], tw["b1"], tw["w2"], tw["b2"])
+        fc.fc_mlp_set_weights(pool, k, tw["w1"], tw["b1"], tw["w2"], tw["b2"],
+                              {"gelu_erf": fc.FC_ACT_GELU_ERF, "gelu_tanh": fc.FC_ACT_GELU_TANH}[activation])
         img_b = np.array(img_b, dtype=np.int32)
         img_e = np.array(img_e, dtype=np.int32)
         en = np.array(enable, dtype=np.int32)
@@ -96,16 +99,27 @@ def run_case(lens, img_b, img_e, enable, d, k, hidden, n_layers=1, n_heads=2, se
         fc.fc_pool_destroy(pool)
 
 
-def test_single_image_request_k5():
+@pytest.mark.parametrize("activation", ["gelu_erf", "gelu_tanh"])
+def test_single_image_request_k5(activation):
     # LLaVA-like: 35 text, 576 image, 29 text tokens; k = 5 -> 7 + 116 + 6 rows
-    run_case([640], [35], [611], [1], d=128, k=5, hidden=256)
+    run_case([640], [35], [611], [1], d=128, k=5, hidden=256, activation=activation)
 
 
+@pytest.mark.parametrize("activation", ["gelu_erf", "gelu_tanh"])
 @pytest.mark.parametrize("d,hidden,k", [(128, 256, 5), (128, 128, 4), (64, 256, 8), (64, 128, 1),
                                         (128, 256, 3)])
-def test_shapes_and_factors(d, hidden, k):
+def test_shapes_and_factors(d, hidden, k, activation):
     run_case([333, 77, 1200], [10, 0, 1200], [300, 77, 1200], [1, 1, 1], d=d, k=k, hidden=hidden,
-             n_layers=2, n_heads=3, seed=5)
+             n_layers=2, n_heads=3, seed=5, activation=activation)
+
+
+def test_large_pre_activations_both_signs():
+    """Rows scaled so that the pre-activations reach far into both tails of the
+    activation (|v| up to about 12), where the erf form is v * (a tiny number)
+    on one side and v itself on the other."""
+    for activation in ("gelu_erf", "gelu_tanh"):
+        run_case([200], [20], [180], [1], d=64, k=4, hidden=128, seed=21, activation=activation,
+                 row_scale=6.0)
 
 
 def test_pass_through_and_degenerate_spans():
@@ -129,6 +143,9 @@ def test_errors_leave_everything_untouched():
         assert ei.value.code == fc.FC_EINVAL
         w = make_weights(64, 2, 128, 0)
         tw = {key: [torch.from_numpy(a).cuda() for a in w[key]] for key in w}
+        with pytest.raises(fc.FastCacheError) as ei:          # unknown activation
+            fc.fc_mlp_set_weights(pool, 2, tw["w1"], tw["b1"], tw["w2"], tw["b2"], activation=7)
+        assert ei.value.code == fc.FC_EINVAL
         fc.fc_mlp_set_weights(pool, 2, tw["w1"], tw["b1"], tw["w2"], tw["b2"])
         with pytest.raises(fc.FastCacheError) as ei:          # 50 rows need 4 blocks, 1 free
             fc.fc_compress_batch_mlp(pool, bt, lens, zero, full)
