@@ -10,8 +10,17 @@
  * by block tables, i.e. by reference ("zero-copy mechanism", System
  * Implementation section); the only data movement is the compaction copy.
  *
- * Every function returns FC_OK (0) or a negative error code.  On any error
- * the pool, its free list and all caller buffers are left unchanged.
+ * Every function returns FC_OK (0) or a negative error code.  FC_EINVAL and
+ * FC_ENOMEM are raised before anything is queued: the pool, its free list and
+ * all caller buffers are left unchanged.  FC_EDEVICE (a HIP call failed) is
+ * different: if it comes from a launch in the middle of a stage, part of the
+ * stage's device work is already queued while the host mirrors (free count,
+ * lengths) were not advanced; the pool is then marked unusable, every later
+ * call on it returns FC_EDEVICE, and the caller has to destroy it and rebuild
+ * its block tables.  The library's scratch buffers (kept lists, saved ids,
+ * un-pooled scores, descriptors) grow on demand: a call that needs more than
+ * any earlier one waits for the device, frees and reallocates BEFORE it queues
+ * anything; calls whose needs were met before are fully asynchronous.
  * "dev" pointers are device (HBM) addresses, "host" pointers are ordinary
  * host memory.  All device work is issued on the hipStream_t passed as
  * `stream` (NULL = the default stream) and is asynchronous with respect to

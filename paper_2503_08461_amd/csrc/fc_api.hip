@@ -6,6 +6,7 @@
 
 #include "../../include/fastcache.h"
 #include "fc_internal.h"
+#include "fc_plan.h"
 
 #include <math.h>
 #include <stdarg.h>
@@ -42,11 +43,18 @@ const char* const kKernelNames[K_COUNT] = {"plan_alloc", "snapkv_score", "knorm_
                                            "fused_unit", "mlp_compress", "append",
                                            "decode_attention", "window_lse", "select_gather"};
 
-// Team sizes of the token-split score kernel when a batch has more distinct
-// ones than launches are worth: a head takes the next size of this ladder.
-const int kTeamLadder[] = {1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 14, 16, 20, 24, 28, 32, 40, 48, 56, 64};
-constexpr int kSplitMaxTeam = 64;
-constexpr int kSplitMaxClasses = 12;
+// the planning module restates the public constants; they must agree
+static_assert(PLAN_OK == FC_OK && PLAN_EINVAL == FC_EINVAL && PLAN_ENOMEM == FC_ENOMEM, "codes");
+static_assert(PLAN_METHOD_SNAPKV == FC_METHOD_SNAPKV && PLAN_METHOD_KNORM == FC_METHOD_KNORM &&
+              PLAN_METHOD_STREAMING == FC_METHOD_STREAMING && PLAN_METHOD_NONE == FC_METHOD_NONE,
+              "methods");
+static_assert(PLAN_SCORE_AUTO == FC_SCORE_AUTO && PLAN_SCORE_TWO_PASS == FC_SCORE_TWO_PASS &&
+              PLAN_SCORE_ONE_PASS == FC_SCORE_ONE_PASS, "score modes");
+static_assert(kPlanBlockSize == FC_BLOCK_SIZE && kPlanMaxWindow == FC_MAX_WINDOW &&
+              kPlanMaxSeqLen == FC_MAX_SEQ_LEN && kPlanMaxPoolKernel == FC_MAX_POOL_KERNEL &&
+              kPlanFusedMaxLen == kFusedMaxLen && kPlanClasses == FC_MAX_WINDOW / 16 + 1,
+              "limits");
+
 
 size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -60,6 +68,10 @@ struct fc_pool {
   int n_blocks = 0, n_layers = 0, n_heads = 0, head_dim = 0;
   int32_t* stack = nullptr;  // device
   int top = 0;               // host mirror, exact
+  bool poisoned = false;     // a launch failed in the middle of a stage: device and host disagree
+  // ownership checks (debug mode): one int per block, 0 free, 1 handed out, 2 being released
+  bool debug_checks = false;
+  int32_t* owner = nullptr;
 
   // scratch, grown on demand
   float* raw_scores = nullptr;
@@ -182,6 +194,7 @@ int fc_pool_destroy(fc_pool* p) {
   if (!p) return FC_OK;
   (void)hipDeviceSynchronize();
   if (p->stack) (void)hipFree(p->stack);
+  if (p->owner) (void)hipFree(p->owner);
   if (p->raw_scores) (void)hipFree(p->raw_scores);
   if (p->kept) (void)hipFree(p->kept);
   if (p->ids) (void)hipFree(p->ids);
@@ -315,268 +328,140 @@ int fc_pool_import_state_dev(fc_pool* p, const int32_t* dev_stack, int top, void
   return FC_OK;
 }
 
-// Both entry points of the pruning stage.  host_window / host_pool_kernel are
-// NULL for the call that takes one size for the whole batch.
-static int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_req,
-                               int32_t* host_seq_lens, const void* dev_q_window,
-                               const float* dev_lse_window, bool need_lse,
-                               const int32_t* host_window, int window,
-                               const int32_t* host_method, const int32_t* host_budget, int n_req,
-                               const int32_t* host_pool_kernel, int pool_kernel, float scale,
-                               float* dev_scores_out, int32_t* dev_kept_out, void* stream_) {
-  hipStream_t stream = static_cast<hipStream_t>(stream_);
-  if (!p) return fail(FC_EINVAL, "pool is NULL");
-  if (n_req < 0) return fail(FC_EINVAL, "n_req < 0");
-  if (n_req == 0) return FC_OK;
-  if (!dev_block_tables || !host_seq_lens || !host_method || !host_budget)
-    return fail(FC_EINVAL, "NULL argument");
-  if (max_blocks_per_req < 1) return fail(FC_EINVAL, "max_blocks_per_req < 1");
-  const bool per_request = host_window != nullptr;
-  if (per_request && !host_pool_kernel) return fail(FC_EINVAL, "NULL argument");
-  if (!per_request &&
-      (pool_kernel < 1 || pool_kernel > FC_MAX_POOL_KERNEL || (pool_kernel & 1) == 0))
-    return fail(FC_EINVAL, "pool_kernel must be odd and in 1..%d", FC_MAX_POOL_KERNEL);
+}  // extern "C"
 
-  // ---- validate with host-known quantities; nothing is touched on error ----
-  const size_t n_lh = (size_t)p->n_layers * p->n_heads;
-  std::vector<ReqDesc> descs;
-  descs.reserve(n_req);
-  const bool in_place = p->compact_mode == FC_COMPACT_IN_PLACE;
-  int total_new = 0, total_old = 0, total_released = 0, max_len = 0;
-  size_t score_off = 0, kept_off = 0, q_off = 0;
-  int window_hi = 0;  // over the SnapKV requests
-  for (int r = 0; r < n_req; ++r) {
-    const int m = host_method[r];
-    // queries are packed: with per-request windows only SnapKV requests have any
-    const size_t q_here = q_off;
-    if (per_request) {
-      if (m == FC_METHOD_SNAPKV) q_off += n_lh * (size_t)std::max(host_window[r], 0) * p->head_dim;
-    } else {
-      q_off += n_lh * (size_t)std::max(window, 0) * p->head_dim;
-    }
-    if (m == FC_METHOD_NONE) continue;
-    const int L = host_seq_lens[r], B = host_budget[r];
-    const int win = per_request ? host_window[r] : window;
-    const int pk = per_request ? host_pool_kernel[r] : pool_kernel;
-    if (m != FC_METHOD_SNAPKV && m != FC_METHOD_KNORM && m != FC_METHOD_STREAMING)
-      return fail(FC_EINVAL, "request %d: unknown method %d", r, m);
-    if (L < 1 || L > FC_MAX_SEQ_LEN)
-      return fail(FC_EINVAL, "request %d: length %d outside 1..%d", r, L, FC_MAX_SEQ_LEN);
-    if (B < 1 || B > L) return fail(FC_EINVAL, "request %d: budget %d outside 1..%d", r, B, L);
-    if (m == FC_METHOD_SNAPKV) {
-      if (win < 1 || win > FC_MAX_WINDOW)
-        return fail(FC_EINVAL, "request %d: window %d outside 1..%d", r, win, FC_MAX_WINDOW);
-      if (pk < 1 || pk > FC_MAX_POOL_KERNEL || (pk & 1) == 0)
-        return fail(FC_EINVAL, "request %d: pool_kernel must be odd and in 1..%d", r,
-                    FC_MAX_POOL_KERNEL);
-      if (L < win || B < win)
-        return fail(FC_EINVAL, "request %d: SnapKV needs length and budget >= window", r);
-      if (!dev_q_window || (reinterpret_cast<uintptr_t>(dev_q_window) & 15))
-        return fail(FC_EINVAL, "dev_q_window must be a 16-byte aligned device pointer");
-      if (need_lse && (!dev_lse_window || (reinterpret_cast<uintptr_t>(dev_lse_window) & 3)))
-        return fail(FC_EINVAL, "dev_lse_window must be a 4-byte aligned device pointer");
-      if (need_lse && p->score_mode == FC_SCORE_ONE_PASS)
-        return fail(FC_EINVAL, "the one-pass scheduling takes no log-sum-exp input");
-      window_hi = std::max(window_hi, win);
-    }
-    ReqDesc d = {};
-    d.window = m == FC_METHOD_SNAPKV ? win : 0;
-    d.pool_kernel = m == FC_METHOD_SNAPKV ? pk : 1;
-    d.seq_len = L;
-    d.budget = B;
-    d.method = m;
-    d.table_row = r;
-    d.n_old = (L + FC_BLOCK_SIZE - 1) / FC_BLOCK_SIZE;
-    d.n_new = (B + FC_BLOCK_SIZE - 1) / FC_BLOCK_SIZE;
-    if (d.n_old > max_blocks_per_req)
-      return fail(FC_EINVAL, "request %d: %d blocks exceed max_blocks_per_req %d", r, d.n_old,
-                  max_blocks_per_req);
-    d.old_off = total_old;
-    d.new_off = in_place ? total_released : total_new;
-    d.score_off = (int64_t)score_off;
-    d.raw_off = 0;
-    d.kept_off = (int64_t)kept_off;
-    d.q_off = (int64_t)q_here;
-    total_old += d.n_old;
-    total_new += in_place ? 0 : d.n_new;
-    total_released += d.n_old - d.n_new;
-    score_off += n_lh * (size_t)L;
-    kept_off += n_lh * (size_t)B;
-    max_len = std::max(max_len, L);
-    descs.push_back(d);
-  }
-  const int n_comp = (int)descs.size();
-  if (n_comp == 0) return FC_OK;
-  if (total_new > p->top)
-    return fail(FC_ENOMEM, "batch needs %d new blocks, %d free", total_new, p->top);
+namespace {
 
-  // ---- token-split one-pass SnapKV scoring: which requests, which team sizes ----
-  // A request takes it if the scheduling asks for it (FC_SCORE_ONE_PASS: every
-  // SnapKV request; FC_SCORE_AUTO: those of at least split_min_len tokens, if set), the
-  // device can hold the kernel's grid co-resident and the head fits a team.
-  int rc;
-  bool any_snap = false;
-  for (const ReqDesc& d : descs) any_snap |= d.method == FC_METHOD_SNAPKV;
-  std::vector<int> split_team(n_comp, 0);  // 0: not split
-  int n_split_req = 0;
-  if (any_snap && !need_lse && p->score_mode != FC_SCORE_TWO_PASS) {
-    const int cap = split_blocks_per_workgroup();
-    for (int i = 0; i < n_comp; ++i) {
-      const ReqDesc& d = descs[i];
-      if (d.method != FC_METHOD_SNAPKV) continue;
-      if (p->score_mode == FC_SCORE_AUTO && (p->split_min_len == 0 || d.seq_len < p->split_min_len))
-        continue;
-      const int nt = (d.window + 15) / 16;
+PoolView pool_view(fc_pool* p, bool want_split) {
+  PoolView v;
+  v.n_layers = p->n_layers;
+  v.n_heads = p->n_heads;
+  v.head_dim = p->head_dim;
+  v.n_free = p->top;
+  v.score_mode = p->score_mode;
+  v.in_place = p->compact_mode == FC_COMPACT_IN_PLACE;
+  v.split_min_len = p->split_min_len;
+  v.split_cap_blocks = split_blocks_per_workgroup();
+  if (want_split) {
+    // the co-resident grid of the token-split score kernel, asked once per query-tile count
+    for (int nt = 1; nt <= FC_MAX_WINDOW / 16; ++nt) {
       if (p->split_grid[nt] == 0) {
-        const int gsz = split_grid_size(p->head_dim, d.window);
+        const int gsz = split_grid_size(p->head_dim, 16 * nt);
         p->split_grid[nt] = gsz > 0 ? gsz : -1;
       }
-      const int g = (d.n_old + cap - 1) / cap;
-      if (p->split_grid[nt] > 0 && g <= kSplitMaxTeam && g <= p->split_grid[nt]) {
-        split_team[i] = g;
-        ++n_split_req;
-      } else if (p->score_mode == FC_SCORE_ONE_PASS) {
-        return fail(FC_EINVAL, "request %d: one-pass scoring is not possible on this device "
-                    "(no co-resident grid, or more than %d tokens)", d.table_row,
-                    kSplitMaxTeam * cap * FC_BLOCK_SIZE);
-      }
+      v.split_grid[nt] = p->split_grid[nt];
     }
-    // few launches: with many distinct team sizes, round them up along the ladder
-    std::vector<int> sizes;
-    for (int g : split_team)
-      if (g > 0) sizes.push_back(g);
-    std::sort(sizes.begin(), sizes.end());
-    sizes.erase(std::unique(sizes.begin(), sizes.end()), sizes.end());
-    if ((int)sizes.size() > kSplitMaxClasses)
-      for (int& g : split_team)
-        if (g > 0) g = *std::lower_bound(std::begin(kTeamLadder), std::end(kTeamLadder), g);
   }
-  if (n_split_req > 0) {
-    int grid_max = 0;
-    for (int g : p->split_grid) grid_max = std::max(grid_max, g);
-    if ((rc = grow(&p->split_xchg, &p->split_xchg_cap, (size_t)2 * grid_max * 64)) != FC_OK)
-      return rc;
-  }
+  return v;
+}
 
-  // ---- scratch and descriptors --------------------------------------------
-  if (!dev_kept_out && (rc = grow(&p->kept, &p->kept_cap, kept_off)) != FC_OK) return rc;
-  if ((rc = grow(&p->ids, &p->ids_cap, (size_t)total_old + total_new)) != FC_OK) return rc;
-  const size_t desc_bytes = round_up((size_t)n_comp * sizeof(ReqDesc), 16);
-  const size_t order_bytes = round_up((size_t)n_comp * sizeof(int32_t), 16);
-  // Work lists (descriptor indices, heaviest first so that the tail of each
-  // launch is made of light units).  Heads short enough for the fused kernel
-  // (score -> select -> gather in one workgroup) are listed per window class
-  // (class c: SnapKV with ceil(window/16) == c, which is the number of 16-row
-  // query tiles the kernel is compiled for; class 0: no queries at all); the
-  // rest go through the separate kernels: SnapKV per class, key-norm, and one
-  // list of all of them for select and gather.
-  enum { kClasses = 5 };
-  enum { LIST_FUSED = 0, LIST_SNAP = kClasses, LIST_KNORM = 2 * kClasses, LIST_ALL, LIST_SPLIT,
-         N_LISTS };
-  const size_t meta_bytes = desc_bytes + N_LISTS * order_bytes;
-  if ((rc = grow_meta(p, meta_bytes)) != FC_OK) return rc;
+// The calls of a launch sequence change the pool on the device step by step;
+// if one of them fails after the first has been queued, the device state and
+// the host mirrors no longer agree.  The pool is then marked and every later
+// call on it is refused.
+#define FC_HIP_STAGE(pool, call)                                                    \
+  do {                                                                              \
+    hipError_t e_ = (call);                                                         \
+    if (e_ != hipSuccess) {                                                         \
+      (pool)->poisoned = true;                                                      \
+      return fail(FC_EDEVICE, "%s failed: %s; the pool is now unusable", #call,     \
+                  hipGetErrorString(e_));                                           \
+    }                                                                               \
+  } while (0)
+
+#define FC_CHECK_POOL(pool)                                                         \
+  do {                                                                              \
+    if (!(pool)) return fail(FC_EINVAL, "pool is NULL");                            \
+    if ((pool)->poisoned)                                                           \
+      return fail(FC_EDEVICE, "a device error in an earlier call left this pool in an " \
+                              "undefined state; destroy it");                       \
+  } while (0)
+
+// Descriptors and work lists to the device, through the pinned staging buffer
+// and one asynchronous copy.
+int upload_meta(fc_pool* p, const char* image, size_t bytes, char* dev_dst, hipStream_t stream) {
   if (p->meta_pending) {
     // the previous call's descriptor upload must have left the staging buffer
     FC_HIP(hipEventSynchronize(p->meta_event));
     p->meta_pending = false;
   }
-  memcpy(p->host_meta, descs.data(), (size_t)n_comp * sizeof(ReqDesc));
-  int32_t* lists[N_LISTS];
-  size_t list_off[N_LISTS];
-  int n_list[N_LISTS] = {};
-  int max_len_list[N_LISTS] = {};
-  for (int i = 0; i < N_LISTS; ++i) {
-    list_off[i] = desc_bytes + (size_t)i * order_bytes;
-    lists[i] = reinterpret_cast<int32_t*>(p->host_meta + list_off[i]);
-  }
-  std::vector<int> sorted(n_comp);
-  std::iota(sorted.begin(), sorted.end(), 0);
-  // heaviest first: bytes a unit moves (K once or twice, kept K/V read and written)
-  auto weight = [&](int i) {
-    const ReqDesc& d = descs[i];
-    const int passes = d.method == FC_METHOD_SNAPKV ? (need_lse ? 1 : 2)
-                                                    : d.method == FC_METHOD_KNORM ? 1 : 0;
-    return (int64_t)d.seq_len * passes + (int64_t)d.budget * 4;
-  };
-  std::stable_sort(sorted.begin(), sorted.end(),
-                   [&](int a, int b) { return weight(a) > weight(b); });
-  const bool allow_fused = p->score_mode == FC_SCORE_AUTO;
-  auto fused = [&](int i) {
-    const ReqDesc& d = descs[i];
-    // (streaming: no score, no LDS, so the fused kernel whatever the length)
-    return d.method == FC_METHOD_STREAMING ||
-           (allow_fused && split_team[i] == 0 && d.seq_len <= kFusedMaxLen);
-  };
-  // Units without queries (key-norm, streaming) ride in the launch of the
-  // SnapKV class that has the most fused units, if there is one: one launch
-  // fills the chip better than two that each end in a tail.
-  int home_class = 0;
-  {
-    int count[kClasses] = {};
-    for (int i = 0; i < n_comp; ++i)
-      if (descs[i].method == FC_METHOD_SNAPKV && fused(i)) ++count[(descs[i].window + 15) / 16];
-    for (int c = 1; c < kClasses; ++c)
-      if (count[c] > count[home_class]) home_class = c;
-  }
-  size_t raw_need = 0;
-  for (int di : sorted) {
-    const ReqDesc& d = descs[di];
-    const bool snap = d.method == FC_METHOD_SNAPKV;
-    const int cls = snap ? (d.window + 15) / 16 : 0;
-    int li;
-    if (fused(di)) {
-      li = LIST_FUSED + (snap ? cls : home_class);
-    } else if (split_team[di] > 0) {
-      // scores through the scratch; listed below, grouped by launch
-      reinterpret_cast<ReqDesc*>(p->host_meta)[di].raw_off = (int64_t)raw_need;
-      raw_need += n_lh * (size_t)d.seq_len;
-      max_len_list[LIST_SPLIT] = std::max(max_len_list[LIST_SPLIT], d.seq_len);
-      continue;
-    } else {
-      // scores of these units travel through the library's scratch
-      reinterpret_cast<ReqDesc*>(p->host_meta)[di].raw_off = (int64_t)raw_need;
-      raw_need += n_lh * (size_t)d.seq_len;
-      li = snap ? LIST_SNAP + cls : LIST_KNORM;
-      lists[LIST_ALL][n_list[LIST_ALL]++] = di;
-      max_len_list[LIST_ALL] = std::max(max_len_list[LIST_ALL], d.seq_len);
-    }
-    lists[li][n_list[li]++] = di;
-    // (sizes the score buffer in LDS, which streaming units do not use)
-    if (d.method != FC_METHOD_STREAMING) max_len_list[li] = std::max(max_len_list[li], d.seq_len);
-  }
-  // token-split launches: one per (team size, query-tile count), requests of a
-  // launch contiguous in LIST_SPLIT, heaviest first inside it
-  struct SplitLaunch {
-    int team, nt, first, count;
-  };
-  std::vector<SplitLaunch> split_launches;
-  if (n_split_req > 0) {
-    std::vector<int> idx;
-    for (int di : sorted)
-      if (split_team[di] > 0) idx.push_back(di);
-    auto key = [&](int i) { return split_team[i] * 8 + (descs[i].window + 15) / 16; };
-    std::stable_sort(idx.begin(), idx.end(), [&](int a, int b) { return key(a) > key(b); });
-    for (int di : idx) {
-      const int nt = (descs[di].window + 15) / 16;
-      if (split_launches.empty() || split_launches.back().team != split_team[di] ||
-          split_launches.back().nt != nt)
-        split_launches.push_back({split_team[di], nt, n_list[LIST_SPLIT], 0});
-      ++split_launches.back().count;
-      lists[LIST_SPLIT][n_list[LIST_SPLIT]++] = di;
-    }
-  }
-  int ns = 0, n_fused = 0;
-  for (int c = 0; c < kClasses; ++c) {
-    ns += n_list[LIST_SNAP + c];
-    n_fused += n_list[LIST_FUSED + c];
-  }
-  const int nk = n_list[LIST_KNORM];
-  if ((rc = grow(&p->raw_scores, &p->raw_cap, raw_need)) != FC_OK) return rc;
-  FC_HIP(hipMemcpyAsync(p->dev_meta, p->host_meta, meta_bytes, hipMemcpyHostToDevice, stream));
+  memcpy(p->host_meta, image, bytes);
+  FC_HIP(hipMemcpyAsync(dev_dst, p->host_meta, bytes, hipMemcpyHostToDevice, stream));
   FC_HIP(hipEventRecord(p->meta_event, stream));
   p->meta_pending = true;
+  return FC_OK;
+}
 
-  BatchParams bp;
+// All entry points of the pruning stage.  host_window / host_pool_kernel are
+// NULL for the calls that take one size for the whole batch.
+int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_req,
+                        int32_t* host_seq_lens, const void* dev_q_window,
+                        const float* dev_lse_window, bool need_lse, const int32_t* host_window,
+                        int window, const int32_t* host_method, const int32_t* host_budget,
+                        int n_req, const int32_t* host_pool_kernel, int pool_kernel, float scale,
+                        float* dev_scores_out, int32_t* dev_kept_out, void* stream_) {
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  FC_CHECK_POOL(p);
+  if (n_req > 0 && !dev_block_tables) return fail(FC_EINVAL, "NULL argument");
+
+  // ---- plan with host-known quantities; nothing is touched on error -----------
+  CompressArgs a;
+  a.n_req = n_req;
+  a.max_blocks = max_blocks_per_req;
+  a.seq_lens = host_seq_lens;
+  a.method = host_method;
+  a.budget = host_budget;
+  a.window_per_req = host_window;
+  a.pool_kernel_per_req = host_pool_kernel;
+  a.window = window;
+  a.pool_kernel = pool_kernel;
+  a.need_lse = need_lse;
+  a.q_ok = dev_q_window && (reinterpret_cast<uintptr_t>(dev_q_window) & 15) == 0;
+  a.lse_ok = dev_lse_window && (reinterpret_cast<uintptr_t>(dev_lse_window) & 3) == 0;
+  const bool want_split = !need_lse &&
+                          (p->score_mode == FC_SCORE_ONE_PASS ||
+                           (p->score_mode == FC_SCORE_AUTO && p->split_min_len > 0));
+  const PoolView pv = pool_view(p, want_split);
+  CompressPlan plan;
+  if (plan_compress(pv, a, &plan) != PLAN_OK) return fail(plan.code, "%s", plan.message);
+  const int n_comp = (int)plan.descs.size();
+  if (n_comp == 0) return FC_OK;
+
+  // ---- scratch: kept lists, saved ids, un-pooled scores, descriptors -----------
+  const size_t desc_bytes = round_up((size_t)n_comp * sizeof(ReqDesc), 16);
+  const size_t order_bytes = round_up((size_t)n_comp * sizeof(int32_t), 16);
+  const size_t meta_bytes = desc_bytes + N_LISTS * order_bytes;
+  const size_t n_ids = (size_t)plan.total_old + plan.total_new;
+  int32_t* kept_buf = dev_kept_out;
+  int32_t* ids_buf = nullptr;
+  char* dev_meta = nullptr;
+  int rc;
+  {
+    // (growth waits for the device and frees: it happens before anything is queued)
+    if (!dev_kept_out && (rc = grow(&p->kept, &p->kept_cap, plan.kept_entries)) != FC_OK) return rc;
+    if ((rc = grow(&p->ids, &p->ids_cap, n_ids)) != FC_OK) return rc;
+    if ((rc = grow(&p->raw_scores, &p->raw_cap, plan.raw_floats)) != FC_OK) return rc;
+    if (!plan.split_launches.empty() &&
+        (rc = grow(&p->split_xchg, &p->split_xchg_cap, (size_t)2 * plan.split_grid_max * 64)) != FC_OK)
+      return rc;
+    if ((rc = grow_meta(p, meta_bytes)) != FC_OK) return rc;
+    if (!kept_buf) kept_buf = p->kept;
+    ids_buf = p->ids;
+    dev_meta = p->dev_meta;
+  }
+  std::vector<char> image(meta_bytes, 0);
+  memcpy(image.data(), plan.descs.data(), (size_t)n_comp * sizeof(ReqDesc));
+  size_t list_off[N_LISTS];
+  int n_list[N_LISTS];
+  for (int i = 0; i < N_LISTS; ++i) {
+    list_off[i] = desc_bytes + (size_t)i * order_bytes;
+    n_list[i] = (int)plan.lists[i].size();
+    if (n_list[i] > 0)
+      memcpy(image.data() + list_off[i], plan.lists[i].data(), (size_t)n_list[i] * sizeof(int32_t));
+  }
+  if ((rc = upload_meta(p, image.data(), meta_bytes, dev_meta, stream)) != FC_OK) return rc;
+
+  BatchParams bp = {};
   bp.kv = p->kv;
   bp.n_blocks = p->n_blocks;
   bp.n_layers = p->n_layers;
@@ -584,40 +469,42 @@ static int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_bl
   bp.head_dim = p->head_dim;
   bp.stack = p->stack;
   bp.top_before = p->top;
-  bp.total_new = total_new;
-  bp.total_old = total_old;
-  bp.descs = reinterpret_cast<const ReqDesc*>(p->dev_meta);
-  auto dev_list = [&](int i) { return reinterpret_cast<const int32_t*>(p->dev_meta + list_off[i]); };
+  bp.total_new = plan.total_new;
+  bp.total_old = plan.total_old;
+  bp.descs = reinterpret_cast<const ReqDesc*>(dev_meta);
+  auto dev_list = [&](int i) { return reinterpret_cast<const int32_t*>(dev_meta + list_off[i]); };
   bp.order_all = dev_list(LIST_ALL);
   bp.order_knorm = dev_list(LIST_KNORM);
   bp.n_comp = n_comp;  // plan_alloc / reclaim walk every descriptor
-  bp.n_knorm = nk;
+  bp.n_knorm = n_list[LIST_KNORM];
   bp.n_unfused = n_list[LIST_ALL];
   // per launch: order_snap / n_snap, order_fused / n_fused, window (of the class)
-  bp.order_snap = bp.order_fused = nullptr;
-  bp.n_snap = bp.n_fused = 0;
   bp.order_split = dev_list(LIST_SPLIT);
   bp.n_split = n_list[LIST_SPLIT];
-  bp.split_team = 0;
   bp.split_xchg = p->split_xchg;
   bp.block_tables = dev_block_tables;
   bp.max_blocks = max_blocks_per_req;
-  bp.old_ids = p->ids;
-  bp.new_ids = p->ids + total_old;
+  bp.old_ids = ids_buf;
+  bp.new_ids = ids_buf + plan.total_old;
   bp.q_window = static_cast<const _Float16*>(dev_q_window);
   bp.lse_window = need_lse ? dev_lse_window : nullptr;
-  bp.lse_out = nullptr;
-  bp.window = window_hi;
+  bp.window = plan.window_hi;
   bp.n_sink = p->n_sink;
-  bp.in_place = in_place ? 1 : 0;
+  bp.in_place = pv.in_place ? 1 : 0;
   const float sc = (scale > 0.f) ? scale : 1.0f / sqrtf((float)p->head_dim);
   bp.scale_log2e = sc * 1.44269504088896340736f;
   bp.raw_scores = p->raw_scores;
   bp.scores_out = dev_scores_out;
-  bp.kept = dev_kept_out ? dev_kept_out : p->kept;
+  bp.kept = kept_buf;
   bp.error_flag = p->error_flag;
+  bp.owner = p->debug_checks ? p->owner : nullptr;
 
   // ---- the stage ------------------------------------------------------------
+  int ns = 0, n_fused = 0;
+  for (int c = 0; c < kPlanClasses; ++c) {
+    ns += n_list[LIST_SNAP + c];
+    n_fused += n_list[LIST_FUSED + c];
+  }
   const int ring = p->prof_calls % kProfRing;
   if (p->profiling) {
     for (int k = 0; k < K_COUNT; ++k) p->timed[ring][k] = false;
@@ -634,10 +521,10 @@ static int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_bl
     }
     return e;
   };
-  FC_HIP(run(K_PLAN_ALLOC, true, [&] { return launch_plan_alloc(bp, stream); }));
-  FC_HIP(run(K_SNAPKV_SCORE, ns > 0 || !split_launches.empty(), [&] {
+  FC_HIP_STAGE(p, run(K_PLAN_ALLOC, true, [&] { return launch_plan_alloc(bp, stream); }));
+  FC_HIP_STAGE(p, run(K_SNAPKV_SCORE, ns > 0 || !plan.split_launches.empty(), [&] {
     hipError_t e = hipSuccess;
-    for (const SplitLaunch& sl : split_launches) {
+    for (const SplitLaunch& sl : plan.split_launches) {
       if (e != hipSuccess) break;
       const int grid = p->split_grid[sl.nt];
       // (a fill kernel, not a memset: the call may be captured into a graph)
@@ -649,7 +536,7 @@ static int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_bl
       bc.window = 16 * sl.nt;
       if (e == hipSuccess) e = launch_snapkv_split(bc, grid, stream);
     }
-    for (int c = 1; c < kClasses && e == hipSuccess; ++c) {
+    for (int c = 1; c < kPlanClasses && e == hipSuccess; ++c) {
       if (n_list[LIST_SNAP + c] == 0) continue;
       BatchParams bc = bp;
       bc.order_snap = dev_list(LIST_SNAP + c);
@@ -659,31 +546,36 @@ static int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_bl
     }
     return e;
   }));
-  FC_HIP(run(K_SELECT_GATHER, bp.n_split > 0,
-             [&] { return launch_select_gather(bp, max_len_list[LIST_SPLIT], stream); }));
-  FC_HIP(run(K_KNORM_SCORE, nk > 0, [&] { return launch_knorm_score(bp, stream); }));
-  FC_HIP(run(K_SELECT, bp.n_unfused > 0,
-             [&] { return launch_select(bp, max_len_list[LIST_ALL], stream); }));
-  FC_HIP(run(K_GATHER, bp.n_unfused > 0, [&] { return launch_gather(bp, stream); }));
-  FC_HIP(run(K_FUSED, n_fused > 0, [&] {
+  FC_HIP_STAGE(p, run(K_SELECT_GATHER, bp.n_split > 0, [&] {
+    return launch_select_gather(bp, plan.max_len[LIST_SPLIT], stream);
+  }));
+  FC_HIP_STAGE(p, run(K_KNORM_SCORE, bp.n_knorm > 0, [&] { return launch_knorm_score(bp, stream); }));
+  FC_HIP_STAGE(p, run(K_SELECT, bp.n_unfused > 0,
+                      [&] { return launch_select(bp, plan.max_len[LIST_ALL], stream); }));
+  FC_HIP_STAGE(p, run(K_GATHER, bp.n_unfused > 0, [&] { return launch_gather(bp, stream); }));
+  FC_HIP_STAGE(p, run(K_FUSED, n_fused > 0, [&] {
     hipError_t e = hipSuccess;
-    for (int c = 0; c < kClasses && e == hipSuccess; ++c) {
+    for (int c = 0; c < kPlanClasses && e == hipSuccess; ++c) {
       if (n_list[LIST_FUSED + c] == 0) continue;
       BatchParams bc = bp;
       bc.order_fused = dev_list(LIST_FUSED + c);
       bc.n_fused = n_list[LIST_FUSED + c];
       bc.window = 16 * c;
-      e = launch_fused(bc, c > 0, max_len_list[LIST_FUSED + c], stream);
+      e = launch_fused(bc, c > 0, plan.max_len[LIST_FUSED + c], stream);
     }
     return e;
   }));
-  FC_HIP(run(K_RECLAIM, true, [&] { return launch_reclaim(bp, stream); }));
+  FC_HIP_STAGE(p, run(K_RECLAIM, true, [&] { return launch_reclaim(bp, stream); }));
 
   // ---- host mirrors ------------------------------------------------------------
-  p->top = in_place ? p->top + total_released : p->top - total_new + total_old;
-  for (const ReqDesc& d : descs) host_seq_lens[d.table_row] = d.budget;
+  p->top = plan.top_after;
+  for (const ReqDesc& d : plan.descs) host_seq_lens[d.table_row] = d.budget;
   return FC_OK;
 }
+
+}  // namespace
+
+extern "C" {
 
 int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_req,
                       int32_t* host_seq_lens, const void* dev_q_window, int window,
@@ -706,12 +598,24 @@ int fc_compress_batch_lse(fc_pool* p, int32_t* dev_block_tables, int max_blocks_
                              stream);
 }
 
+int fc_compress_batch_var(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_req,
+                          int32_t* host_seq_lens, const void* dev_q_window,
+                          const int32_t* host_window, const int32_t* host_method,
+                          const int32_t* host_budget, const int32_t* host_pool_kernel, int n_req,
+                          float scale, float* dev_scores_out, int32_t* dev_kept_out,
+                          void* stream) {
+  if (n_req > 0 && (!host_window || !host_pool_kernel)) return fail(FC_EINVAL, "NULL argument");
+  return compress_batch_impl(p, dev_block_tables, max_blocks_per_req, host_seq_lens, dev_q_window,
+                             nullptr, false, host_window, 0, host_method, host_budget, n_req,
+                             host_pool_kernel, 0, scale, dev_scores_out, dev_kept_out, stream);
+}
+
 int fc_window_lse(fc_pool* p, const int32_t* dev_block_tables, int max_blocks_per_req,
                   const int32_t* host_seq_lens, const void* dev_q_window, int window,
                   const int32_t* host_method, int n_req, float scale, float* dev_lse_out,
                   void* stream_) {
   hipStream_t stream = static_cast<hipStream_t>(stream_);
-  if (!p) return fail(FC_EINVAL, "pool is NULL");
+  FC_CHECK_POOL(p);
   if (n_req < 0) return fail(FC_EINVAL, "n_req < 0");
   if (n_req == 0) return FC_OK;
   if (!dev_block_tables || !host_seq_lens || !dev_q_window || !dev_lse_out)
@@ -720,49 +624,21 @@ int fc_window_lse(fc_pool* p, const int32_t* dev_block_tables, int max_blocks_pe
     return fail(FC_EINVAL, "dev_q_window must be 16-byte aligned");
   if (reinterpret_cast<uintptr_t>(dev_lse_out) & 3)
     return fail(FC_EINVAL, "dev_lse_out must be 4-byte aligned");
-  if (max_blocks_per_req < 1) return fail(FC_EINVAL, "max_blocks_per_req < 1");
-  if (window < 1 || window > FC_MAX_WINDOW)
-    return fail(FC_EINVAL, "window %d outside 1..%d", window, FC_MAX_WINDOW);
-  const size_t n_lh = (size_t)p->n_layers * p->n_heads;
-  std::vector<ReqDesc> descs;
-  for (int r = 0; r < n_req; ++r) {
-    if (host_method && host_method[r] != FC_METHOD_SNAPKV) continue;
-    const int L = host_seq_lens[r];
-    if (L < window || L > FC_MAX_SEQ_LEN)
-      return fail(FC_EINVAL, "request %d: length %d outside %d..%d", r, L, window, FC_MAX_SEQ_LEN);
-    ReqDesc d = {};
-    d.window = window;
-    d.pool_kernel = 1;
-    d.seq_len = L;
-    d.budget = L;
-    d.method = FC_METHOD_SNAPKV;
-    d.table_row = r;
-    d.n_old = (L + FC_BLOCK_SIZE - 1) / FC_BLOCK_SIZE;
-    if (d.n_old > max_blocks_per_req)
-      return fail(FC_EINVAL, "request %d: %d blocks exceed max_blocks_per_req %d", r, d.n_old,
-                  max_blocks_per_req);
-    d.q_off = (int64_t)((size_t)r * n_lh * window * p->head_dim);
-    descs.push_back(d);
-  }
-  if (descs.empty()) return FC_OK;
-  // longest first, so that the tail of the launch is made of short units
-  std::stable_sort(descs.begin(), descs.end(),
-                   [](const ReqDesc& a, const ReqDesc& b) { return a.seq_len > b.seq_len; });
-  const int n = (int)descs.size();
+  LsePlan plan;
+  if (plan_window_lse(pool_view(p, false), n_req, max_blocks_per_req, host_seq_lens, host_method,
+                      window, &plan) != PLAN_OK)
+    return fail(plan.code, "%s", plan.message);
+  if (plan.descs.empty()) return FC_OK;
+  const int n = (int)plan.descs.size();
   const size_t desc_bytes = round_up((size_t)n * sizeof(ReqDesc), 16);
   const size_t meta_bytes = desc_bytes + round_up((size_t)n * sizeof(int32_t), 16);
   int rc;
   if ((rc = grow_meta(p, meta_bytes)) != FC_OK) return rc;
-  if (p->meta_pending) {
-    FC_HIP(hipEventSynchronize(p->meta_event));
-    p->meta_pending = false;
-  }
-  memcpy(p->host_meta, descs.data(), (size_t)n * sizeof(ReqDesc));
-  int32_t* order = reinterpret_cast<int32_t*>(p->host_meta + desc_bytes);
+  std::vector<char> image(meta_bytes, 0);
+  memcpy(image.data(), plan.descs.data(), (size_t)n * sizeof(ReqDesc));
+  int32_t* order = reinterpret_cast<int32_t*>(image.data() + desc_bytes);
   for (int i = 0; i < n; ++i) order[i] = i;
-  FC_HIP(hipMemcpyAsync(p->dev_meta, p->host_meta, meta_bytes, hipMemcpyHostToDevice, stream));
-  FC_HIP(hipEventRecord(p->meta_event, stream));
-  p->meta_pending = true;
+  if ((rc = upload_meta(p, image.data(), meta_bytes, p->dev_meta, stream)) != FC_OK) return rc;
 
   BatchParams bp = {};
   bp.kv = p->kv;
@@ -792,18 +668,6 @@ int fc_window_lse(fc_pool* p, const int32_t* dev_block_tables, int max_blocks_pe
     p->timed[ring][K_WINDOW_LSE] = true;
   }
   return FC_OK;
-}
-
-int fc_compress_batch_var(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_req,
-                          int32_t* host_seq_lens, const void* dev_q_window,
-                          const int32_t* host_window, const int32_t* host_method,
-                          const int32_t* host_budget, const int32_t* host_pool_kernel, int n_req,
-                          float scale, float* dev_scores_out, int32_t* dev_kept_out,
-                          void* stream) {
-  if (n_req > 0 && (!host_window || !host_pool_kernel)) return fail(FC_EINVAL, "NULL argument");
-  return compress_batch_impl(p, dev_block_tables, max_blocks_per_req, host_seq_lens, dev_q_window,
-                             nullptr, false, host_window, 0, host_method, host_budget, n_req,
-                             host_pool_kernel, 0, scale, dev_scores_out, dev_kept_out, stream);
 }
 
 int fc_mlp_set_weights(fc_pool* p, const fc_mlp_weights* w, void* stream_) {
@@ -852,81 +716,27 @@ int fc_compress_batch_mlp(fc_pool* p, int32_t* dev_block_tables, int max_blocks_
                           const int32_t* host_img_end, const int32_t* host_enable, int n_req,
                           void* stream_) {
   hipStream_t stream = static_cast<hipStream_t>(stream_);
-  if (!p) return fail(FC_EINVAL, "pool is NULL");
+  FC_CHECK_POOL(p);
   if (p->mlp_k == 0) return fail(FC_EINVAL, "fc_mlp_set_weights has not been called");
-  if (n_req < 0) return fail(FC_EINVAL, "n_req < 0");
-  if (n_req == 0) return FC_OK;
-  if (!dev_block_tables || !host_seq_lens || !host_img_begin || !host_img_end)
-    return fail(FC_EINVAL, "NULL argument");
-  if (max_blocks_per_req < 1) return fail(FC_EINVAL, "max_blocks_per_req < 1");
-  const int k = p->mlp_k;
-  const int n_units = p->n_layers * p->n_heads * 2;
-  const int tile_rows = mlp_rows_per_tile(p->mlp_hidden);
-  std::vector<ReqDesc> descs;
-  std::vector<MlpJob> jobs;
-  int total_new = 0, total_old = 0;
-  long long n_tiles = 0;
-  for (int r = 0; r < n_req; ++r) {
-    if (host_enable && !host_enable[r]) continue;
-    const int L = host_seq_lens[r], ib = host_img_begin[r], ie = host_img_end[r];
-    if (L < 1 || L > FC_MAX_SEQ_LEN)
-      return fail(FC_EINVAL, "request %d: length %d outside 1..%d", r, L, FC_MAX_SEQ_LEN);
-    if (ib < 0 || ib > ie || ie > L)
-      return fail(FC_EINVAL, "request %d: image span [%d, %d) outside [0, %d]", r, ib, ie, L);
-    ReqDesc d = {};
-    d.seq_len = L;
-    d.img_begin = ib;
-    d.img_end = ie;
-    d.chunks_text0 = (ib + k - 1) / k;
-    d.chunks_image = (ie - ib + k - 1) / k;
-    d.chunks_text1 = (L - ie + k - 1) / k;
-    d.budget = d.chunks_text0 + d.chunks_image + d.chunks_text1;
-    d.method = FC_METHOD_NONE;
-    d.table_row = r;
-    d.n_old = (L + FC_BLOCK_SIZE - 1) / FC_BLOCK_SIZE;
-    d.n_new = (d.budget + FC_BLOCK_SIZE - 1) / FC_BLOCK_SIZE;
-    if (d.n_old > max_blocks_per_req)
-      return fail(FC_EINVAL, "request %d: %d blocks exceed max_blocks_per_req %d", r, d.n_old,
-                  max_blocks_per_req);
-    d.old_off = total_old;
-    d.new_off = total_new;
-    total_old += d.n_old;
-    total_new += d.n_new;
-    const int di = (int)descs.size();
-    const int per_modality[2] = {d.chunks_text0 + d.chunks_text1, d.chunks_image};
-    for (int m = 0; m < 2; ++m) {
-      if (per_modality[m] == 0) continue;
-      MlpJob j;
-      j.desc = di;
-      j.modality = m;
-      j.chunks = per_modality[m];
-      j.tile_start = (int)n_tiles;
-      n_tiles += ((long long)n_units * per_modality[m] + tile_rows - 1) / tile_rows;
-      jobs.push_back(j);
-    }
-    descs.push_back(d);
-  }
-  const int n_comp = (int)descs.size();
+  if (n_req > 0 && !dev_block_tables) return fail(FC_EINVAL, "NULL argument");
+  MlpPlan plan;
+  if (plan_mlp(pool_view(p, false), n_req, max_blocks_per_req, host_seq_lens, host_img_begin,
+               host_img_end, host_enable, p->mlp_k, mlp_rows_per_tile(p->mlp_hidden),
+               &plan) != PLAN_OK)
+    return fail(plan.code, "%s", plan.message);
+  const int n_comp = (int)plan.descs.size();
   if (n_comp == 0) return FC_OK;
-  if (n_tiles > 0x7fffffffLL) return fail(FC_EINVAL, "batch too large for one launch");
-  if (total_new > p->top)
-    return fail(FC_ENOMEM, "batch needs %d new blocks, %d free", total_new, p->top);
 
   int rc;
-  if ((rc = grow(&p->ids, &p->ids_cap, (size_t)total_old + total_new)) != FC_OK) return rc;
+  if ((rc = grow(&p->ids, &p->ids_cap, (size_t)plan.total_old + plan.total_new)) != FC_OK) return rc;
   const size_t desc_bytes = round_up((size_t)n_comp * sizeof(ReqDesc), 16);
-  const size_t job_bytes = round_up(jobs.size() * sizeof(MlpJob), 16);
+  const size_t job_bytes = round_up(plan.jobs.size() * sizeof(MlpJob), 16);
   if ((rc = grow_meta(p, desc_bytes + job_bytes)) != FC_OK) return rc;
-  if (p->meta_pending) {
-    FC_HIP(hipEventSynchronize(p->meta_event));
-    p->meta_pending = false;
-  }
-  memcpy(p->host_meta, descs.data(), (size_t)n_comp * sizeof(ReqDesc));
-  memcpy(p->host_meta + desc_bytes, jobs.data(), jobs.size() * sizeof(MlpJob));
-  FC_HIP(hipMemcpyAsync(p->dev_meta, p->host_meta, desc_bytes + job_bytes, hipMemcpyHostToDevice,
-                        stream));
-  FC_HIP(hipEventRecord(p->meta_event, stream));
-  p->meta_pending = true;
+  std::vector<char> image(desc_bytes + job_bytes, 0);
+  memcpy(image.data(), plan.descs.data(), (size_t)n_comp * sizeof(ReqDesc));
+  memcpy(image.data() + desc_bytes, plan.jobs.data(), plan.jobs.size() * sizeof(MlpJob));
+  if ((rc = upload_meta(p, image.data(), image.size(), p->dev_meta, stream)) != FC_OK)
+    return rc;
 
   BatchParams bp = {};
   bp.kv = p->kv;
@@ -936,26 +746,27 @@ int fc_compress_batch_mlp(fc_pool* p, int32_t* dev_block_tables, int max_blocks_
   bp.head_dim = p->head_dim;
   bp.stack = p->stack;
   bp.top_before = p->top;
-  bp.total_new = total_new;
-  bp.total_old = total_old;
+  bp.total_new = plan.total_new;
+  bp.total_old = plan.total_old;
   bp.descs = reinterpret_cast<const ReqDesc*>(p->dev_meta);
   bp.n_comp = n_comp;
   bp.block_tables = dev_block_tables;
   bp.max_blocks = max_blocks_per_req;
   bp.old_ids = p->ids;
-  bp.new_ids = p->ids + total_old;
+  bp.new_ids = p->ids + plan.total_old;
   bp.error_flag = p->error_flag;
+  bp.owner = p->debug_checks ? p->owner : nullptr;
   MlpParams mp = {};
   mp.jobs = reinterpret_cast<const MlpJob*>(p->dev_meta + desc_bytes);
-  mp.n_jobs = (int)jobs.size();
-  mp.n_tiles = (int)n_tiles;
+  mp.n_jobs = (int)plan.jobs.size();
+  mp.n_tiles = (int)plan.n_tiles;
   {
     int dev = 0, cus = 0;
     FC_HIP(hipGetDevice(&dev));
     FC_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
     mp.max_grid = std::max(cus, 1) * mlp_workgroups_per_cu();
   }
-  mp.k = k;
+  mp.k = p->mlp_k;
   mp.hidden = p->mlp_hidden;
   mp.activation = p->mlp_activation;
   for (int m = 0; m < 2; ++m) {
@@ -980,12 +791,12 @@ int fc_compress_batch_mlp(fc_pool* p, int32_t* dev_block_tables, int max_blocks_
     }
     return e;
   };
-  FC_HIP(run(K_PLAN_ALLOC, [&] { return launch_plan_alloc(bp, stream); }));
-  FC_HIP(run(K_MLP, [&] { return launch_mlp_compress(bp, mp, stream); }));
-  FC_HIP(run(K_RECLAIM, [&] { return launch_reclaim(bp, stream); }));
+  FC_HIP_STAGE(p, run(K_PLAN_ALLOC, [&] { return launch_plan_alloc(bp, stream); }));
+  FC_HIP_STAGE(p, run(K_MLP, [&] { return launch_mlp_compress(bp, mp, stream); }));
+  FC_HIP_STAGE(p, run(K_RECLAIM, [&] { return launch_reclaim(bp, stream); }));
 
-  p->top = p->top - total_new + total_old;
-  for (const ReqDesc& d : descs) host_seq_lens[d.table_row] = d.budget;
+  p->top = plan.top_after;
+  for (const ReqDesc& d : plan.descs) host_seq_lens[d.table_row] = d.budget;
   return FC_OK;
 }
 
@@ -1016,15 +827,9 @@ int upload_decode_reqs(fc_pool* p, const std::vector<DecodeReq>& reqs, hipStream
   const size_t bytes = round_up(reqs.size() * sizeof(DecodeReq), 16);
   int rc;
   if ((rc = grow_meta(p, bytes)) != FC_OK) return rc;
-  if (p->meta_pending) {
-    FC_HIP(hipEventSynchronize(p->meta_event));
-    p->meta_pending = false;
-  }
-  memcpy(p->host_meta, reqs.data(), reqs.size() * sizeof(DecodeReq));
-  FC_HIP(hipMemcpyAsync(p->dev_meta, p->host_meta, bytes, hipMemcpyHostToDevice, stream));
-  FC_HIP(hipEventRecord(p->meta_event, stream));
-  p->meta_pending = true;
-  return FC_OK;
+  std::vector<char> image(bytes, 0);
+  memcpy(image.data(), reqs.data(), reqs.size() * sizeof(DecodeReq));
+  return upload_meta(p, image.data(), bytes, p->dev_meta, stream);
 }
 
 DecodeParams decode_params(fc_pool* p) {
@@ -1037,89 +842,28 @@ DecodeParams decode_params(fc_pool* p) {
   dp.stack = p->stack;
   dp.top_before = p->top;
   dp.reqs = reinterpret_cast<const DecodeReq*>(p->dev_meta);
+  dp.owner = p->debug_checks ? p->owner : nullptr;
+  dp.error_flag = p->error_flag;
   return dp;
 }
 
-}  // namespace
-
-extern "C" {
-
-int fc_append_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_req,
-                    int32_t* host_seq_lens, const void* dev_new_kv, const int32_t* host_enable,
-                    int n_req, void* stream_) {
+int decode_attention_impl(fc_pool* p, const int32_t* dev_block_tables, int max_blocks_per_req,
+                          const int32_t* host_seq_lens, const int32_t* host_budget,
+                          const int32_t* dev_kept, const void* dev_q, float* dev_out, int n_req,
+                          float scale, void* stream_) {
   hipStream_t stream = static_cast<hipStream_t>(stream_);
-  if (!p) return fail(FC_EINVAL, "pool is NULL");
-  if (n_req < 0) return fail(FC_EINVAL, "n_req < 0");
-  if (n_req == 0) return FC_OK;
-  if (!dev_block_tables || !host_seq_lens || !dev_new_kv) return fail(FC_EINVAL, "NULL argument");
-  if (reinterpret_cast<uintptr_t>(dev_new_kv) & 15)
-    return fail(FC_EINVAL, "dev_new_kv must be 16-byte aligned");
-  if (max_blocks_per_req < 1) return fail(FC_EINVAL, "max_blocks_per_req < 1");
-  std::vector<DecodeReq> reqs;
-  int n_pop = 0;
-  for (int r = 0; r < n_req; ++r) {
-    if (host_enable && !host_enable[r]) continue;
-    const int L = host_seq_lens[r];
-    if (L < 0 || L >= FC_MAX_SEQ_LEN)
-      return fail(FC_EINVAL, "request %d: length %d outside 0..%d", r, L, FC_MAX_SEQ_LEN - 1);
-    if (L / FC_BLOCK_SIZE >= max_blocks_per_req)
-      return fail(FC_EINVAL, "request %d: its table row is full", r);
-    DecodeReq q = {r, L, (L % FC_BLOCK_SIZE == 0) ? n_pop++ : -1, 0, 0};
-    reqs.push_back(q);
-  }
-  if (reqs.empty()) return FC_OK;
-  if (n_pop > p->top) return fail(FC_ENOMEM, "append needs %d new blocks, %d free", n_pop, p->top);
-  int rc;
-  if ((rc = upload_decode_reqs(p, reqs, stream)) != FC_OK) return rc;
-  DecodeParams dp = decode_params(p);
-  dp.block_tables = dev_block_tables;
-  dp.max_blocks = max_blocks_per_req;
-  dp.n_req = (int)reqs.size();
-  dp.new_kv = static_cast<const _Float16*>(dev_new_kv);
-  FC_HIP(run_profiled(p, K_APPEND, stream, [&] { return launch_append(dp, stream); }));
-  p->top -= n_pop;
-  for (const DecodeReq& q : reqs) host_seq_lens[q.table_row] = q.seq_len + 1;
-  return FC_OK;
-}
-
-static int decode_attention_impl(fc_pool* p, const int32_t* dev_block_tables,
-                                 int max_blocks_per_req, const int32_t* host_seq_lens,
-                                 const int32_t* host_budget, const int32_t* dev_kept,
-                                 const void* dev_q, float* dev_out, int n_req, float scale,
-                                 void* stream_) {
-  hipStream_t stream = static_cast<hipStream_t>(stream_);
-  if (!p) return fail(FC_EINVAL, "pool is NULL");
+  FC_CHECK_POOL(p);
   if (n_req < 0) return fail(FC_EINVAL, "n_req < 0");
   if (n_req == 0) return FC_OK;
   if (!dev_block_tables || !host_seq_lens || !dev_q || !dev_out)
     return fail(FC_EINVAL, "NULL argument");
   if (reinterpret_cast<uintptr_t>(dev_q) & 15) return fail(FC_EINVAL, "dev_q must be 16-byte aligned");
-  if (max_blocks_per_req < 1) return fail(FC_EINVAL, "max_blocks_per_req < 1");
-  const size_t n_lh = (size_t)p->n_layers * p->n_heads;
-  std::vector<DecodeReq> reqs(n_req);
-  size_t kept_off = 0;
-  for (int r = 0; r < n_req; ++r) {
-    const int L = host_seq_lens[r];
-    if (L < 0 || L > FC_MAX_SEQ_LEN)
-      return fail(FC_EINVAL, "request %d: length %d outside 0..%d", r, L, FC_MAX_SEQ_LEN);
-    if ((L + FC_BLOCK_SIZE - 1) / FC_BLOCK_SIZE > max_blocks_per_req)
-      return fail(FC_EINVAL, "request %d: %d tokens exceed max_blocks_per_req", r, L);
-    DecodeReq q = {r, L, -1, 0, 0};
-    if (dev_kept) {
-      const int B = host_budget[r];
-      if (B < 0 || B > L) return fail(FC_EINVAL, "request %d: budget %d outside 0..%d", r, B, L);
-      q.pop_index = B;
-      q.kept_off = (int64_t)kept_off;
-      kept_off += n_lh * (size_t)B;
-    }
-    reqs[r] = q;
-  }
-  // longest first, so that the tail of the launch is made of short units
-  std::stable_sort(reqs.begin(), reqs.end(), [&](const DecodeReq& a, const DecodeReq& b) {
-    return (dev_kept ? a.pop_index > b.pop_index : a.seq_len > b.seq_len);
-  });
+  DecodePlan plan;
+  if (plan_decode_attention(pool_view(p, false), n_req, max_blocks_per_req, host_seq_lens,
+                            dev_kept ? host_budget : nullptr, &plan) != PLAN_OK)
+    return fail(plan.code, "%s", plan.message);
   int rc;
-  if ((rc = upload_decode_reqs(p, reqs, stream)) != FC_OK) return rc;
+  if ((rc = upload_decode_reqs(p, plan.reqs, stream)) != FC_OK) return rc;
   DecodeParams dp = decode_params(p);
   dp.block_tables = const_cast<int32_t*>(dev_block_tables);
   dp.max_blocks = max_blocks_per_req;
@@ -1131,6 +875,38 @@ static int decode_attention_impl(fc_pool* p, const int32_t* dev_block_tables,
   dp.scale_log2e = sc * 1.44269504088896340736f;
   FC_HIP(run_profiled(p, K_DECODE_ATTENTION, stream,
                       [&] { return launch_decode_attention(dp, stream); }));
+  return FC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int fc_append_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_req,
+                    int32_t* host_seq_lens, const void* dev_new_kv, const int32_t* host_enable,
+                    int n_req, void* stream_) {
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  FC_CHECK_POOL(p);
+  if (n_req < 0) return fail(FC_EINVAL, "n_req < 0");
+  if (n_req == 0) return FC_OK;
+  if (!dev_block_tables || !host_seq_lens || !dev_new_kv) return fail(FC_EINVAL, "NULL argument");
+  if (reinterpret_cast<uintptr_t>(dev_new_kv) & 15)
+    return fail(FC_EINVAL, "dev_new_kv must be 16-byte aligned");
+  DecodePlan plan;
+  if (plan_append(pool_view(p, false), n_req, max_blocks_per_req, host_seq_lens, host_enable,
+                  &plan) != PLAN_OK)
+    return fail(plan.code, "%s", plan.message);
+  if (plan.reqs.empty()) return FC_OK;
+  int rc;
+  if ((rc = upload_decode_reqs(p, plan.reqs, stream)) != FC_OK) return rc;
+  DecodeParams dp = decode_params(p);
+  dp.block_tables = dev_block_tables;
+  dp.max_blocks = max_blocks_per_req;
+  dp.n_req = (int)plan.reqs.size();
+  dp.new_kv = static_cast<const _Float16*>(dev_new_kv);
+  FC_HIP_STAGE(p, run_profiled(p, K_APPEND, stream, [&] { return launch_append(dp, stream); }));
+  p->top -= plan.n_pop;
+  for (const DecodeReq& q : plan.reqs) host_seq_lens[q.table_row] = q.seq_len + 1;
   return FC_OK;
 }
 
