@@ -163,6 +163,35 @@ int fc_compress_batch(fc_pool* pool, int32_t* dev_block_tables, int max_blocks_p
                       int32_t* dev_kept_out, void* stream);
 
 /*
+ * fc_compress_batch for callers that cannot allocate device memory while they
+ * call it: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same results (the same kernels run), but
+ * every scratch buffer of the call (kept lists, saved and new block ids,
+ * request descriptors) lies in ONE fixed device array of
+ * FC_NOALLOC_SCRATCH_BYTES that the library's code object holds on every GPU
+ * it is loaded on until the process ends; the call allocates and frees
+ * nothing, on the device or in pinned host memory, and never waits for the
+ * device.  Limits (FC_EINVAL beyond them, nothing touched):
+ *   - at most FC_NOALLOC_MAX_REQUESTS compressed requests per call;
+ *   - every compressed request has at most 8192 tokens and the pool uses the
+ *     default scheduling (FC_SCORE_AUTO, no split threshold): nothing may
+ *     need the library's un-pooled score scratch;
+ *   - sum over requests of budget * n_layers * n_heads <= 15 Mi entries,
+ *     unless dev_kept_out is given (then the kept lists go there);
+ *   - sum over requests of ceil(L/16) + ceil(budget/16) <= 256 Ki block ids.
+ * All calls on one GPU share that GPU's array and it keeps the last call's
+ * contents (nothing in it has to start at zero): two such calls that overlap
+ * in time on one GPU, on any streams or pools, race.
+ */
+#define FC_NOALLOC_MAX_REQUESTS 64
+#define FC_NOALLOC_SCRATCH_BYTES ((15u << 20) * 4u + (256u << 10) * 4u + (16u << 10))
+int fc_compress_batch_noalloc(fc_pool* pool, int32_t* dev_block_tables, int max_blocks_per_req,
+                              int32_t* host_seq_lens, const void* dev_q_window, int window,
+                              const int32_t* host_method, const int32_t* host_budget, int n_req,
+                              int pool_kernel, float scale, float* dev_scores_out,
+                              int32_t* dev_kept_out, void* stream);
+
+/*
  * The same stage (Algorithm 1, "Batch compression") for a batch whose SnapKV
  * requests each have their own observation window and max-pool width, as
  * when requests come from models or prompts with different settings.

@@ -55,10 +55,45 @@ static_assert(kPlanBlockSize == FC_BLOCK_SIZE && kPlanMaxWindow == FC_MAX_WINDOW
               kPlanFusedMaxLen == kFusedMaxLen && kPlanClasses == FC_MAX_WINDOW / 16 + 1,
               "limits");
 
+// ---- scratch of the allocation-free entry point --------------------------------
+// One file-scope device array per GPU, carved into the kept lists, the saved
+// and new block ids and the descriptors.  Its name is only a host-side handle:
+// the device address comes from hipGetSymbolAddress, once per device.
+constexpr size_t kNoAllocKeptInts = (size_t)15 << 20;  // 60 MiB of kept indices
+constexpr size_t kNoAllocIdInts = (size_t)256 << 10;   // 1 MiB of block ids
+constexpr size_t kNoAllocMetaBytes = (size_t)16 << 10;
+constexpr size_t kNoAllocKeptOff = 0;
+constexpr size_t kNoAllocIdsOff = kNoAllocKeptOff + kNoAllocKeptInts * sizeof(int32_t);
+constexpr size_t kNoAllocMetaOff = kNoAllocIdsOff + kNoAllocIdInts * sizeof(int32_t);
+constexpr size_t kNoAllocBytes = kNoAllocMetaOff + kNoAllocMetaBytes;
+static_assert(kNoAllocBytes == FC_NOALLOC_SCRATCH_BYTES, "the header states the size");
+constexpr int kMaxDevices = 64;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};
 
 size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 constexpr int kProfRing = 32;
+
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kNoAllocBytes];
+
+namespace {
+
+// Device address of `scratch` on the current device (looked up once per device).
+int fixed_scratch_of_current_device(unsigned char** out) {
+  int dev = 0;
+  FC_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(FC_EDEVICE, "device index %d out of range", dev);
+  if (!g_scratch_ptr[dev]) {
+    unsigned char* ptr = nullptr;
+    FC_HIP(hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch)));
+    if (!ptr) return fail(FC_EDEVICE, "hipGetSymbolAddress returned a null address");
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return FC_OK;
+}
 
 }  // namespace
 
@@ -69,6 +104,7 @@ struct fc_pool {
   int32_t* stack = nullptr;  // device
   int top = 0;               // host mirror, exact
   bool poisoned = false;     // a launch failed in the middle of a stage: device and host disagree
+  unsigned char* fixed_scratch = nullptr;  // this device's copy of the file-scope scratch array
   // ownership checks (debug mode): one int per block, 0 free, 1 handed out, 2 being released
   bool debug_checks = false;
   int32_t* owner = nullptr;
@@ -165,7 +201,11 @@ int fc_pool_create(fc_pool** out, void* kv_base, size_t kv_bytes, int n_blocks, 
                 need);
   FC_HIP(kernels_one_time_setup());
   FC_HIP(mlp_one_time_setup());
+  // this device's copy of the allocation-free entry point's scratch array
+  unsigned char* fixed = nullptr;
+  if (int rc = fixed_scratch_of_current_device(&fixed)) return rc;
   fc_pool* p = new fc_pool();
+  p->fixed_scratch = fixed;
   p->kv = static_cast<_Float16*>(kv_base);
   p->kv_bytes = kv_bytes;
   p->n_blocks = n_blocks;
@@ -377,9 +417,20 @@ PoolView pool_view(fc_pool* p, bool want_split) {
                               "undefined state; destroy it");                       \
   } while (0)
 
-// Descriptors and work lists to the device, through the pinned staging buffer
-// and one asynchronous copy.
-int upload_meta(fc_pool* p, const char* image, size_t bytes, char* dev_dst, hipStream_t stream) {
+// Descriptors and work lists to the device.  With the library's own scratch
+// they go through the pinned staging buffer and one asynchronous copy; the
+// allocation-free path sends them as kernel arguments, a few KB per launch.
+int upload_meta(fc_pool* p, const char* image, size_t bytes, char* dev_dst, bool no_alloc,
+                hipStream_t stream) {
+  if (no_alloc) {
+    for (size_t off = 0; off < bytes; off += sizeof(MetaChunk)) {
+      MetaChunk c;
+      const size_t n = std::min(sizeof(MetaChunk), bytes - off);
+      memcpy(c.bytes, image + off, n);
+      FC_HIP(launch_meta_upload(c, dev_dst + off, (int)n, stream));
+    }
+    return FC_OK;
+  }
   if (p->meta_pending) {
     // the previous call's descriptor upload must have left the staging buffer
     FC_HIP(hipEventSynchronize(p->meta_event));
@@ -393,13 +444,15 @@ int upload_meta(fc_pool* p, const char* image, size_t bytes, char* dev_dst, hipS
 }
 
 // All entry points of the pruning stage.  host_window / host_pool_kernel are
-// NULL for the calls that take one size for the whole batch.
+// NULL for the calls that take one size for the whole batch.  no_alloc: every
+// scratch buffer lies in the file-scope device array and nothing is allocated.
 int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_req,
                         int32_t* host_seq_lens, const void* dev_q_window,
                         const float* dev_lse_window, bool need_lse, const int32_t* host_window,
                         int window, const int32_t* host_method, const int32_t* host_budget,
                         int n_req, const int32_t* host_pool_kernel, int pool_kernel, float scale,
-                        float* dev_scores_out, int32_t* dev_kept_out, void* stream_) {
+                        float* dev_scores_out, int32_t* dev_kept_out, void* stream_,
+                        bool no_alloc) {
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   FC_CHECK_POOL(p);
   if (n_req > 0 && !dev_block_tables) return fail(FC_EINVAL, "NULL argument");
@@ -418,7 +471,7 @@ int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_blocks_pe
   a.need_lse = need_lse;
   a.q_ok = dev_q_window && (reinterpret_cast<uintptr_t>(dev_q_window) & 15) == 0;
   a.lse_ok = dev_lse_window && (reinterpret_cast<uintptr_t>(dev_lse_window) & 3) == 0;
-  const bool want_split = !need_lse &&
+  const bool want_split = !no_alloc && !need_lse &&
                           (p->score_mode == FC_SCORE_ONE_PASS ||
                            (p->score_mode == FC_SCORE_AUTO && p->split_min_len > 0));
   const PoolView pv = pool_view(p, want_split);
@@ -436,7 +489,25 @@ int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_blocks_pe
   int32_t* ids_buf = nullptr;
   char* dev_meta = nullptr;
   int rc;
-  {
+  if (no_alloc) {
+    if (!p->fixed_scratch) return fail(FC_EDEVICE, "the fixed scratch array was not set up");
+    if (n_comp > FC_NOALLOC_MAX_REQUESTS)
+      return fail(FC_EINVAL, "%d requests exceed the %d of the allocation-free call", n_comp,
+                  FC_NOALLOC_MAX_REQUESTS);
+    if (plan.raw_floats > 0 || !plan.split_launches.empty())
+      return fail(FC_EINVAL, "the allocation-free call takes heads of at most %d tokens with "
+                             "the default scheduling", kFusedMaxLen);
+    if (!dev_kept_out && plan.kept_entries > kNoAllocKeptInts)
+      return fail(FC_EINVAL, "%zu kept entries exceed the %zu of the fixed scratch (pass "
+                             "dev_kept_out)", plan.kept_entries, kNoAllocKeptInts);
+    if (n_ids > kNoAllocIdInts)
+      return fail(FC_EINVAL, "%zu block ids exceed the %zu of the fixed scratch", n_ids,
+                  kNoAllocIdInts);
+    if (meta_bytes > kNoAllocMetaBytes) return fail(FC_EINVAL, "descriptors exceed the fixed scratch");
+    if (!kept_buf) kept_buf = reinterpret_cast<int32_t*>(p->fixed_scratch + kNoAllocKeptOff);
+    ids_buf = reinterpret_cast<int32_t*>(p->fixed_scratch + kNoAllocIdsOff);
+    dev_meta = reinterpret_cast<char*>(p->fixed_scratch + kNoAllocMetaOff);
+  } else {
     // (growth waits for the device and frees: it happens before anything is queued)
     if (!dev_kept_out && (rc = grow(&p->kept, &p->kept_cap, plan.kept_entries)) != FC_OK) return rc;
     if ((rc = grow(&p->ids, &p->ids_cap, n_ids)) != FC_OK) return rc;
@@ -459,7 +530,7 @@ int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_blocks_pe
     if (n_list[i] > 0)
       memcpy(image.data() + list_off[i], plan.lists[i].data(), (size_t)n_list[i] * sizeof(int32_t));
   }
-  if ((rc = upload_meta(p, image.data(), meta_bytes, dev_meta, stream)) != FC_OK) return rc;
+  if ((rc = upload_meta(p, image.data(), meta_bytes, dev_meta, no_alloc, stream)) != FC_OK) return rc;
 
   BatchParams bp = {};
   bp.kv = p->kv;
@@ -584,7 +655,19 @@ int fc_compress_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_
                       void* stream) {
   return compress_batch_impl(p, dev_block_tables, max_blocks_per_req, host_seq_lens, dev_q_window,
                              nullptr, false, nullptr, window, host_method, host_budget, n_req,
-                             nullptr, pool_kernel, scale, dev_scores_out, dev_kept_out, stream);
+                             nullptr, pool_kernel, scale, dev_scores_out, dev_kept_out, stream,
+                             false);
+}
+
+int fc_compress_batch_noalloc(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_req,
+                              int32_t* host_seq_lens, const void* dev_q_window, int window,
+                              const int32_t* host_method, const int32_t* host_budget, int n_req,
+                              int pool_kernel, float scale, float* dev_scores_out,
+                              int32_t* dev_kept_out, void* stream) {
+  return compress_batch_impl(p, dev_block_tables, max_blocks_per_req, host_seq_lens, dev_q_window,
+                             nullptr, false, nullptr, window, host_method, host_budget, n_req,
+                             nullptr, pool_kernel, scale, dev_scores_out, dev_kept_out, stream,
+                             true);
 }
 
 int fc_compress_batch_lse(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_req,
@@ -595,7 +678,7 @@ int fc_compress_batch_lse(fc_pool* p, int32_t* dev_block_tables, int max_blocks_
   return compress_batch_impl(p, dev_block_tables, max_blocks_per_req, host_seq_lens, dev_q_window,
                              dev_lse_window, true, nullptr, window, host_method, host_budget,
                              n_req, nullptr, pool_kernel, scale, dev_scores_out, dev_kept_out,
-                             stream);
+                             stream, false);
 }
 
 int fc_compress_batch_var(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_req,
@@ -607,7 +690,8 @@ int fc_compress_batch_var(fc_pool* p, int32_t* dev_block_tables, int max_blocks_
   if (n_req > 0 && (!host_window || !host_pool_kernel)) return fail(FC_EINVAL, "NULL argument");
   return compress_batch_impl(p, dev_block_tables, max_blocks_per_req, host_seq_lens, dev_q_window,
                              nullptr, false, host_window, 0, host_method, host_budget, n_req,
-                             host_pool_kernel, 0, scale, dev_scores_out, dev_kept_out, stream);
+                             host_pool_kernel, 0, scale, dev_scores_out, dev_kept_out, stream,
+                             false);
 }
 
 int fc_window_lse(fc_pool* p, const int32_t* dev_block_tables, int max_blocks_per_req,
@@ -638,7 +722,7 @@ int fc_window_lse(fc_pool* p, const int32_t* dev_block_tables, int max_blocks_pe
   memcpy(image.data(), plan.descs.data(), (size_t)n * sizeof(ReqDesc));
   int32_t* order = reinterpret_cast<int32_t*>(image.data() + desc_bytes);
   for (int i = 0; i < n; ++i) order[i] = i;
-  if ((rc = upload_meta(p, image.data(), meta_bytes, p->dev_meta, stream)) != FC_OK) return rc;
+  if ((rc = upload_meta(p, image.data(), meta_bytes, p->dev_meta, false, stream)) != FC_OK) return rc;
 
   BatchParams bp = {};
   bp.kv = p->kv;
@@ -735,7 +819,7 @@ int fc_compress_batch_mlp(fc_pool* p, int32_t* dev_block_tables, int max_blocks_
   std::vector<char> image(desc_bytes + job_bytes, 0);
   memcpy(image.data(), plan.descs.data(), (size_t)n_comp * sizeof(ReqDesc));
   memcpy(image.data() + desc_bytes, plan.jobs.data(), plan.jobs.size() * sizeof(MlpJob));
-  if ((rc = upload_meta(p, image.data(), image.size(), p->dev_meta, stream)) != FC_OK)
+  if ((rc = upload_meta(p, image.data(), image.size(), p->dev_meta, false, stream)) != FC_OK)
     return rc;
 
   BatchParams bp = {};
@@ -829,7 +913,7 @@ int upload_decode_reqs(fc_pool* p, const std::vector<DecodeReq>& reqs, hipStream
   if ((rc = grow_meta(p, bytes)) != FC_OK) return rc;
   std::vector<char> image(bytes, 0);
   memcpy(image.data(), reqs.data(), reqs.size() * sizeof(DecodeReq));
-  return upload_meta(p, image.data(), bytes, p->dev_meta, stream);
+  return upload_meta(p, image.data(), bytes, p->dev_meta, false, stream);
 }
 
 DecodeParams decode_params(fc_pool* p) {

@@ -83,6 +83,10 @@ struct BatchParams {
                                // 2 being released; NULL when the checks are off
 };
 
+// Descriptor bytes that travel as a kernel argument (allocation-free entry point).
+struct MetaChunk {
+  char bytes[3584];
+};
 
 enum KernelSlot {
   K_PLAN_ALLOC = 0,
@@ -123,6 +127,7 @@ hipError_t launch_gather(const BatchParams& p, hipStream_t s);
 hipError_t launch_fused(const BatchParams& p, bool any_snap, int max_seq_len, hipStream_t s);
 static constexpr int kFusedMaxLen = 8192;
 hipError_t launch_reclaim(const BatchParams& p, hipStream_t s);
+hipError_t launch_meta_upload(const MetaChunk& c, char* dst, int n_bytes, hipStream_t s);
 hipError_t kernels_one_time_setup();
 // decode-side pool traffic (fc_decode.hip)
 hipError_t launch_append(const DecodeParams& p, hipStream_t s);

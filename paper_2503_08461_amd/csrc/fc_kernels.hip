@@ -31,6 +31,11 @@ __global__ void pool_push_kernel(int32_t* stack, int top, int n, const int32_t* 
   if (i < n) stack[top + i] = ids[i];
 }
 
+// Writes descriptor bytes that came as a kernel argument to device memory.
+__global__ void meta_upload_kernel(MetaChunk c, char* dst, int n_bytes) {
+  for (int i = threadIdx.x; i < n_bytes; i += blockDim.x) dst[i] = c.bytes[i];
+}
+
 // Pops the new blocks of every compressed request (batch order) and saves the
 // pre-compression ids.  One workgroup per request; offsets are exclusive
 // prefix sums computed by the host, which knows every count.
@@ -823,6 +828,13 @@ hipError_t launch_pool_pop(const int32_t* stack, int top, int n, int32_t* out, h
 hipError_t launch_pool_push(int32_t* stack, int top, int n, const int32_t* ids, hipStream_t s) {
   if (n <= 0) return hipSuccess;
   pool_push_kernel<<<(n + 255) / 256, 256, 0, s>>>(stack, top, n, ids);
+  return hipGetLastError();
+}
+
+hipError_t launch_meta_upload(const MetaChunk& c, char* dst, int n_bytes, hipStream_t s) {
+  if (n_bytes <= 0) return hipSuccess;
+  if (n_bytes > (int)sizeof(MetaChunk)) return hipErrorInvalidValue;
+  meta_upload_kernel<<<1, 256, 0, s>>>(c, dst, n_bytes);
   return hipGetLastError();
 }
 

@@ -26,7 +26,7 @@ EXPORTS = [
     "fc_pool_create", "fc_pool_destroy", "fc_pool_alloc", "fc_pool_free",
     "fc_pool_num_free", "fc_pool_export_state", "fc_pool_import_state",
     "fc_pool_import_state_dev",
-    "fc_compress_batch", "fc_compress_batch_var", "fc_compress_batch_lse", "fc_window_lse",
+    "fc_compress_batch", "fc_compress_batch_noalloc", "fc_compress_batch_var", "fc_compress_batch_lse", "fc_window_lse",
     "fc_append_batch", "fc_decode_attention",
     "fc_decode_attention_kept",
     "fc_mlp_set_weights", "fc_compress_batch_mlp", "fc_set_compaction_mode", "fc_set_streaming_sinks", "fc_set_score_mode", "fc_set_split_threshold", "fc_set_profiling", "fc_get_kernel_times",
@@ -86,6 +86,7 @@ def load_library():
     lib.fc_pool_import_state_dev.argtypes = [vp, vp, i, vp]
     lib.fc_compress_batch.argtypes = [vp, vp, i, i32p, vp, i, i32p, i32p, i, i,
                                       ctypes.c_float, vp, vp, vp]
+    lib.fc_compress_batch_noalloc.argtypes = lib.fc_compress_batch.argtypes
     lib.fc_compress_batch_var.argtypes = [vp, vp, i, i32p, vp, i32p, i32p, i32p, i32p, i,
                                           ctypes.c_float, vp, vp, vp]
     lib.fc_compress_batch_lse.argtypes = [vp, vp, i, i32p, vp, vp, i, i32p, i32p, i, i,
@@ -230,8 +231,18 @@ def fc_pool_import_state_dev(pool, dev_stack, top, stream=None):
                                         _stream_ptr(stream)))
 
 
+def fc_compress_batch_noalloc(pool, block_tables, seq_lens, q_window, window, method, budget,
+                              pool_kernel=7, scale=0.0, scores_out=None, kept_out=None,
+                              stream=None):
+    """fc_compress_batch through the entry point that allocates nothing."""
+    return fc_compress_batch(pool, block_tables, seq_lens, q_window, window, method, budget,
+                             pool_kernel, scale, scores_out, kept_out, stream,
+                             _entry="fc_compress_batch_noalloc")
+
+
 def fc_compress_batch(pool, block_tables, seq_lens, q_window, window, method, budget,
-                      pool_kernel=7, scale=0.0, scores_out=None, kept_out=None, stream=None):
+                      pool_kernel=7, scale=0.0, scores_out=None, kept_out=None, stream=None,
+                      _entry="fc_compress_batch"):
     """block_tables: int32 device tensor [n_req][max_blocks] (in/out);
     seq_lens, method, budget: int32 numpy arrays [n_req] (seq_lens in/out);
     q_window: fp16 device tensor [n_req][n_layers][n_heads][window][head_dim] or None;
@@ -256,7 +267,7 @@ def fc_compress_batch(pool, block_tables, seq_lens, q_window, window, method, bu
         need = int((budget[comp].astype(np.int64)).sum()) * pool.n_layers * pool.n_heads
         if kept_out.numel() < need:
             raise ValueError("kept_out too small")
-    _check(lib.fc_compress_batch(
+    _check(getattr(lib, _entry)(
         pool.ptr, _dev_ptr(block_tables, torch.int32), int(block_tables.shape[1]),
         _host_i32(seq_lens), _dev_ptr(q_window, torch.float16), int(window),
         _host_i32(method), _host_i32(budget), n_req, int(pool_kernel), float(scale),
