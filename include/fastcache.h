@@ -87,10 +87,31 @@ int fc_pool_alloc(fc_pool* pool, int n_blocks, int32_t* dev_out_ids, void* strea
 /*
  * P.Release: pushes ids in array order, stack[top+i] = dev_ids[i], then
  * top += n_blocks.  dev_ids: dev, int32[n_blocks].  The ids must have come
- * from this pool and be owned by the caller (not checked on the device);
- * FC_EINVAL if the push would exceed the pool size.
+ * from this pool and be owned by the caller (checked only with
+ * fc_set_debug_checks); FC_EINVAL if the push would exceed the pool size.
  */
 int fc_pool_free(fc_pool* pool, const int32_t* dev_ids, int n_blocks, void* stream);
+
+/*
+ * Ownership checks, a debug mode for the pool's invariant that every block is
+ * either on the free stack or owned by exactly one request ("KV-cache Memory
+ * Pool" paragraph: the pool is the one authority over allocation and release).
+ * With the checks on, the library keeps one word per block on the device
+ * (free / handed out) and
+ *   - fc_pool_free, and the release of the old blocks inside fc_compress_batch
+ *     (all variants) and fc_compress_batch_mlp, first verify every id they are
+ *     about to push: inside the pool, currently handed out, named once.  A
+ *     double free, a foreign or free id, or a duplicate gives FC_EINVAL and
+ *     nothing is changed.  These calls then wait for the device once (the
+ *     verdict is read on the host), so they are no longer asynchronous;
+ *   - every pop (fc_pool_alloc, the new blocks of a compression, fc_append_batch)
+ *     marks its blocks handed out and raises a flag if one of them was not
+ *     free; fc_pool_export_state reports the flag as FC_EDEVICE.
+ * Switching the checks on takes what is on the free stack as free and every
+ * other block as handed out (so does fc_pool_import_state); it waits for the
+ * device.  Off by default: block ids are then only clamped into the pool.
+ */
+int fc_set_debug_checks(fc_pool* pool, int enable);
 
 /* Number of free blocks (exact host-side mirror of top), or a negative error. */
 int fc_pool_num_free(const fc_pool* pool);

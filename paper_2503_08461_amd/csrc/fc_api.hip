@@ -38,6 +38,28 @@ int fail(int code, const char* fmt, ...) {
       return fail(FC_EDEVICE, "%s failed: %s", #call, hipGetErrorString(e_));   \
   } while (0)
 
+// The calls of a launch sequence change the pool on the device step by step;
+// if one of them fails after the first has been queued, the device state and
+// the host mirrors no longer agree.  The pool is then marked and every later
+// call on it is refused.
+#define FC_HIP_STAGE(pool, call)                                                    \
+  do {                                                                              \
+    hipError_t e_ = (call);                                                         \
+    if (e_ != hipSuccess) {                                                         \
+      (pool)->poisoned = true;                                                      \
+      return fail(FC_EDEVICE, "%s failed: %s; the pool is now unusable", #call,     \
+                  hipGetErrorString(e_));                                           \
+    }                                                                               \
+  } while (0)
+
+#define FC_CHECK_POOL(pool)                                                         \
+  do {                                                                              \
+    if (!(pool)) return fail(FC_EINVAL, "pool is NULL");                            \
+    if ((pool)->poisoned)                                                           \
+      return fail(FC_EDEVICE, "a device error in an earlier call left this pool in an " \
+                              "undefined state; destroy it");                       \
+  } while (0)
+
 const char* const kKernelNames[K_COUNT] = {"plan_alloc", "snapkv_score", "knorm_score",
                                            "select",     "gather",       "reclaim",
                                            "fused_unit", "mlp_compress", "append",
@@ -97,6 +119,11 @@ int fixed_scratch_of_current_device(unsigned char** out) {
 
 }  // namespace
 
+struct fc_pool;
+namespace {
+int release_verdict(fc_pool* p, hipStream_t stream, const char* what);
+}
+
 struct fc_pool {
   _Float16* kv = nullptr;
   size_t kv_bytes = 0;
@@ -108,6 +135,7 @@ struct fc_pool {
   // ownership checks (debug mode): one int per block, 0 free, 1 handed out, 2 being released
   bool debug_checks = false;
   int32_t* owner = nullptr;
+  int32_t* check_word = nullptr;  // device: what the last release check found
 
   // scratch, grown on demand
   float* raw_scores = nullptr;
@@ -235,6 +263,7 @@ int fc_pool_destroy(fc_pool* p) {
   (void)hipDeviceSynchronize();
   if (p->stack) (void)hipFree(p->stack);
   if (p->owner) (void)hipFree(p->owner);
+  if (p->check_word) (void)hipFree(p->check_word);
   if (p->raw_scores) (void)hipFree(p->raw_scores);
   if (p->kept) (void)hipFree(p->kept);
   if (p->ids) (void)hipFree(p->ids);
@@ -257,25 +286,37 @@ int fc_pool_destroy(fc_pool* p) {
 }
 
 int fc_pool_alloc(fc_pool* p, int n, int32_t* dev_out_ids, void* stream) {
-  if (!p) return fail(FC_EINVAL, "pool is NULL");
+  FC_CHECK_POOL(p);
   if (n < 0) return fail(FC_EINVAL, "n_blocks < 0");
   if (n == 0) return FC_OK;
   if (!dev_out_ids) return fail(FC_EINVAL, "dev_out_ids is NULL");
   if (n > p->top) return fail(FC_ENOMEM, "asked for %d blocks, %d free", n, p->top);
-  FC_HIP(launch_pool_pop(p->stack, p->top, n, dev_out_ids, static_cast<hipStream_t>(stream)));
+  FC_HIP(launch_pool_pop(p->stack, p->top, n, dev_out_ids, p->debug_checks ? p->owner : nullptr,
+                         p->n_blocks, p->error_flag, static_cast<hipStream_t>(stream)));
   p->top -= n;
   return FC_OK;
 }
 
 int fc_pool_free(fc_pool* p, const int32_t* dev_ids, int n, void* stream) {
-  if (!p) return fail(FC_EINVAL, "pool is NULL");
+  FC_CHECK_POOL(p);
   if (n < 0) return fail(FC_EINVAL, "n_blocks < 0");
   if (n == 0) return FC_OK;
   if (!dev_ids) return fail(FC_EINVAL, "dev_ids is NULL");
   if (p->top + n > p->n_blocks)
     return fail(FC_EINVAL, "freeing %d blocks with %d already free exceeds the pool (%d)", n,
                 p->top, p->n_blocks);
-  FC_HIP(launch_pool_push(p->stack, p->top, n, dev_ids, static_cast<hipStream_t>(stream)));
+  if (p->debug_checks) {
+    // every id in range, handed out, and named once: checked before anything is pushed
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    FC_HIP(launch_zero_ints(p->check_word, 1, st));
+    FC_HIP(launch_owner_check_ids(dev_ids, n, p->n_blocks, p->owner, p->check_word, false, st));
+    if (int rc = release_verdict(p, st, "fc_pool_free")) {
+      (void)launch_owner_check_ids(dev_ids, n, p->n_blocks, p->owner, p->check_word, true, st);
+      return rc;
+    }
+  }
+  FC_HIP(launch_pool_push(p->stack, p->top, n, dev_ids, p->debug_checks ? p->owner : nullptr,
+                         p->n_blocks, static_cast<hipStream_t>(stream)));
   p->top += n;
   return FC_OK;
 }
@@ -287,7 +328,11 @@ int fc_pool_export_state(fc_pool* p, int32_t* host_stack, int* top) {
   FC_HIP(hipDeviceSynchronize());
   int32_t flag = 0;
   FC_HIP(hipMemcpy(&flag, p->error_flag, sizeof(flag), hipMemcpyDeviceToHost));
-  if (flag) return fail(FC_EDEVICE, "a bounded wait between workgroups ran out in an earlier call");
+  if (flag & 0xFF)
+    return fail(FC_EDEVICE, "a bounded wait between workgroups ran out in an earlier call");
+  if (flag)
+    return fail(FC_EDEVICE, "ownership checks: a block that was popped off the free stack was "
+                            "not free (the free list is corrupt)");
   FC_HIP(hipMemcpy(host_stack, p->stack, (size_t)p->n_blocks * sizeof(int32_t),
                    hipMemcpyDeviceToHost));
   *top = p->top;
@@ -301,6 +346,10 @@ int fc_pool_import_state(fc_pool* p, const int32_t* host_stack, int top) {
   FC_HIP(hipMemcpy(p->stack, host_stack, (size_t)p->n_blocks * sizeof(int32_t),
                    hipMemcpyHostToDevice));
   p->top = top;
+  if (p->debug_checks) {  // what is not on the new stack counts as handed out
+    FC_HIP(launch_owner_init(p->owner, p->stack, top, p->n_blocks, nullptr));
+    FC_HIP(hipDeviceSynchronize());
+  }
   return FC_OK;
 }
 
@@ -324,6 +373,21 @@ int fc_set_score_mode(fc_pool* p, int mode) {
   if (mode != FC_SCORE_AUTO && mode != FC_SCORE_TWO_PASS && mode != FC_SCORE_ONE_PASS)
     return fail(FC_EINVAL, "unknown score mode %d", mode);
   p->score_mode = mode;
+  return FC_OK;
+}
+
+int fc_set_debug_checks(fc_pool* p, int enable) {
+  FC_CHECK_POOL(p);
+  if (!enable) {
+    p->debug_checks = false;
+    return FC_OK;
+  }
+  FC_HIP(hipDeviceSynchronize());  // the free stack must be what the host mirror says
+  if (!p->owner) FC_HIP(hipMalloc(reinterpret_cast<void**>(&p->owner), (size_t)p->n_blocks * sizeof(int32_t)));
+  if (!p->check_word) FC_HIP(hipMalloc(reinterpret_cast<void**>(&p->check_word), sizeof(int32_t)));
+  FC_HIP(launch_owner_init(p->owner, p->stack, p->top, p->n_blocks, nullptr));
+  FC_HIP(hipDeviceSynchronize());
+  p->debug_checks = true;
   return FC_OK;
 }
 
@@ -363,8 +427,11 @@ int fc_get_kernel_times(fc_pool* p, float* host_ms) {
 int fc_pool_import_state_dev(fc_pool* p, const int32_t* dev_stack, int top, void* stream) {
   if (!p || !dev_stack) return fail(FC_EINVAL, "NULL argument");
   if (top < 0 || top > p->n_blocks) return fail(FC_EINVAL, "top out of range");
-  FC_HIP(launch_pool_push(p->stack, 0, p->n_blocks, dev_stack, static_cast<hipStream_t>(stream)));
+  FC_HIP(launch_pool_push(p->stack, 0, p->n_blocks, dev_stack, nullptr, p->n_blocks,
+                         static_cast<hipStream_t>(stream)));
   p->top = top;
+  if (p->debug_checks)  // what is not on the new stack counts as handed out
+    FC_HIP(launch_owner_init(p->owner, p->stack, top, p->n_blocks, static_cast<hipStream_t>(stream)));
   return FC_OK;
 }
 
@@ -395,27 +462,18 @@ PoolView pool_view(fc_pool* p, bool want_split) {
   return v;
 }
 
-// The calls of a launch sequence change the pool on the device step by step;
-// if one of them fails after the first has been queued, the device state and
-// the host mirrors no longer agree.  The pool is then marked and every later
-// call on it is refused.
-#define FC_HIP_STAGE(pool, call)                                                    \
-  do {                                                                              \
-    hipError_t e_ = (call);                                                         \
-    if (e_ != hipSuccess) {                                                         \
-      (pool)->poisoned = true;                                                      \
-      return fail(FC_EDEVICE, "%s failed: %s; the pool is now unusable", #call,     \
-                  hipGetErrorString(e_));                                           \
-    }                                                                               \
-  } while (0)
-
-#define FC_CHECK_POOL(pool)                                                         \
-  do {                                                                              \
-    if (!(pool)) return fail(FC_EINVAL, "pool is NULL");                            \
-    if ((pool)->poisoned)                                                           \
-      return fail(FC_EDEVICE, "a device error in an earlier call left this pool in an " \
-                              "undefined state; destroy it");                       \
-  } while (0)
+// Ownership checks: waits for the check kernel on `stream` and reads its word.
+int release_verdict(fc_pool* p, hipStream_t stream, const char* what) {
+  int32_t word = 0;
+  FC_HIP(hipStreamSynchronize(stream));
+  FC_HIP(hipMemcpy(&word, p->check_word, sizeof(word), hipMemcpyDeviceToHost));
+  if (word == 0) return FC_OK;
+  return fail(FC_EINVAL, "%s: %s%s%s", what,
+              (word & 1) ? "a block id lies outside the pool; " : "",
+              (word & 2) ? "a block id is not handed out (double free, foreign id) or is named "
+                           "twice; " : "",
+              "nothing was changed");
+}
 
 // Descriptors and work lists to the device.  With the library's own scratch
 // they go through the pinned staging buffer and one asynchronous copy; the
@@ -569,6 +627,16 @@ int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_blocks_pe
   bp.kept = kept_buf;
   bp.error_flag = p->error_flag;
   bp.owner = p->debug_checks ? p->owner : nullptr;
+
+  if (p->debug_checks) {
+    // the table rows that the stage will release: every id in range, handed out, named once
+    FC_HIP(launch_zero_ints(p->check_word, 1, stream));
+    FC_HIP(launch_owner_check_tables(bp, p->check_word, false, stream));
+    if (int vr = release_verdict(p, stream, "block tables of the compressed requests")) {
+      (void)launch_owner_check_tables(bp, p->check_word, true, stream);
+      return vr;
+    }
+  }
 
   // ---- the stage ------------------------------------------------------------
   int ns = 0, n_fused = 0;
@@ -860,6 +928,14 @@ int fc_compress_batch_mlp(fc_pool* p, int32_t* dev_block_tables, int max_blocks_
     mp.b2[m] = p->mlp_b2[m];
   }
 
+  if (p->debug_checks) {
+    FC_HIP(launch_zero_ints(p->check_word, 1, stream));
+    FC_HIP(launch_owner_check_tables(bp, p->check_word, false, stream));
+    if (int vr = release_verdict(p, stream, "block tables of the compressed requests")) {
+      (void)launch_owner_check_tables(bp, p->check_word, true, stream);
+      return vr;
+    }
+  }
   const int ring = p->prof_calls % kProfRing;
   if (p->profiling) {
     for (int kk = 0; kk < K_COUNT; ++kk) p->timed[ring][kk] = false;

@@ -24,8 +24,14 @@ __global__ __launch_bounds__(kThreads) void append_kernel(DecodeParams p) {
   int32_t* row = p.block_tables + (size_t)rq.table_row * p.max_blocks;
   int blk;
   if (rq.pop_index >= 0) {
-    blk = clamp_block(p.stack[p.top_before - 1 - rq.pop_index], p.n_blocks);
-    if (layer == 0 && threadIdx.x == 0) row[L >> 4] = blk;
+    const int id = p.stack[p.top_before - 1 - rq.pop_index];
+    blk = clamp_block(id, p.n_blocks);
+    if (layer == 0 && threadIdx.x == 0) {
+      row[L >> 4] = blk;
+      // ownership checks (debug mode): a popped block must have been free
+      if (p.owner && ((unsigned)id >= (unsigned)p.n_blocks || atomicExch(&p.owner[id], 1) != 0))
+        atomicOr(p.error_flag, 4 << 8);
+    }
   } else {
     blk = clamp_block(row[L >> 4], p.n_blocks);
   }

@@ -106,8 +106,19 @@ enum KernelSlot {
 
 // Launchers (fc_kernels.hip).  Each returns the hipError_t of the launch.
 hipError_t launch_stack_init(int32_t* stack, int n_blocks, hipStream_t s);
-hipError_t launch_pool_pop(const int32_t* stack, int top, int n, int32_t* out, hipStream_t s);
-hipError_t launch_pool_push(int32_t* stack, int top, int n, const int32_t* ids, hipStream_t s);
+// owner / flag: ownership checks (debug mode), NULL when off
+hipError_t launch_pool_pop(const int32_t* stack, int top, int n, int32_t* out, int32_t* owner,
+                           int n_blocks, int32_t* flag, hipStream_t s);
+hipError_t launch_pool_push(int32_t* stack, int top, int n, const int32_t* ids, int32_t* owner,
+                            int n_blocks, hipStream_t s);
+// owner[b] = 1, then 0 for the blocks on the free stack
+hipError_t launch_owner_init(int32_t* owner, const int32_t* stack, int top, int n_blocks,
+                             hipStream_t s);
+// claim (or, revert: give back) the ids of a release; *word collects what was wrong
+hipError_t launch_owner_check_ids(const int32_t* ids, int n, int n_blocks, int32_t* owner,
+                                  int32_t* word, bool revert, hipStream_t s);
+hipError_t launch_owner_check_tables(const BatchParams& p, int32_t* word, bool revert,
+                                     hipStream_t s);
 hipError_t launch_plan_alloc(const BatchParams& p, hipStream_t s);
 hipError_t launch_snapkv_score(const BatchParams& p, hipStream_t s);
 // Token-split one-pass variant (fc_score_split.hip).  split_blocks_per_workgroup()

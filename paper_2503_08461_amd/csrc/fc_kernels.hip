@@ -21,14 +21,87 @@ __global__ void stack_init_kernel(int32_t* stack, int n_blocks) {
   if (i < n_blocks) stack[i] = n_blocks - 1 - i;
 }
 
-__global__ void pool_pop_kernel(const int32_t* stack, int top, int n, int32_t* out) {
-  int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) out[i] = stack[top - 1 - i];
+// ---------------------------------------------------------------------------
+// ownership checks (debug mode)
+// ---------------------------------------------------------------------------
+//
+// owner[b]: 0 = block b is on the free stack, 1 = handed out, 2 = named by a
+// release that is being checked.  A release (fc_pool_free, or the reclaim of a
+// compression) is checked before it is carried out: every id must be in range
+// and handed out, and no id may come twice; the check claims each id with a
+// compare-and-swap 1 -> 2, so a second occurrence finds 2.  The host reads the
+// verdict and either lets the release go ahead (2 -> 0 as the ids are pushed)
+// or takes the claims back (2 -> 1) and refuses the call.
+enum { kOwnBadRange = 1, kOwnNotOwned = 2, kOwnNotFree = 4 };
+
+__device__ __forceinline__ void owner_claim(int32_t* owner, int id, int n_blocks, int32_t* word) {
+  if ((unsigned)id >= (unsigned)n_blocks) {
+    atomicOr(word, kOwnBadRange);
+  } else if (atomicCAS(&owner[id], 1, 2) != 1) {
+    atomicOr(word, kOwnNotOwned);
+  }
 }
 
-__global__ void pool_push_kernel(int32_t* stack, int top, int n, const int32_t* ids) {
+__device__ __forceinline__ void owner_unclaim(int32_t* owner, int id, int n_blocks) {
+  if ((unsigned)id < (unsigned)n_blocks) atomicCAS(&owner[id], 2, 1);
+}
+
+__global__ void owner_fill_kernel(int32_t* owner, int n_blocks, int value) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) stack[top + i] = ids[i];
+  if (i < n_blocks) owner[i] = value;
+}
+
+__global__ void owner_mark_free_kernel(int32_t* owner, const int32_t* stack, int top, int n_blocks) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < top && (unsigned)stack[i] < (unsigned)n_blocks) owner[stack[i]] = 0;
+}
+
+__global__ void owner_check_ids_kernel(const int32_t* ids, int n, int n_blocks, int32_t* owner,
+                                       int32_t* word, int revert) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  if (revert)
+    owner_unclaim(owner, ids[i], n_blocks);
+  else
+    owner_claim(owner, ids[i], n_blocks, word);
+}
+
+// the table rows of the requests a compression is about to release
+__global__ __launch_bounds__(kThreads) void owner_check_tables_kernel(BatchParams p, int32_t* word,
+                                                                    int revert) {
+  const ReqDesc rd = p.descs[blockIdx.x];
+  const int32_t* row = p.block_tables + (size_t)rd.table_row * p.max_blocks;
+  for (int i = threadIdx.x; i < rd.n_old; i += kThreads) {
+    if (revert)
+      owner_unclaim(p.owner, row[i], p.n_blocks);
+    else
+      owner_claim(p.owner, row[i], p.n_blocks, word);
+  }
+}
+
+// a popped id must have been free
+__device__ __forceinline__ void owner_take(int32_t* owner, int id, int n_blocks, int32_t* flag) {
+  if (!owner) return;
+  if ((unsigned)id >= (unsigned)n_blocks || atomicExch(&owner[id], 1) != 0) atomicOr(flag, kOwnNotFree << 8);
+}
+
+__global__ void pool_pop_kernel(const int32_t* stack, int top, int n, int32_t* out, int32_t* owner,
+                                int n_blocks, int32_t* flag) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) {
+    const int id = stack[top - 1 - i];
+    out[i] = id;
+    owner_take(owner, id, n_blocks, flag);
+  }
+}
+
+__global__ void pool_push_kernel(int32_t* stack, int top, int n, const int32_t* ids, int32_t* owner,
+                                 int n_blocks) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) {
+    stack[top + i] = ids[i];
+    if (owner && (unsigned)ids[i] < (unsigned)n_blocks) owner[ids[i]] = 0;  // checked before
+  }
 }
 
 // Writes descriptor bytes that came as a kernel argument to device memory.
@@ -45,8 +118,11 @@ __global__ __launch_bounds__(kThreads) void plan_alloc_kernel(BatchParams p) {
   for (int i = threadIdx.x; i < rd.n_old; i += kThreads)
     p.old_ids[rd.old_off + i] = row[i];
   if (!p.in_place)
-    for (int i = threadIdx.x; i < rd.n_new; i += kThreads)
-      p.new_ids[rd.new_off + i] = p.stack[p.top_before - 1 - rd.new_off - i];
+    for (int i = threadIdx.x; i < rd.n_new; i += kThreads) {
+      const int id = p.stack[p.top_before - 1 - rd.new_off - i];
+      p.new_ids[rd.new_off + i] = id;
+      owner_take(p.owner, id, p.n_blocks, p.error_flag);
+    }
 }
 
 // Zombie reclaim: pushes the pre-compression blocks (batch order, table
@@ -59,11 +135,16 @@ __global__ __launch_bounds__(kThreads) void reclaim_kernel(BatchParams p) {
     for (int i = threadIdx.x; i < rd.n_old - rd.n_new; i += kThreads)
       p.stack[p.top_before + rd.new_off + i] = p.old_ids[rd.old_off + rd.n_new + i];
     for (int i = rd.n_new + threadIdx.x; i < p.max_blocks; i += kThreads) row[i] = -1;
+    if (p.owner)  // (ids checked before the stage: in range, claimed)
+      for (int i = threadIdx.x; i < rd.n_old; i += kThreads)
+        p.owner[p.old_ids[rd.old_off + i]] = i < rd.n_new ? 1 : 0;
     return;
   }
   const int base = p.top_before - p.total_new;
-  for (int i = threadIdx.x; i < rd.n_old; i += kThreads)
+  for (int i = threadIdx.x; i < rd.n_old; i += kThreads) {
     p.stack[base + rd.old_off + i] = p.old_ids[rd.old_off + i];
+    if (p.owner) p.owner[p.old_ids[rd.old_off + i]] = 0;  // (checked before the stage)
+  }
   for (int i = threadIdx.x; i < p.max_blocks; i += kThreads)
     row[i] = (i < rd.n_new) ? p.new_ids[rd.new_off + i] : -1;
 }
@@ -819,15 +900,39 @@ hipError_t launch_stack_init(int32_t* stack, int n_blocks, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_pool_pop(const int32_t* stack, int top, int n, int32_t* out, hipStream_t s) {
+hipError_t launch_pool_pop(const int32_t* stack, int top, int n, int32_t* out, int32_t* owner,
+                           int n_blocks, int32_t* flag, hipStream_t s) {
   if (n <= 0) return hipSuccess;
-  pool_pop_kernel<<<(n + 255) / 256, 256, 0, s>>>(stack, top, n, out);
+  pool_pop_kernel<<<(n + 255) / 256, 256, 0, s>>>(stack, top, n, out, owner, n_blocks, flag);
   return hipGetLastError();
 }
 
-hipError_t launch_pool_push(int32_t* stack, int top, int n, const int32_t* ids, hipStream_t s) {
+hipError_t launch_pool_push(int32_t* stack, int top, int n, const int32_t* ids, int32_t* owner,
+                            int n_blocks, hipStream_t s) {
   if (n <= 0) return hipSuccess;
-  pool_push_kernel<<<(n + 255) / 256, 256, 0, s>>>(stack, top, n, ids);
+  pool_push_kernel<<<(n + 255) / 256, 256, 0, s>>>(stack, top, n, ids, owner, n_blocks);
+  return hipGetLastError();
+}
+
+hipError_t launch_owner_init(int32_t* owner, const int32_t* stack, int top, int n_blocks,
+                             hipStream_t s) {
+  owner_fill_kernel<<<(n_blocks + 255) / 256, 256, 0, s>>>(owner, n_blocks, 1);
+  if (top > 0) owner_mark_free_kernel<<<(top + 255) / 256, 256, 0, s>>>(owner, stack, top, n_blocks);
+  return hipGetLastError();
+}
+
+hipError_t launch_owner_check_ids(const int32_t* ids, int n, int n_blocks, int32_t* owner,
+                                  int32_t* word, bool revert, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  owner_check_ids_kernel<<<(n + 255) / 256, 256, 0, s>>>(ids, n, n_blocks, owner, word,
+                                                         revert ? 1 : 0);
+  return hipGetLastError();
+}
+
+hipError_t launch_owner_check_tables(const BatchParams& p, int32_t* word, bool revert,
+                                     hipStream_t s) {
+  if (p.n_comp <= 0) return hipSuccess;
+  owner_check_tables_kernel<<<p.n_comp, kThreads, 0, s>>>(p, word, revert ? 1 : 0);
   return hipGetLastError();
 }
 

@@ -301,7 +301,7 @@ __global__ __launch_bounds__(kThreads, 2) void snapkv_split_kernel(BatchParams p
                 pending &= ~(1u << j);
             if (pending) {
               if (++spins > kSplitMaxSpins) {
-                __hip_atomic_store(p.error_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_fetch_or(p.error_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 gave_up = true;
                 break;
               }
