@@ -15,6 +15,16 @@ from parity_util import mlp_error_bound
 pytestmark = pytest.mark.gpu
 
 
+def _require_room(wl):
+    """A configuration that does not run is a failure, not a skip: these sizes
+    are what the benchmark reports."""
+    import torch
+    total = torch.cuda.get_device_properties(0).total_memory
+    need = wl.pool_bytes() + (10 << 30)
+    assert need <= total, "%s needs %.0f GiB of device memory, this device has %.0f GiB" % (
+        wl.name, need / 2**30, total / 2**30)
+
+
 def _oracle_pool_replay(wl):
     """The oracle's pool bookkeeping for the whole workload.  A pool array with
     zero layers makes compress_batch skip all scoring and copying and run
@@ -33,20 +43,21 @@ def _oracle_pool_replay(wl):
     return st, bt0, bt, lens
 
 
-@pytest.mark.parametrize("config,n_samples,lse", [(2, 48, False), (3, 40, False), (4, 24, False),
-                                                  (3, 16, True), (4, 16, True)])
-def test_fullsize_batch(config, n_samples, lse):
+@pytest.mark.parametrize("config,n_samples,lse,slab", [
+    (2, 48, False, True), (3, 40, False, True), (4, 24, False, True),
+    (3, 16, True, False), (4, 16, True, False)])
+def test_fullsize_batch(config, n_samples, lse, slab):
     """lse: the window rows' log-sum-exp is produced by fc_window_lse and the
     batch goes through fc_compress_batch_lse (what bench.py's configN_lse
-    workloads time); the result must still match the plain definition."""
+    workloads time); the result must still match the plain definition.
+    slab: besides the sampled units, every (request, head) of one whole layer
+    (seeded choice) is compared with the oracle element by element."""
     import torch
     from paper_2503_08461_amd import fastcache as fc
     from paper_2503_08461_amd.device_setup import DeviceWorkload
     from parity_util import check_unit_on_device
     wl = synth.make_workload(config)
-    total = torch.cuda.get_device_properties(0).total_memory
-    if wl.pool_bytes() + (10 << 30) > total:
-        pytest.skip("pool does not fit this device")
+    _require_room(wl)
     print("full-size", wl.name, "pool GiB %.1f" % (wl.pool_bytes() / 2**30), flush=True)
     dw = DeviceWorkload(wl)
     try:
@@ -120,6 +131,33 @@ def test_fullsize_batch(config, n_samples, lse):
         print("sampled units: %d, kept identical: %d, max rel score err %.2e" % (
             n_samples, same_cnt, worst), flush=True)
         assert worst < 2e-3
+
+        # one whole layer slab, every request and head of it, element by element
+        if slab:
+            l = int(rng.integers(wl.n_layers))
+            worst, same_cnt, units = 0.0, 0, 0
+            for r in range(wl.n_req):
+                L, B = int(wl.seq_lens[r]), int(wl.budgets[r])
+                so, ko = offs[r]
+                n_old, n_new = fo.blocks_for(L, 16), fo.blocks_for(B, 16)
+                # the request's part of the layer in one transfer each
+                sg_l = scores[so + l * wl.n_heads * L: so + (l + 1) * wl.n_heads * L].cpu().numpy()
+                kg_l = kept[ko + l * wl.n_heads * B: ko + (l + 1) * wl.n_heads * B].cpu().numpy()
+                q_l = dw.q[r, l].cpu().numpy() if wl.methods[r] == fo.METHOD_SNAPKV else None
+                for h in range(wl.n_heads):
+                    err, same = check_unit_on_device(
+                        dw.kv, None if q_l is None else q_l[h], bt0_o[r, :n_old], bt_o[r, :n_new],
+                        l, h, L, B, int(wl.methods[r]), wl.window, wl.pool_kernel,
+                        sg_l[h * L:(h + 1) * L], kg_l[h * B:(h + 1) * B],
+                        "(%s req %d layer %d head %d)" % (wl.name, r, l, h))
+                    worst = max(worst, err)
+                    same_cnt += int(same)
+                    units += 1
+                if r % 8 == 7:
+                    print("slab: layer %d, %d requests done" % (l, r + 1), flush=True)
+            print("whole slab of layer %d: %d units, kept identical: %d, max rel score err %.2e" % (
+                l, units, same_cnt, worst), flush=True)
+            assert units == wl.n_req * wl.n_heads and worst < 2e-3
     finally:
         dw.close()
 
@@ -135,9 +173,7 @@ def test_fullsize_chunk_mlp_config4(MLP_ACTIVATION):
     from paper_2503_08461_amd import fastcache as fc
     from paper_2503_08461_amd.device_setup import DeviceWorkload
     wl = synth.make_workload(4)
-    total = torch.cuda.get_device_properties(0).total_memory
-    if wl.pool_bytes() + (10 << 30) > total:
-        pytest.skip("pool does not fit this device")
+    _require_room(wl)
     k, hidden, d = 5, 256, wl.head_dim
     dw = DeviceWorkload(wl)
     try:
@@ -217,9 +253,7 @@ def test_fullsize_decode_attention_config4_after_compression():
     from paper_2503_08461_amd import fastcache as fc
     from paper_2503_08461_amd.device_setup import DeviceWorkload
     wl = synth.make_workload(4)
-    total = torch.cuda.get_device_properties(0).total_memory
-    if wl.pool_bytes() + (10 << 30) > total:
-        pytest.skip("pool does not fit this device")
+    _require_room(wl)
     dw = DeviceWorkload(wl)
     try:
         d = wl.head_dim
