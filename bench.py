@@ -499,7 +499,10 @@ def bench_decode(args, wl):
                    "kernel_GBps": app_bytes / (app_ms * 1e-3) / 1e9},
         "roofline": {"kernel": "decode_attention", "bound": "hbm",
                      "achieved": after["kernel_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": after["frac_of_hbm_peak"], "traffic": None},
+                     "frac": after["frac_of_hbm_peak"],
+                     "traffic": measured_traffic(wl.name, "decode_attention")[0],
+                     "traffic_source": measured_traffic(wl.name, "decode_attention")[1],
+                     "note": "the launch over the compressed caches"},
     }), flush=True)
     dw.close()
 
