@@ -120,7 +120,10 @@ int fc_pool_num_free(const fc_pool* pool);
  * Copies the free stack to host_stack (host, int32[n_blocks]; entries
  * [0, *top) are meaningful) after waiting for all device work.  Synchronous.
  * Also reports, as FC_EDEVICE, a bounded wait between workgroups that ran
- * out inside an earlier fc_compress_batch (its scores are then invalid).
+ * out inside an earlier fc_compress_batch (its scores are then invalid) and a
+ * finding of the ownership checks on a pop.  Such a condition is reported by
+ * one call (which copies nothing) and cleared; the next call succeeds unless
+ * it has happened again.
  */
 int fc_pool_export_state(fc_pool* pool, int32_t* host_stack, int* top);
 

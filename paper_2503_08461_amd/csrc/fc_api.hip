@@ -328,11 +328,15 @@ int fc_pool_export_state(fc_pool* p, int32_t* host_stack, int* top) {
   FC_HIP(hipDeviceSynchronize());
   int32_t flag = 0;
   FC_HIP(hipMemcpy(&flag, p->error_flag, sizeof(flag), hipMemcpyDeviceToHost));
-  if (flag & 0xFF)
-    return fail(FC_EDEVICE, "a bounded wait between workgroups ran out in an earlier call");
-  if (flag)
+  if (flag) {
+    // reported once: the flag starts over, so that a later export says what happened since
+    FC_HIP(launch_zero_ints(p->error_flag, 1, nullptr));
+    FC_HIP(hipDeviceSynchronize());
+    if (flag & 0xFF)
+      return fail(FC_EDEVICE, "a bounded wait between workgroups ran out in an earlier call");
     return fail(FC_EDEVICE, "ownership checks: a block that was popped off the free stack was "
                             "not free (the free list is corrupt)");
+  }
   FC_HIP(hipMemcpy(host_stack, p->stack, (size_t)p->n_blocks * sizeof(int32_t),
                    hipMemcpyDeviceToHost));
   *top = p->top;

@@ -85,6 +85,25 @@ def test_import_state_redefines_what_is_free():
         fc.fc_pool_destroy(pool)
 
 
+def test_pop_of_a_block_that_is_not_free_is_reported_once():
+    fc, torch, pool, kv = _small_pool(16)
+    try:
+        # a corrupt free list from outside: block 5 is on the stack twice
+        stack = np.arange(15, -1, -1, dtype=np.int32)
+        stack[14] = 5                                         # pops return 0, 5, 2, ...
+        fc.fc_pool_import_state(pool, stack, 16)
+        ids = fc.fc_pool_alloc(pool, 6)                       # 0, 5, 2, 3, 4, 5: the second 5 is not free
+        assert ids.cpu().tolist() == [0, 5, 2, 3, 4, 5]
+        with pytest.raises(fc.FastCacheError) as e:
+            fc.fc_pool_export_state(pool)
+        assert e.value.code == fc.FC_EDEVICE and "not free" in str(e.value)
+        # reported once; the pool itself keeps working
+        out, top = fc.fc_pool_export_state(pool)
+        assert top == 10 and (out == stack).all()
+    finally:
+        fc.fc_pool_destroy(pool)
+
+
 def _custom(L, B, method, W=16, d=64, n_heads=2, n_layers=1, seed=11):
     lens = np.array(L, dtype=np.int32)
     nb = int(sum(synth.blocks_for(int(x)) for x in lens) * 2 + 8)
