@@ -661,7 +661,9 @@ def run_stage(args, wl, cpu_seconds, lse_variant=False):
     kbytes = dw.kernel_algorithmic_bytes(args.score_mode, args.split_threshold)
     # dominant kernel = the one with the largest average duration
     dom = max(kbytes, key=lambda k: kavg.get(k, 0.0))
-    dom_gbps = kbytes[dom] / (kavg[dom] * 1e-3) / 1e9
+    # (a batch issued as several calls launches the kernel once per call:
+    # the average launch moves that share of the bytes)
+    dom_gbps = kbytes[dom] / dw.parts / (kavg[dom] * 1e-3) / 1e9
     traffic, traffic_source = measured_traffic(wl.name, dom)
     if args.score_mode != "auto" or args.split_threshold != 0:
         traffic, traffic_source = None, "counters are kept for the default scheduling only"
