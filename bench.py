@@ -533,6 +533,9 @@ def main():
                     help="CPU time budget of the oracle baseline (0 = skip)")
     ap.add_argument("--score-mode", default="auto", choices=["auto", "two_pass", "one_pass"],
                     help="which SnapKV score kernel the library uses")
+    ap.add_argument("--score-pruning", type=int, default=0, choices=[0, 1],
+                    help="1: fc_set_score_pruning (the fused kernel bounds the column sums in its "
+                         "first pass over K and re-reads only the rows that can decide the selection)")
     ap.add_argument("--split-threshold", type=int, default=0,
                     help="auto scheduling: SnapKV requests of at least this many tokens take "
                          "the token-split one-pass score kernel (0, the library's default: none)")
@@ -614,6 +617,7 @@ def run_stage(args, wl, cpu_seconds, lse_variant=False):
     dw = DeviceWorkload(wl, verbose=True)
     fc.fc_set_score_mode(dw.pool, {"auto": 0, "two_pass": 1, "one_pass": 2}[args.score_mode])
     fc.fc_set_split_threshold(dw.pool, args.split_threshold)
+    fc.fc_set_score_pruning(dw.pool, bool(args.score_pruning))
     fc.fc_set_profiling(dw.pool, True)
     lse_ms = None
     if args.workload.endswith("_precall70"):

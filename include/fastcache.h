@@ -383,6 +383,18 @@ int fc_set_score_mode(fc_pool* pool, int mode);
 int fc_set_split_threshold(fc_pool* pool, int min_tokens);
 
 /*
+ * Pruned second pass of the SnapKV-style score (Algorithm 1, "Batch
+ * compression"; the selection only needs exact scores near its threshold).
+ * With enable != 0, the fused kernel of the default scheduling bounds every
+ * column sum during its first pass over K and re-reads only the key rows whose
+ * exact score can still decide the selection; the kept sets, the compacted
+ * caches and the pool are exactly what the two-pass path produces.  It applies
+ * to calls that do not ask for the scores (dev_scores_out == NULL) and do not
+ * bring the row log-sum-exps; all other calls are unaffected.
+ */
+int fc_set_score_pruning(fc_pool* pool, int enable);
+
+/*
  * Per-kernel timing for benchmarks.  With profiling enabled every kernel
  * launched by fc_compress_batch is bracketed by HIP events on the call's
  * stream; the events of the last 32 calls are kept.  fc_get_kernel_times

@@ -156,6 +156,7 @@ struct fc_pool {
   int split_min_len = 0;          // FC_SCORE_AUTO: heads at least this long take it (0: none)
   int32_t* error_flag = nullptr;  // device, one int, zero unless a bounded wait ran out
   int score_mode = FC_SCORE_AUTO;
+  bool score_pruning = false;      // the fused kernel prunes the second pass of SnapKV units
   int n_sink = 4;
   int compact_mode = FC_COMPACT_FRESH;
   // chunk-MLP compressor weights in operand order (library-owned)
@@ -395,6 +396,12 @@ int fc_set_debug_checks(fc_pool* p, int enable) {
   return FC_OK;
 }
 
+int fc_set_score_pruning(fc_pool* p, int enable) {
+  if (!p) return fail(FC_EINVAL, "pool is NULL");
+  p->score_pruning = enable != 0;
+  return FC_OK;
+}
+
 int fc_set_split_threshold(fc_pool* p, int min_tokens) {
   if (!p) return fail(FC_EINVAL, "pool is NULL");
   if (min_tokens < 0) return fail(FC_EINVAL, "min_tokens < 0");
@@ -573,7 +580,11 @@ int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_blocks_pe
     // (growth waits for the device and frees: it happens before anything is queued)
     if (!dev_kept_out && (rc = grow(&p->kept, &p->kept_cap, plan.kept_entries)) != FC_OK) return rc;
     if ((rc = grow(&p->ids, &p->ids_cap, n_ids)) != FC_OK) return rc;
-    if ((rc = grow(&p->raw_scores, &p->raw_cap, plan.raw_floats)) != FC_OK) return rc;
+    // (the pruned second pass keeps three per-tile sums per token, 8 bytes, in the score scratch)
+    const bool bounded_call = p->score_pruning && !dev_scores_out && !need_lse;
+    if ((rc = grow(&p->raw_scores, &p->raw_cap,
+                   std::max(plan.raw_floats, bounded_call ? 2 * plan.score_entries : (size_t)0))) != FC_OK)
+      return rc;
     if (!plan.split_launches.empty() &&
         (rc = grow(&p->split_xchg, &p->split_xchg_cap, (size_t)2 * plan.split_grid_max * 64)) != FC_OK)
       return rc;
@@ -631,6 +642,7 @@ int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_blocks_pe
   bp.kept = kept_buf;
   bp.error_flag = p->error_flag;
   bp.owner = p->debug_checks ? p->owner : nullptr;
+  bp.bounded = (p->score_pruning && !dev_scores_out && !need_lse && !no_alloc) ? 1 : 0;
 
   if (p->debug_checks) {
     // the table rows that the stage will release: every id in range, handed out, named once

@@ -20,6 +20,20 @@ __device__ __forceinline__ int clamp_block(int blk, int n_blocks) {
   return ((unsigned)blk < (unsigned)n_blocks) ? blk : 0;
 }
 
+// v + (the same register of another lane of the 16-lane row), by DPP control
+template <int CTRL>
+__device__ __forceinline__ float add_across_row(float v) {
+  return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+// sum over the 16 lanes of a row, left in every one of them
+__device__ __forceinline__ float row16_sum(float v) {
+  v = add_across_row<0xB1>(v);   // quad_perm [1,0,3,2]
+  v = add_across_row<0x4E>(v);   // quad_perm [2,3,0,1]
+  v = add_across_row<0x141>(v);  // row_half_mirror: lane i <-> 7 - i of each 8
+  v = add_across_row<0x140>(v);  // row_mirror: lane i <-> 15 - i
+  return v;
+}
+
 __device__ __forceinline__ half8 load_half8(const _Float16* p) {
   return *reinterpret_cast<const half8*>(p);
 }

@@ -79,6 +79,7 @@ struct BatchParams {
   int32_t split_team;          // workgroups that share one (layer, head) in this launch
   uint64_t* split_xchg;        // [2][grid][64] tagged (max, sum) pairs, zeroed before the launch
   int32_t* error_flag;         // set if a bounded wait ran out or an ownership check failed
+  int32_t bounded;             // 1: the fused kernel prunes the second pass of its SnapKV units
   int32_t* owner;              // ownership checks (debug mode): [n_blocks] 0 free, 1 handed out,
                                // 2 being released; NULL when the checks are off
 };

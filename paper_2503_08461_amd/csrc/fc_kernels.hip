@@ -170,6 +170,20 @@ __global__ __launch_bounds__(kThreads) void reclaim_kernel(BatchParams p) {
 // The un-pooled column sums of the prefix are written to raw_scores; pooling
 // and the forced window are applied by the select kernel.
 
+// Epochs of the bound-keeping first pass: wavefront w takes blocks w, w + kWaves,
+// ...; its t-th block belongs to epoch 0 (t = 0), 1 (t = 1), 2 (t = 2, 3) and
+// then to 2 + t / 4: the references are renewed before t = 1, 2 and every
+// multiple of 4, by all wavefronts together.
+static constexpr int kBoundSeg = 4;
+static constexpr int kBoundMinLen = 2048;  // shorter heads take the two passes
+static constexpr int kBoundMaxEpochs = 3 + (kFusedMaxLen / 16 / kWaves + kBoundSeg - 1) / kBoundSeg;
+__host__ __device__ constexpr int bound_epoch_of_step(int t) {
+  return t < 2 ? t : (t < kBoundSeg ? 2 : 2 + t / kBoundSeg);
+}
+__host__ __device__ constexpr bool bound_renews_before(int t) {
+  return t == 1 || t == 2 || (t >= kBoundSeg && t % kBoundSeg == 0);
+}
+
 struct ScoreShared {
   float m[kWaves][4][64];
   float z[kWaves][4][64];
@@ -179,22 +193,17 @@ struct ScoreShared {
 // Scores one (request, layer, head); store(j, a_j) receives the un-pooled
 // column sum of every prefix token j.  All threads of the workgroup call.
 // `old_ids` are the request's pre-compression block ids (global or LDS copy).
-template <int D, int NT, typename Store>
-__device__ __forceinline__ void snapkv_unit(const BatchParams& p, const ReqDesc& rd, int lh,
-                                            const int32_t* old_ids, ScoreShared& sh, Store store) {
+// The window queries of a (request, layer, head) in MFMA operand layout (rows
+// past the window are zero), resident in registers for every pass over K.
+template <int D, int NT>
+__device__ __forceinline__ void load_window_queries(const BatchParams& p, const ReqDesc& rd, int lh,
+                                                    half8 (&qreg)[NT][D / 32]) {
   constexpr int KS = D / 32;
-  const int layer = lh / p.n_heads;
-  const int head = lh - layer * p.n_heads;
-  const int L = rd.seq_len;
-  const int W = rd.window;  // <= 16 NT; the rows past it are padding
   const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int c16 = lane & 15;
   const int q4 = lane >> 4;
-
-  // window queries, resident in registers for both passes
+  const int W = rd.window;
   const _Float16* qbase = p.q_window + rd.q_off + (size_t)lh * W * D;
-  half8 qreg[NT][KS];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
     const int row = nt * 16 + c16;
@@ -204,6 +213,21 @@ __device__ __forceinline__ void snapkv_unit(const BatchParams& p, const ReqDesc&
       qreg[nt][ks] = (row < W) ? load_half8(qbase + (size_t)row * D + ks * 32 + q4 * 8) : z;
     }
   }
+}
+
+template <int D, int NT, typename Store>
+__device__ __forceinline__ void snapkv_unit_q(const BatchParams& p, const ReqDesc& rd, int lh,
+                                              const int32_t* old_ids, ScoreShared& sh,
+                                              half8 (&qreg)[NT][D / 32], Store store) {
+  constexpr int KS = D / 32;
+  const int layer = lh / p.n_heads;
+  const int head = lh - layer * p.n_heads;
+  const int L = rd.seq_len;
+  const int W = rd.window;  // <= 16 NT; the rows past it are padding
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int c16 = lane & 15;
+  const int q4 = lane >> 4;
 
   const size_t blk_stride = (size_t)2 * p.n_heads * 16 * D;
   const _Float16* kbase = p.kv + (size_t)layer * p.n_blocks * blk_stride +
@@ -346,6 +370,14 @@ __device__ __forceinline__ void snapkv_unit(const BatchParams& p, const ReqDesc&
       for (int ks = 0; ks < KS; ++ks) kc[ks] = kn[ks];
     }
   }
+}
+
+template <int D, int NT, typename Store>
+__device__ __forceinline__ void snapkv_unit(const BatchParams& p, const ReqDesc& rd, int lh,
+                                            const int32_t* old_ids, ScoreShared& sh, Store store) {
+  half8 qreg[NT][D / 32];
+  load_window_queries<D, NT>(p, rd, lh, qreg);
+  snapkv_unit_q<D, NT>(p, rd, lh, old_ids, sh, qreg, store);
 }
 
 template <int D, int NT>
@@ -701,6 +733,464 @@ __device__ __forceinline__ void select_unit(const BatchParams& p, const ReqDesc&
   }
 }
 
+// ---------------------------------------------------------------------------
+// SnapKV-style score with a pruned second pass
+// ---------------------------------------------------------------------------
+//
+// The second pass over K only serves the selection, and the selection only
+// needs exact column sums near its threshold.  The first pass can bound every
+// column sum: it accumulates the soft-max numerators 2^(logit - ref_i) against a
+// per-row reference ref_i that is known when the token is read (log2 of the
+// row's sum over what the workgroup has read so far, renewed at fixed steps by
+// all wavefronts together), so the exact weight of logit (i, j) is that
+// numerator times rho_i = 2^(ref_i - lse_i) <= 1, a factor that is only known at
+// the end but is the same for every token of an epoch.  With c_j^g the sum of a
+// token's numerators over the rows of the g-th 16-row tile of the window,
+//     sum_g c_j^g min_(i in g) rho_i  <=  a_j  <=  sum_g c_j^g max_(i in g) rho_i .
+// (The sum over all rows stays in LDS, the per-tile sums but one go through a
+// scratch buffer in HBM: 12 bytes per token written and read once, against 256
+// bytes per row that is not re-read.)
+// After the pass: bounds of the max-pooled scores, a lower and an upper bound of
+// the selection threshold from two histograms, and the tokens whose pooled
+// interval contains neither are decided without a second look.  For the others
+// the tokens of their pooling window that can carry the maximum are re-scored
+// exactly, row by row (256 bytes each), and everything else keeps its upper
+// bound: the plain selection that follows then returns exactly the set it
+// would return from exact scores (a decided-out token stays below the
+// threshold, a decided-in one above it, an undecided one carries its exact
+// pooled score; ties can only occur among those).
+//
+// The scores themselves are not produced (callers that ask for them take the
+// two-pass path).  A reference can be overtaken by more than the fp32 exponent
+// range only by inputs far outside any attention layer; the numerators then
+// overflow, the row's log-sum-exp is not finite, and the head falls back to
+// the two-pass code.
+
+typedef _Float16 half4v __attribute__((ext_vector_type(4)));
+
+struct BoundShared {
+  float fin[64];                   // log2 of every row's soft-max denominator
+  float pub[2][kWaves][64];        // the wavefronts' row sums at a renewal, absolute log2
+  float ref[kBoundMaxEpochs][64];  // the reference of every epoch
+};
+
+struct BoundKeep {                    // what survives into the selection's LDS
+  float rmax[kBoundMaxEpochs][4];     // largest factor of an epoch over the rows of a 16-row tile
+  float rmin[kBoundMaxEpochs][4];     // smallest
+  int bad;                            // a row's log-sum-exp is not finite: fall back
+};
+
+// A token's bounds share one 32-bit word of LDS: the upper bound rounded up to
+// its leading 16 bits, the lower bound rounded down to its leading 16 bits
+// (both are non-negative floats).  0.8 % of slack against bounds that are tens
+// of per cent apart.
+__device__ __forceinline__ uint32_t pack_bounds(float lo, float hi) {
+  const uint32_t h = (__float_as_uint(hi) + 0xFFFFu) >> 16;
+  const uint32_t l = __float_as_uint(lo) >> 16;
+  return (h << 16) | l;
+}
+__device__ __forceinline__ float upper_of(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+__device__ __forceinline__ float lower_of(uint32_t w) { return __uint_as_float(w << 16); }
+
+__device__ __forceinline__ int bound_epoch_of_token(int j) {
+  return bound_epoch_of_step((j >> 4) / kWaves);
+}
+
+// First pass with bounds.  On return stage[j] holds the packed bounds of the
+// column sum of every prefix token j and bs.fin the rows' log-sum-exps.  aux:
+// room for L - W entries of four halves (the sums of tiles 1..3) of this head in HBM.  All threads of the
+// workgroup call; ends with a barrier.
+template <int D, int NT>
+__device__ __forceinline__ void snapkv_bounds(const BatchParams& p, const ReqDesc& rd, int lh,
+                                              const int32_t* old_ids, BoundShared& bs,
+                                              BoundKeep& keep, float* stage, half4v* aux,
+                                              half8 (&qreg)[NT][D / 32]) {
+  constexpr int KS = D / 32;
+  const int layer = lh / p.n_heads;
+  const int head = lh - layer * p.n_heads;
+  const int L = rd.seq_len;
+  const int W = rd.window;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int c16 = lane & 15;
+  const int q4 = lane >> 4;
+  const size_t blk_stride = (size_t)2 * p.n_heads * 16 * D;
+  const _Float16* kbase = p.kv + (size_t)layer * p.n_blocks * blk_stride +
+                          (size_t)head * 16 * D + (size_t)c16 * D + q4 * 8;
+  const float c = p.scale_log2e;
+  const int nb = (L + 15) >> 4;
+  const int n_prefix = L - W;
+  const int n_unmasked = n_prefix >> 4;
+  auto load_block = [&](int b, half8 (&k)[KS]) {
+    const int blk = clamp_block(old_ids[b], p.n_blocks);
+    const _Float16* kp = kbase + (size_t)blk * blk_stride;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) k[ks] = load_half8(kp + ks * 32);
+  };
+
+  float ref[NT], zacc[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    ref[nt] = 0.f;
+    zacc[nt] = 0.f;
+  }
+  // the wavefront's row sums in absolute log2 units -> pub[buf]
+  auto publish = [&](int buf) {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      float zr = zacc[nt];
+      zr += __shfl_xor(zr, 16);
+      zr += __shfl_xor(zr, 32);
+      if (q4 == 0) bs.pub[buf][wave][nt * 16 + c16] = zr > 0.f ? ref[nt] + log2f(zr) : -INFINITY;
+    }
+  };
+  // log2 of the workgroup's row sum from the published shares; own = this wavefront's share
+  auto merged = [&](int buf, int row, float& own) {
+    float l[kWaves];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      l[w] = bs.pub[buf][w][row];
+      mx = fmaxf(mx, l[w]);
+    }
+    own = l[0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) own = wave == w ? l[w] : own;
+    if (mx == -INFINITY) return 0.f;  // nothing visible yet: any finite reference will do
+    float zz = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) zz += __builtin_amdgcn_exp2f(l[w] - mx);
+    return mx + log2f(zz);
+  };
+
+  const int T = (nb + kWaves - 1) / kWaves;  // steps; every wavefront walks all of them
+  int epoch = 0, buf = 0;
+  half8 kc[KS], kn[KS];
+  if (wave < nb) load_block(wave, kc);
+  for (int t = 0; t < T; ++t) {
+    const int b = wave + kWaves * t;
+    if (b + kWaves < nb) load_block(b + kWaves, kn);
+    if (bound_renews_before(t)) {  // uniform over the workgroup
+      publish(buf);
+      __syncthreads();
+      ++epoch;
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const int row = nt * 16 + c16;
+        float own;
+        const float nr = merged(buf, row, own);
+        zacc[nt] = (q4 == 0 && own > -INFINITY) ? __builtin_amdgcn_exp2f(own - nr) : 0.f;
+        ref[nt] = nr;
+        if (wave == 0 && q4 == 0) bs.ref[epoch][row] = nr;
+      }
+      buf ^= 1;  // the other buffer is written next: its readers passed a barrier since
+    }
+    if (b < nb) {  // uniform per wavefront
+      float col[NT][4];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(kc[ks], qreg[nt][ks], acc, 0, 0, 0);
+        float tv[4];
+        const bool row_ok = nt * 16 + c16 < W;  // padded rows carry no weight
+#pragma unroll
+        for (int r = 0; r < 4; ++r) tv[r] = row_ok ? acc[r] * c : -INFINITY;
+        if (b >= n_unmasked) {
+          const int limit = L - W + nt * 16 + c16;
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            if (b * 16 + q4 * 4 + r > limit) tv[r] = -INFINITY;
+        }
+        if (t == 0) {
+          // no reference yet: the block's own row maximum (these tokens get the
+          // trivial bounds, whatever they accumulate here)
+          float bm = fmaxf(fmaxf(tv[0], tv[1]), fmaxf(tv[2], tv[3]));
+          bm = fmaxf(bm, __shfl_xor(bm, 16));
+          bm = fmaxf(bm, __shfl_xor(bm, 32));
+          ref[nt] = bm == -INFINITY ? 0.f : bm;
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float e = __builtin_amdgcn_exp2f(tv[r] - ref[nt]);
+          zacc[nt] += e;
+          col[nt][r] = e;
+        }
+      }
+      // sums over the 16 rows of every tile (the lanes of a row of 16); lane
+      // c16 < 4 of each row keeps those of token 4 q4 + c16
+      float mine[NT];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        mine[nt] = 0.f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float v = row16_sum(col[nt][r]);
+          mine[nt] = c16 == r ? v : mine[nt];
+        }
+      }
+      const int tok = b * 16 + q4 * 4 + c16;
+      if (c16 < 4 && tok < n_prefix) {
+        float total = 0.f;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) total += mine[nt];
+        stage[tok] = total;
+        if (NT > 1) {
+          half4v hv = {0, 0, 0, 0};
+#pragma unroll
+          for (int nt = 1; nt < NT; ++nt) hv[nt - 1] = (_Float16)mine[nt];
+          aux[tok] = hv;  // 16 lanes x 8 bytes: one full line per block
+        }
+      }
+    }
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) kc[ks] = kn[ks];
+  }
+  publish(buf);
+  __syncthreads();
+  if (threadIdx.x < 64) {
+    const int row = threadIdx.x;
+    float own;
+    const float lse = merged(buf, row, own);
+    bs.fin[row] = row < W ? lse : INFINITY;  // padded rows contribute exp2(-inf) = 0
+    if (row < W && !(fabsf(lse) < 3.0e38f)) keep.bad = 1;
+  }
+  __syncthreads();
+  // the factor range of every epoch and tile: rho_i = 2^(ref_i - lse_i), i in the tile
+  for (int e = 1 + wave; e <= epoch; e += kWaves) {
+    const bool ok = lane < W;
+    const float rho = ok ? __builtin_amdgcn_exp2f(bs.ref[e][lane] - bs.fin[lane]) : 0.f;
+    float lo = ok ? rho : INFINITY, hi = rho;
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) {
+      lo = fminf(lo, __shfl_xor(lo, o));
+      hi = fmaxf(hi, __shfl_xor(hi, o));
+    }
+    if (c16 == 0) {
+      // (margins far above the rounding of the numerators, the sums and the factors;
+      // a tile without window rows carries no weight at all)
+      keep.rmax[e][q4] = hi * 1.0002f;
+      keep.rmin[e][q4] = lo == INFINITY ? 0.f : lo * 0.9998f;
+    }
+  }
+  __syncthreads();
+  // per token: the tiles' sums -> bounds, packed in place
+  {
+    const float trivial = (float)W;  // every row contributes at most 1
+    // (four tokens per thread at a time, so that their loads from the scratch travel together)
+    for (int j0 = threadIdx.x; j0 < n_prefix; j0 += 4 * kThreads) {
+      half4v v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const half4v z = {0, 0, 0, 0};
+        v[u] = NT > 1 ? aux[min(j0 + u * kThreads, n_prefix - 1)] : z;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int j = j0 + u * kThreads;
+        if (j >= n_prefix) break;
+        const int e = bound_epoch_of_token(j);
+        float lo = 0.f, hi = trivial;
+        if (e > 0) {
+          const float total = stage[j];
+          float rest = total, l = 0.f, h = 0.f;
+#pragma unroll
+          for (int nt = 1; nt < NT; ++nt) {
+            // (a tile's sum went through fp16: 2^-11 relative, or flushed below 6e-8)
+            const float x = (float)v[u][nt - 1];
+            rest -= x;
+            l += x * 0.999f * keep.rmin[e][nt];
+            h += (x * 1.001f + 1.0e-7f) * keep.rmax[e][nt];
+          }
+          // tile 0 by subtraction: off by the roundings of the others at most
+          const float slack = total * 1.0e-3f + 3.0e-7f;
+          l += fmaxf(rest - slack, 0.f) * keep.rmin[e][0];
+          h += (fmaxf(rest, 0.f) + slack) * keep.rmax[e][0];
+          lo = l;
+          hi = fminf(h, trivial);
+        }
+        reinterpret_cast<uint32_t*>(stage)[j] = pack_bounds(lo, hi);
+      }
+    }
+  }
+  __syncthreads();
+}
+
+// Exact column sums of the tokens named by need[] (one bit per prefix token),
+// row by row -> stage[].  mrow: the rows' log-sum-exps as the second product
+// leaves the rows in registers.
+template <int D, int NT>
+__device__ __forceinline__ void snapkv_rescore(const BatchParams& p, const ReqDesc& rd, int lh,
+                                               const int32_t* old_ids, const uint32_t* need,
+                                               float* stage, half8 (&qreg)[NT][D / 32],
+                                               const float (&mrow)[NT][4]) {
+  constexpr int KS = D / 32;
+  const int layer = lh / p.n_heads;
+  const int head = lh - layer * p.n_heads;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int c16 = lane & 15;
+  const int q4 = lane >> 4;
+  const size_t blk_stride = (size_t)2 * p.n_heads * 16 * D;
+  const _Float16* base = p.kv + (size_t)layer * p.n_blocks * blk_stride + (size_t)head * 16 * D + q4 * 8;
+  const float c = p.scale_log2e;
+  const int n_prefix = rd.seq_len - rd.window;
+  const int n_words = (n_prefix + 31) >> 5;
+  // Tiles of 16 named tokens (a wavefront walks its words of the bit map and
+  // fills a tile across them), the rows of the next tile requested before this
+  // one is multiplied.
+  int w = wave - kWaves;
+  uint32_t bits = 0u;
+  auto next_tile = [&](int& tok) -> bool {  // uniform over the wavefront
+    tok = -1;
+    int filled = 0;
+    while (filled < 16) {
+      while (bits == 0u) {
+        w += kWaves;
+        if (w >= n_words) return filled > 0;
+        bits = __builtin_amdgcn_readfirstlane(need[w]);
+      }
+#pragma unroll 1
+      for (; filled < 16 && bits; ++filled) {
+        const int pos = __ffs(bits) - 1;
+        bits &= bits - 1;
+        tok = c16 == filled ? (w << 5) + pos : tok;
+      }
+    }
+    return true;
+  };
+  auto load_rows = [&](int tok, half8 (&k)[KS]) {
+    // (a lane without a token reads the head's first row and drops the result)
+    const int tk = max(tok, 0);
+    const int blk = clamp_block(old_ids[tk >> 4], p.n_blocks);
+    const _Float16* kp = base + (size_t)blk * blk_stride + (size_t)(tk & 15) * D;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) k[ks] = load_half8_nt(kp + ks * 32);
+  };
+  half8 kc[KS], kn[KS];
+  int tok_c = -1, tok_n = -1;
+  bool have = next_tile(tok_c);
+  if (have) load_rows(tok_c, kc);
+  while (have) {
+    const bool more = next_tile(tok_n);
+    if (more) load_rows(tok_n, kn);
+    float colsum = 0.f;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qreg[nt][ks], kc[ks], acc, 0, 0, 0);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) colsum += __builtin_amdgcn_exp2f(acc[r] * c - mrow[nt][r]);
+    }
+    colsum += __shfl_xor(colsum, 16);
+    colsum += __shfl_xor(colsum, 32);
+    if (q4 == 0 && tok_c >= 0) stage[tok_c] = colsum;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) kc[ks] = kn[ks];
+    tok_c = tok_n;
+    have = more;
+  }
+}
+
+// Between the two: which prefix tokens need their exact column sum.  stage[]
+// holds the packed bounds; need[] is set.
+__device__ __forceinline__ void bound_classify(const ReqDesc& rd, const float* stage_f,
+                                               uint32_t* need, SelectShared& sh) {
+  const uint32_t* stage = reinterpret_cast<const uint32_t*>(stage_f);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n_sel = rd.seq_len - rd.window;
+  const int k_sel = rd.budget - rd.window;
+  const int h = rd.pool_kernel >> 1;
+  float vmax = 0.f;
+  for (int j = tid; j < n_sel; j += kThreads) vmax = fmaxf(vmax, upper_of(stage[j]));
+  for (int j = tid; j < ((n_sel + 31) >> 5); j += kThreads) need[j] = 0u;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) vmax = fmaxf(vmax, __shfl_xor(vmax, o));
+  if (lane == 0) sh.wmax[wave] = __float_as_uint(vmax);
+  __syncthreads();
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) vmax = fmaxf(vmax, __uint_as_float(sh.wmax[w]));
+  if (k_sel <= 0 || k_sel >= n_sel) return;  // uniform: window only, or everything is kept
+  auto pooled = [&](int j, float& plo, float& phi) {
+    const int a = max(0, j - h), b = min(n_sel - 1, j + h);
+    plo = 0.f;
+    phi = 0.f;
+    for (int k = a; k <= b; ++k) {
+      const uint32_t w = stage[k];
+      phi = fmaxf(phi, upper_of(w));
+      plo = fmaxf(plo, lower_of(w));
+    }
+  };
+  // thresholds: the buckets that hold the k_sel-th largest lower and the k_sel-th
+  // largest upper bound (two histograms from one evaluation of the pooled bounds)
+  const uint32_t kmin = score_key(0.f), kmax = score_key(vmax);
+  const int shift = kmax > kmin ? max(0, 32 - __clz(kmax - kmin) - kBucketBits) : 0;
+  int* hist_lo = sh.hist;
+  int* hist_hi = reinterpret_cast<int*>(sh.cand);
+  static_assert(kMaxCand >= kBuckets, "the candidate list doubles as the second histogram");
+#pragma unroll
+  for (int i = 0; i < kBuckets / kThreads; ++i) {
+    hist_lo[tid + i * kThreads] = 0;
+    hist_hi[tid + i * kThreads] = 0;
+  }
+  __syncthreads();
+  for (int j = tid; j < n_sel; j += kThreads) {
+    float plo, phi;
+    pooled(j, plo, phi);
+    atomicAdd(&hist_lo[(score_key(plo) - kmin) >> shift], 1);
+    atomicAdd(&hist_hi[(score_key(phi) - kmin) >> shift], 1);
+  }
+  __syncthreads();
+  // the bucket of the k_sel-th largest entry of a histogram -> sel[which]
+  auto kth_bucket = [&](const int* hist, int which) {
+    int own[kBuckets / kThreads];
+    int sum = 0;
+#pragma unroll
+    for (int i = 0; i < kBuckets / kThreads; ++i) {
+      own[i] = hist[tid * (kBuckets / kThreads) + i];
+      sum += own[i];
+    }
+    int v = sum;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int t = __shfl_up(v, o);
+      if (lane >= o) v += t;
+    }
+    if (lane == 63) sh.wsum[wave] = v;
+    __syncthreads();
+    int before = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      if (w < wave) before += sh.wsum[w];
+      total += sh.wsum[w];
+    }
+    int above = total - (v + before);  // entries in buckets above this thread's
+#pragma unroll
+    for (int i = kBuckets / kThreads - 1; i >= 0; --i) {
+      if (above < k_sel && above + own[i] >= k_sel) sh.sel[which] = tid * (kBuckets / kThreads) + i;
+      above += own[i];
+    }
+    __syncthreads();
+  };
+  kth_bucket(hist_lo, 0);
+  kth_bucket(hist_hi, 1);
+  const uint32_t t_lo = kmin + ((uint32_t)sh.sel[0] << shift);               // <= the threshold's key
+  const uint32_t t_hi = kmin + (((uint32_t)sh.sel[1] + 1u) << shift) - 1u;  // >= the threshold's key
+  for (int j = tid; j < n_sel; j += kThreads) {
+    float plo, phi;
+    pooled(j, plo, phi);
+    if (score_key(phi) >= t_lo && score_key(plo) <= t_hi) {
+      const int a = max(0, j - h), b = min(n_sel - 1, j + h);
+      for (int k = a; k <= b; ++k)
+        if (upper_of(stage[k]) >= plo) atomicOr(&need[k >> 5], 1u << (k & 31));
+    }
+  }
+  __syncthreads();
+}
+
 __global__ __launch_bounds__(kThreads) void select_kernel(BatchParams p) {
   extern __shared__ uint32_t keys[];
   __shared__ SelectShared sh;
@@ -843,6 +1333,72 @@ __global__ __launch_bounds__(kThreads) void fused_unit_kernel(BatchParams p) {
     if (snap) {
       if constexpr (NT > 0)
         snapkv_unit<D, NT>(p, rd, lh, sm_ids, sh.score, [&](int j, float v) { stage[j] = v; });
+    } else {
+      knorm_unit<D>(p, rd, lh, sm_ids, [&](int j, float v) { stage[j] = v; });
+    }
+    __syncthreads();
+    select_unit<true>(p, rd, lh, keys, sh.select);
+  }
+  __syncthreads();  // the kept list (global memory, this workgroup's own) is complete
+  gather_unit<D>(p, rd, lh, ids_in_lds ? sm_ids : p.old_ids + rd.old_off);
+}
+
+// The fused kernel with the pruned second pass for its SnapKV units (see
+// snapkv_bounds); key-norm and streaming units that ride in the launch run as in
+// fused_unit_kernel.  Dynamic LDS: seq_len words of scores, then one bit per token.
+template <int D, int NT>
+__global__ __launch_bounds__(kThreads, 3) void fused_bounded_kernel(BatchParams p) {  // 3 wavefronts per SIMD
+  extern __shared__ uint32_t keys[];
+  __shared__ union {
+    ScoreShared score;
+    SelectShared select;
+    BoundShared bound;
+  } sh;
+  __shared__ BoundKeep keep;
+  const int n_lh = p.n_layers * p.n_heads;
+  const int slot = blockIdx.x / n_lh;
+  const int lh = blockIdx.x - slot * n_lh;
+  const ReqDesc rd = p.descs[p.order_fused[slot]];
+  float* stage = reinterpret_cast<float*>(keys);
+  uint32_t* need = keys + ((rd.seq_len + 31) & ~31);
+  __shared__ int32_t sm_ids[kFusedMaxLen / 16];
+  const bool ids_in_lds = rd.n_old <= kFusedMaxLen / 16;  // streaming units may be longer
+  if (ids_in_lds)
+    for (int i = threadIdx.x; i < rd.n_old; i += kThreads)
+      sm_ids[i] = clamp_block(p.old_ids[rd.old_off + i], p.n_blocks);
+  if (threadIdx.x == 0) keep.bad = 0;
+  __syncthreads();
+  if (rd.method == 3 /* FC_METHOD_STREAMING */) {  // uniform per workgroup
+    streaming_unit(p, rd, lh);
+  } else {
+    if (rd.method == 1 /* FC_METHOD_SNAPKV */) {
+      constexpr int KS = D / 32;
+      const int q4 = (threadIdx.x & 63) >> 4;
+      half8 qreg[NT][KS];
+      load_window_queries<D, NT>(p, rd, lh, qreg);
+      // (room for the per-tile sums: 8 bytes per token of the call behind p.raw_scores)
+      half4v* aux = reinterpret_cast<half4v*>(p.raw_scores) + (size_t)rd.score_off + (size_t)lh * rd.seq_len;
+      // Short heads and generous budgets gain nothing (the first blocks of a head
+      // have no useful bounds, and with half of the tokens kept most pooled
+      // intervals straddle the threshold): they take the two passes.
+      const bool prune = rd.seq_len >= kBoundMinLen && 2 * rd.budget <= rd.seq_len;  // uniform
+      if (prune) snapkv_bounds<D, NT>(p, rd, lh, sm_ids, sh.bound, keep, stage, aux, qreg);
+      if (!prune || keep.bad) {  // bad: not representable against a running reference
+        snapkv_unit_q<D, NT>(p, rd, lh, sm_ids, sh.score, qreg, [&](int j, float v) { stage[j] = v; });
+      } else {
+        float mrow[NT][4];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) mrow[nt][r] = sh.bound.fin[nt * 16 + q4 * 4 + r];
+        __syncthreads();  // the log-sum-exps are in registers: the selection's LDS may take over
+        bound_classify(rd, stage, need, sh.select);
+        __syncthreads();
+        // every token not named keeps its upper bound as its value
+        for (int j = threadIdx.x; j < rd.seq_len - rd.window; j += kThreads)
+          if (!((need[j >> 5] >> (j & 31)) & 1u)) stage[j] = upper_of(keys[j]);
+        snapkv_rescore<D, NT>(p, rd, lh, sm_ids, need, stage, qreg, mrow);
+      }
     } else {
       knorm_unit<D>(p, rd, lh, sm_ids, [&](int j, float v) { stage[j] = v; });
     }
@@ -996,6 +1552,16 @@ hipError_t launch_select(const BatchParams& p, int max_seq_len, hipStream_t s) {
 template <int D>
 static hipError_t launch_fused_d(const BatchParams& p, bool any_snap, size_t lds, hipStream_t s) {
   const unsigned grid = (unsigned)p.n_fused * p.n_layers * p.n_heads;
+  if (any_snap && p.bounded) {
+    switch ((p.window + 15) / 16) {
+      case 1: fused_bounded_kernel<D, 1><<<grid, kThreads, lds, s>>>(p); break;
+      case 2: fused_bounded_kernel<D, 2><<<grid, kThreads, lds, s>>>(p); break;
+      case 3: fused_bounded_kernel<D, 3><<<grid, kThreads, lds, s>>>(p); break;
+      case 4: fused_bounded_kernel<D, 4><<<grid, kThreads, lds, s>>>(p); break;
+      default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+  }
   switch (any_snap ? (p.window + 15) / 16 : 0) {
     case 0: fused_unit_kernel<D, 0><<<grid, kThreads, lds, s>>>(p); break;
     case 1: fused_unit_kernel<D, 1><<<grid, kThreads, lds, s>>>(p); break;
@@ -1009,7 +1575,10 @@ static hipError_t launch_fused_d(const BatchParams& p, bool any_snap, size_t lds
 
 hipError_t launch_fused(const BatchParams& p, bool any_snap, int max_seq_len, hipStream_t s) {
   if (p.n_fused == 0) return hipSuccess;
-  const size_t lds = (size_t)max_seq_len * sizeof(uint32_t);
+  // (with the pruned second pass: one bit per token behind the scores)
+  const size_t lds = p.bounded && any_snap
+                         ? ((size_t)((max_seq_len + 31) & ~31) + (size_t)((max_seq_len + 31) >> 5)) * sizeof(uint32_t)
+                         : (size_t)max_seq_len * sizeof(uint32_t);
   if (p.head_dim == 128) return launch_fused_d<128>(p, any_snap, lds, s);
   if (p.head_dim == 64) return launch_fused_d<64>(p, any_snap, lds, s);
   return hipErrorInvalidValue;

@@ -29,7 +29,7 @@ EXPORTS = [
     "fc_compress_batch", "fc_compress_batch_noalloc", "fc_compress_batch_var", "fc_compress_batch_lse", "fc_window_lse",
     "fc_append_batch", "fc_decode_attention",
     "fc_decode_attention_kept",
-    "fc_mlp_set_weights", "fc_compress_batch_mlp", "fc_set_compaction_mode", "fc_set_streaming_sinks", "fc_set_score_mode", "fc_set_split_threshold", "fc_set_debug_checks", "fc_set_profiling", "fc_get_kernel_times",
+    "fc_mlp_set_weights", "fc_compress_batch_mlp", "fc_set_compaction_mode", "fc_set_streaming_sinks", "fc_set_score_mode", "fc_set_split_threshold", "fc_set_score_pruning", "fc_set_debug_checks", "fc_set_profiling", "fc_get_kernel_times",
     "fc_kernel_name", "fc_last_error",
     "fc_sched_create", "fc_sched_destroy", "fc_sched_submit", "fc_sched_pending",
     "fc_sched_batch_target", "fc_sched_ready", "fc_sched_form_batch", "fc_sched_adjust",
@@ -100,6 +100,7 @@ def load_library():
     lib.fc_compress_batch_mlp.argtypes = [vp, vp, i, i32p, i32p, i32p, i32p, i, vp]
     lib.fc_set_score_mode.argtypes = [vp, i]
     lib.fc_set_split_threshold.argtypes = [vp, i]
+    lib.fc_set_score_pruning.argtypes = [vp, i]
     lib.fc_set_debug_checks.argtypes = [vp, i]
     lib.fc_set_streaming_sinks.argtypes = [vp, i]
     lib.fc_set_compaction_mode.argtypes = [vp, i]
@@ -484,6 +485,10 @@ def fc_set_score_mode(pool, mode):
 
 def fc_set_debug_checks(pool, enable):
     _check(load_library().fc_set_debug_checks(pool.ptr, int(bool(enable))))
+
+
+def fc_set_score_pruning(pool, enable):
+    _check(load_library().fc_set_score_pruning(pool.ptr, 1 if enable else 0))
 
 
 def fc_set_split_threshold(pool, min_tokens):

@@ -58,6 +58,25 @@ def check_kept(gk, g_scores, ok, o_scores, budget, where=""):
     return False
 
 
+def check_kept_without_scores(gk, ok, o_scores, budget, where=""):
+    """For a call that produces no scores (pruned second pass): the kept list
+    against the oracle's, identical except inside the band around the oracle's
+    threshold.  (The no-tolerance check of check_kept needs the GPU's own
+    scores; here the same selection code runs on bounds and exact values, and
+    the kept set is compared with the oracle's directly.)"""
+    gk = np.asarray(gk)
+    assert gk.shape[0] == budget, "kept count != budget " + where
+    assert (np.diff(gk) > 0).all(), "kept not strictly ascending " + where
+    assert gk.min() >= 0 and gk.max() < o_scores.shape[0], "kept index out of range " + where
+    if (gk == ok).all():
+        return True
+    T = np.sort(o_scores)[::-1][budget - 1]
+    sym = np.setxor1d(gk, ok)
+    band = np.abs(o_scores[sym] - T) <= REL_TOL * abs(T) + ABS_TOL
+    assert band.all(), "kept sets differ outside the threshold band %s: %s" % (where, sym[~band])
+    return False
+
+
 class SideBySide:
     """Small workloads only: the whole pool lives on the host too."""
 
@@ -106,7 +125,7 @@ class SideBySide:
         assert (stack_g[:top_g] == self.stack.stack[:top_g]).all(), "free stacks differ"
 
     def compress_and_compare(self, methods=None, budgets=None, window=None, pool_kernel=None,
-                             scale=0.0, n_sink=4, q_list=None, lse=None):
+                             scale=0.0, n_sink=4, q_list=None, lse=None, scores=True):
         """One fc_compress_batch on both sides + full comparison.  Returns stats.
         lse = "oracle": the window rows' log-sum-exp comes from the oracle, is
         rounded to fp32 and handed to both sides (fc_compress_batch_lse);
@@ -114,7 +133,9 @@ class SideBySide:
         and the oracle runs the plain two-pass definition.
         With q_list (per request: fp16 array [n_layers][n_heads][window_r][d] or
         None), window and pool_kernel are int32 arrays and the call is
-        fc_compress_batch_var."""
+        fc_compress_batch_var.  scores=False: the call does not ask for the
+        scores (which lets the library prune its second pass); kept lists,
+        bytes and pool state are compared as always."""
         torch, fc, wl = self.torch, self.fc, self.wl
         methods = wl.methods if methods is None else methods
         budgets = wl.budgets if budgets is None else budgets
@@ -154,14 +175,16 @@ class SideBySide:
                                      kept_dev)
         elif q_list is None:
             fc.fc_compress_batch(self.pool, self.bt_dev, self.lens_g, self.q_dev, window,
-                                 methods, budgets, pool_kernel, scale, scores_dev, kept_dev)
+                                 methods, budgets, pool_kernel, scale,
+                                 scores_dev if scores else None, kept_dev)
         else:
             q_host = q_list
             packed = [q.reshape(-1) for r, q in enumerate(q_list)
                       if methods[r] == fo.METHOD_SNAPKV]
             q_flat = (torch.from_numpy(np.concatenate(packed)).to(self.dev) if packed else None)
             fc.fc_compress_batch_var(self.pool, self.bt_dev, self.lens_g, q_flat, window, methods,
-                                     budgets, pool_kernel, scale, scores_dev, kept_dev)
+                                     budgets, pool_kernel, scale, scores_dev if scores else None,
+                                     kept_dev)
         torch.cuda.synchronize()
         scores_g = scores_dev.cpu().numpy()
         kept_g = kept_dev.cpu().numpy()
@@ -192,10 +215,14 @@ class SideBySide:
             for l in range(wl.n_layers):
                 for h in range(wl.n_heads):
                     where = "(req %d layer %d head %d L %d B %d)" % (r, l, h, L, B)
-                    e = check_scores(sg[l, h], scores_o[r][l, h], where)
-                    stats["max_rel_err"] = max(stats["max_rel_err"], e)
-                    same = check_kept(kg[l, h], sg[l, h], kept_o[r][l, h], scores_o[r][l, h],
-                                      B, where)
+                    if scores:
+                        e = check_scores(sg[l, h], scores_o[r][l, h], where)
+                        stats["max_rel_err"] = max(stats["max_rel_err"], e)
+                        same = check_kept(kg[l, h], sg[l, h], kept_o[r][l, h],
+                                          scores_o[r][l, h], B, where)
+                    else:
+                        same = check_kept_without_scores(kg[l, h], kept_o[r][l, h],
+                                                         scores_o[r][l, h], B, where)
                     stats["units"] += 1
                     stats["units_kept_identical"] += int(same)
 
