@@ -533,7 +533,7 @@ def main():
                     help="CPU time budget of the oracle baseline (0 = skip)")
     ap.add_argument("--score-mode", default="auto", choices=["auto", "two_pass", "one_pass"],
                     help="which SnapKV score kernel the library uses")
-    ap.add_argument("--score-pruning", type=int, default=0, choices=[0, 1],
+    ap.add_argument("--score-pruning", type=int, default=1, choices=[0, 1],
                     help="1: fc_set_score_pruning (the fused kernel bounds the column sums in its "
                          "first pass over K and re-reads only the rows that can decide the selection)")
     ap.add_argument("--split-threshold", type=int, default=0,
@@ -668,7 +668,9 @@ def run_stage(args, wl, cpu_seconds, lse_variant=False):
     # (a batch issued as several calls launches the kernel once per call:
     # the average launch moves that share of the bytes)
     dom_gbps = kbytes[dom] / dw.parts / (kavg[dom] * 1e-3) / 1e9
-    traffic, traffic_source = measured_traffic(wl.name, dom)
+    # (records of the fused kernel without the pruned second pass are kept under a name of their own)
+    traffic, traffic_source = measured_traffic(
+        wl.name, dom if args.score_pruning or dom != "fused_unit" else "fused_unit_two_pass")
     if args.score_mode != "auto" or args.split_threshold != 0:
         traffic, traffic_source = None, "counters are kept for the default scheduling only"
 
@@ -693,6 +695,7 @@ def run_stage(args, wl, cpu_seconds, lse_variant=False):
             "pool_blocks": wl.n_blocks, "pool_GiB": round(wl.pool_bytes() / 2**30, 1),
             "kept_fraction": round(float(wl.budgets[comp].sum()) / tokens, 4),
             "score_mode": args.score_mode,
+            "score_pruning": bool(args.score_pruning),
         },
         "path": {
             "algorithmic_bytes": path_bytes,

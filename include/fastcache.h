@@ -385,12 +385,18 @@ int fc_set_split_threshold(fc_pool* pool, int min_tokens);
 /*
  * Pruned second pass of the SnapKV-style score (Algorithm 1, "Batch
  * compression"; the selection only needs exact scores near its threshold).
- * With enable != 0, the fused kernel of the default scheduling bounds every
- * column sum during its first pass over K and re-reads only the key rows whose
- * exact score can still decide the selection; the kept sets, the compacted
- * caches and the pool are exactly what the two-pass path produces.  It applies
- * to calls that do not ask for the scores (dev_scores_out == NULL) and do not
- * bring the row log-sum-exps; all other calls are unaffected.
+ * On by default (enable == 0 turns it off): for heads of at least 2048 tokens
+ * whose budget is at most half their length, the fused kernel of the default
+ * scheduling bounds every column sum during its first pass over K and re-reads
+ * only the key rows whose exact score can still decide the selection.  The kept
+ * set is the exact top-budget set of the exactly evaluated scores, as on the
+ * two-pass path (the two evaluate a column sum in different orders of
+ * addition, so between scores that agree to fp32 rounding the choice may
+ * differ); the compacted caches and the pool follow from it in the same way.
+ * It applies to calls that do not ask for the scores (dev_scores_out == NULL)
+ * and do not bring the row log-sum-exps; fc_compress_batch_noalloc and the
+ * separate-kernel modes never prune.  The bounds use 8 bytes of the library's
+ * score scratch per token of a (layer, head).
  */
 int fc_set_score_pruning(fc_pool* pool, int enable);
 

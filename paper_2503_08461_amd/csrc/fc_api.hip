@@ -156,7 +156,7 @@ struct fc_pool {
   int split_min_len = 0;          // FC_SCORE_AUTO: heads at least this long take it (0: none)
   int32_t* error_flag = nullptr;  // device, one int, zero unless a bounded wait ran out
   int score_mode = FC_SCORE_AUTO;
-  bool score_pruning = false;      // the fused kernel prunes the second pass of SnapKV units
+  bool score_pruning = true;       // the fused kernel prunes the second pass of SnapKV units
   int n_sink = 4;
   int compact_mode = FC_COMPACT_FRESH;
   // chunk-MLP compressor weights in operand order (library-owned)

@@ -1068,13 +1068,15 @@ __device__ __forceinline__ void snapkv_rescore(const BatchParams& p, const ReqDe
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) k[ks] = load_half8_nt(kp + ks * 32);
   };
-  half8 kc[KS], kn[KS];
-  int tok_c = -1, tok_n = -1;
+  half8 kc[KS], kn[KS], kf[KS];
+  int tok_c = -1, tok_n = -1, tok_f = -1;
   bool have = next_tile(tok_c);
   if (have) load_rows(tok_c, kc);
+  bool have_n = have && next_tile(tok_n);
+  if (have_n) load_rows(tok_n, kn);
   while (have) {
-    const bool more = next_tile(tok_n);
-    if (more) load_rows(tok_n, kn);
+    const bool have_f = have_n && next_tile(tok_f);
+    if (have_f) load_rows(tok_f, kf);
     float colsum = 0.f;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
@@ -1089,9 +1091,14 @@ __device__ __forceinline__ void snapkv_rescore(const BatchParams& p, const ReqDe
     colsum += __shfl_xor(colsum, 32);
     if (q4 == 0 && tok_c >= 0) stage[tok_c] = colsum;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) kc[ks] = kn[ks];
+    for (int ks = 0; ks < KS; ++ks) {
+      kc[ks] = kn[ks];
+      kn[ks] = kf[ks];
+    }
     tok_c = tok_n;
-    have = more;
+    tok_n = tok_f;
+    have = have_n;
+    have_n = have_f;
   }
 }
 

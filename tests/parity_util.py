@@ -269,7 +269,9 @@ def check_unit_on_device(kv_dev, q_unit, old_ids, new_ids, layer, head, L, B, me
     and the new blocks are downloaded for the byte comparison.
 
     kv_dev: device pool tensor; q_unit: [window][d] fp16 numpy (or None);
-    old_ids / new_ids: int numpy arrays; scores_g fp32 [L], kept_g int32 [B].
+    old_ids / new_ids: int numpy arrays; scores_g fp32 [L], or None for a call
+    that did not ask for the scores (the kept list is then checked against the
+    oracle's scores alone); kept_g int32 [B].
     Returns (max relative score error, kept lists identical?)."""
     import torch
     bs, d = kv_dev.shape[4], kv_dev.shape[5]
@@ -282,8 +284,12 @@ def check_unit_on_device(kv_dev, q_unit, old_ids, new_ids, layer, head, L, B, me
     table = np.arange(n_old)
     s_o = fo.unit_scores(mini, 0, table, 0, L, method, q_unit, None, pool_kernel)
     k_o = fo.select_topk(s_o, B)
-    err = check_scores(scores_g, s_o, where)
-    same = check_kept(kept_g, scores_g, k_o, s_o, B, where)
+    if scores_g is None:
+        err = 0.0
+        same = check_kept_without_scores(kept_g, k_o, s_o, B, where)
+    else:
+        err = check_scores(scores_g, s_o, where)
+        same = check_kept(kept_g, scores_g, k_o, s_o, B, where)
     fo.copy_rows(mini, 0, 0, table, n_old + np.arange(n_new), kept_g)
     got = kv_dev[layer, ni, :, head].cpu().numpy()            # [n_new][2][bs][d]
     for i in range(n_new):
