@@ -114,7 +114,7 @@ __device__ __forceinline__ float gelu_tanh(float v) {
 // the usual five-term rational approximation of erfc, at one transcendental
 // instead of two and no division).  Past |v| = 8.5 nothing is left of the tail
 // (Phi(-8.5) = 1e-17) and the polynomial is not followed further.
-// GELU(v) = v Phi(-|v|) for v < 0, v - v Phi(-|v|) otherwise.
+// GELU(v) = v Phi(-|v|) for v < 0, v - v Phi(-|v|) otherwise, i.e. max(v, 0) - |v| Phi(-|v|).
 #define FC_GELU_TAIL_P0 -9.999973123e-01f
 #define FC_GELU_TAIL_P1 -1.151156811e+00f
 #define FC_GELU_TAIL_P2 -4.588952346e-01f
@@ -131,8 +131,8 @@ __device__ __forceinline__ float gelu_erf(float v) {
   p = fmaf(a, p, FC_GELU_TAIL_P2);
   p = fmaf(a, p, FC_GELU_TAIL_P1);
   p = fmaf(a, p, FC_GELU_TAIL_P0);
-  const float vq = v * __builtin_amdgcn_exp2f(p);  // v Phi(-|v|)
-  return v < 0.f ? vq : v - vq;
+  // max(v, 0) - |v| Phi(-|v|): v - v Phi(-|v|) for v >= 0, v Phi(-|v|) below
+  return fmaf(-fabsf(v), __builtin_amdgcn_exp2f(p), fmaxf(v, 0.f));
 }
 
 template <int ACT>
