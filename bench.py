@@ -38,6 +38,20 @@ def csrc_digest():
     return h.hexdigest()[:16]
 
 
+def kernel_symbol(slot, wl, pruning):
+    """The kernel's name in a rocprofv3 trace for the library's timing slot
+    `slot` on workload wl (None where a slot covers several kernels)."""
+    nt = 1 if wl.window <= 16 else (2 if wl.window <= 32 else 4)
+    if slot == "fused_unit":
+        return "fc::%s<%d, %d>" % ("fused_bounded_kernel" if pruning else "fused_unit_kernel",
+                                   wl.head_dim, nt)
+    if slot == "snapkv_score":
+        return "fc::snapkv_score_kernel<%d, %d>" % (wl.head_dim, nt)
+    if slot in ("gather", "knorm_score", "select_gather"):
+        return "fc::%s_kernel<%d>" % (slot, wl.head_dim)
+    return None
+
+
 def measured_traffic(workload, kernel):
     """HBM bytes per launch of `kernel` on `workload` from the rocprofv3 counter
     summaries under profiles/ (FETCH_SIZE and WRITE_SIZE, each scaled by what it
@@ -707,6 +721,8 @@ def run_stage(args, wl, cpu_seconds, lse_variant=False):
         "kernel_ms": {k: round(v, 4) for k, v in kavg.items()},
         "roofline": {
             "kernel": dom,
+            # the name rocprofv3 shows for it (profiles/ summaries are keyed by that name)
+            "kernel_symbol": kernel_symbol(dom, wl, bool(args.score_pruning)),
             "bound": "hbm",
             "achieved": dom_gbps,
             "peak": HBM_PEAK_GBPS,

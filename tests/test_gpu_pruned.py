@@ -113,6 +113,49 @@ def test_logits_that_outrun_the_reference_fall_back_to_two_passes():
     _run_pruned(wl, sbs_kw={"kv_host": kv, "q_host": q})
 
 
+def _keys_by_token(wl, make_key):
+    """The synthetic pool with the K row of every (request, token) replaced by
+    make_key(r, tok) -> fp16 [head_dim] (same for all layers and heads)."""
+    from parity_util import SideBySide
+    kv = synth.fill_pool_host(wl)
+    s0 = SideBySide(wl)     # only to learn where the tokens live
+    try:
+        bt = s0.bt_host.copy()
+    finally:
+        s0.close()
+    for r in range(wl.n_req):
+        for tok in range(int(wl.seq_lens[r])):
+            kv[:, bt[r, tok // 16], 0, :, tok % 16, :] = make_key(r, tok)
+    return kv
+
+
+@pytest.mark.parametrize("shape", ["ramp", "sinks", "late_and_uneven"])
+def test_structured_attention_patterns(shape):
+    """Inputs on which the factor between a row's running sum and its final sum
+    behaves in the three extreme ways: it keeps shrinking along the whole head
+    (logits that rise with the position), it is one from the start (a few
+    dominant first tokens), and it differs wildly between the rows of one
+    16-row tile (half of the queries see their mass only at the end)."""
+    d, W = 64, 32
+    wl = _custom([3200, 2300], [640, 300], [fo.METHOD_SNAPKV] * 2, W=W, d=d, n_heads=2)
+    rng = np.random.default_rng(17)
+    u = np.zeros(d, np.float32)
+    u[:8] = 1.0
+    noise = lambda: 0.3 * rng.standard_normal(d).astype(np.float32)
+    q = synth.fill_q_window_host(wl).astype(np.float32) * 0.3
+    if shape == "ramp":
+        key = lambda r, tok: (noise() + u * (6.0 * tok / 3200.0)).astype(np.float16)
+        q[..., :8] += 2.0
+    elif shape == "sinks":
+        key = lambda r, tok: (noise() + (u * 8.0 if tok < 4 else 0.0)).astype(np.float16)
+        q[..., :8] += 2.0
+    else:
+        key = lambda r, tok: (noise() + (u * 5.0 if tok >= int(wl.seq_lens[r]) - 200 else 0.0)).astype(np.float16)
+        q[:, :, :, ::2, :8] += 2.5          # every other query row leans on the late keys
+    kv = _keys_by_token(wl, key)
+    _run_pruned(wl, sbs_kw={"kv_host": kv, "q_host": q.astype(np.float16)})
+
+
 def test_repeated_calls_and_in_place_compaction():
     wl = _custom([5000, 3000], [2500, 1200], [fo.METHOD_SNAPKV] * 2, W=64, d=128, n_heads=2)
     s = _pruned(wl)
