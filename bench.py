@@ -47,7 +47,7 @@ def kernel_symbol(slot, wl, pruning):
                                    wl.head_dim, nt)
     if slot == "snapkv_score":
         return "fc::snapkv_score_kernel<%d, %d>" % (wl.head_dim, nt)
-    if slot in ("gather", "knorm_score", "select_gather"):
+    if slot in ("gather", "knorm_score"):
         return "fc::%s_kernel<%d>" % (slot, wl.head_dim)
     return None
 
@@ -545,14 +545,11 @@ def main():
                     help="hidden width of the chunk-MLP workload")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="CPU time budget of the oracle baseline (0 = skip)")
-    ap.add_argument("--score-mode", default="auto", choices=["auto", "two_pass", "one_pass"],
-                    help="which SnapKV score kernel the library uses")
+    ap.add_argument("--score-mode", default="auto", choices=["auto", "two_pass"],
+                    help="scheduling: fused per-unit kernel, or separate kernels for everything")
     ap.add_argument("--score-pruning", type=int, default=1, choices=[0, 1],
                     help="1: fc_set_score_pruning (the fused kernel bounds the column sums in its "
                          "first pass over K and re-reads only the rows that can decide the selection)")
-    ap.add_argument("--split-threshold", type=int, default=0,
-                    help="auto scheduling: SnapKV requests of at least this many tokens take "
-                         "the token-split one-pass score kernel (0, the library's default: none)")
     ap.add_argument("--with-lse-variant", action="store_true",
                     help="also time the same batch through fc_compress_batch_lse (row log-sum-exp "
                          "supplied, computed before the timed region) and report it beside the value")
@@ -629,8 +626,7 @@ def run_stage(args, wl, cpu_seconds, lse_variant=False):
     from paper_2503_08461_amd import synth, fastcache as fc
     from paper_2503_08461_amd.device_setup import DeviceWorkload
     dw = DeviceWorkload(wl, verbose=True)
-    fc.fc_set_score_mode(dw.pool, {"auto": 0, "two_pass": 1, "one_pass": 2}[args.score_mode])
-    fc.fc_set_split_threshold(dw.pool, args.split_threshold)
+    fc.fc_set_score_mode(dw.pool, {"auto": 0, "two_pass": 1}[args.score_mode])
     fc.fc_set_score_pruning(dw.pool, bool(args.score_pruning))
     fc.fc_set_profiling(dw.pool, True)
     lse_ms = None
@@ -676,7 +672,7 @@ def run_stage(args, wl, cpu_seconds, lse_variant=False):
     comp = wl.methods != synth.METHOD_NONE
     tokens = int(wl.seq_lens[comp].astype(np.int64).sum())
     path_bytes = dw.algorithmic_bytes()
-    kbytes = dw.kernel_algorithmic_bytes(args.score_mode, args.split_threshold)
+    kbytes = dw.kernel_algorithmic_bytes(args.score_mode)
     # dominant kernel = the one with the largest average duration
     dom = max(kbytes, key=lambda k: kavg.get(k, 0.0))
     # (a batch issued as several calls launches the kernel once per call:
@@ -685,7 +681,7 @@ def run_stage(args, wl, cpu_seconds, lse_variant=False):
     # (records of the fused kernel without the pruned second pass are kept under a name of their own)
     traffic, traffic_source = measured_traffic(
         wl.name, dom if args.score_pruning or dom != "fused_unit" else "fused_unit_two_pass")
-    if args.score_mode != "auto" or args.split_threshold != 0:
+    if args.score_mode != "auto":
         traffic, traffic_source = None, "counters are kept for the default scheduling only"
 
     out = {
@@ -734,7 +730,7 @@ def run_stage(args, wl, cpu_seconds, lse_variant=False):
     }
     if dw.parts > 1:
         out["config"]["calls_per_step"] = dw.parts
-    if lse_variant and lse_ms is None and dw.parts == 1 and args.score_mode != "one_pass" and \
+    if lse_variant and lse_ms is None and dw.parts == 1 and \
             bool((wl.methods == synth.METHOD_SNAPKV).any()):
         # the same batch when the caller hands over the window rows' log-sum-exp
         # (one pass over K); reported beside the headline value, never as it

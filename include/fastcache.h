@@ -119,11 +119,10 @@ int fc_pool_num_free(const fc_pool* pool);
 /*
  * Copies the free stack to host_stack (host, int32[n_blocks]; entries
  * [0, *top) are meaningful) after waiting for all device work.  Synchronous.
- * Also reports, as FC_EDEVICE, a bounded wait between workgroups that ran
- * out inside an earlier fc_compress_batch (its scores are then invalid) and a
- * finding of the ownership checks on a pop.  Such a condition is reported by
- * one call (which copies nothing) and cleared; the next call succeeds unless
- * it has happened again.
+ * Also reports, as FC_EDEVICE, a finding of the ownership checks on a pop
+ * (a block that came off the free stack was not free).  Such a condition is
+ * reported by one call (which copies nothing) and cleared; the next call
+ * succeeds unless it has happened again.
  */
 int fc_pool_export_state(fc_pool* pool, int32_t* host_stack, int* top);
 
@@ -198,8 +197,8 @@ int fc_compress_batch(fc_pool* pool, int32_t* dev_block_tables, int max_blocks_p
  * device.  Limits (FC_EINVAL beyond them, nothing touched):
  *   - at most FC_NOALLOC_MAX_REQUESTS compressed requests per call;
  *   - every compressed request has at most 8192 tokens and the pool uses the
- *     default scheduling (FC_SCORE_AUTO, no split threshold): nothing may
- *     need the library's un-pooled score scratch;
+ *     default scheduling (FC_SCORE_AUTO): nothing may need the library's
+ *     un-pooled score scratch;
  *   - sum over requests of budget * n_layers * n_heads <= 15 Mi entries,
  *     unless dev_kept_out is given (then the kept lists go there);
  *   - sum over requests of ceil(L/16) + ceil(budget/16) <= 256 Ki block ids.
@@ -251,8 +250,7 @@ int fc_compress_batch_var(fc_pool* pool, int32_t* dev_block_tables, int max_bloc
  *                   only.  The library does not check it: a row whose entry is
  *                   off by t contributes exp(-t) times its soft-max row.
  * Everything else, including errors, as for fc_compress_batch; additionally
- * FC_EINVAL if a SNAPKV request is present and dev_lse_window is NULL, or if
- * the scheduling is FC_SCORE_ONE_PASS (which is itself a way to read K once).
+ * FC_EINVAL if a SNAPKV request is present and dev_lse_window is NULL.
  */
 int fc_compress_batch_lse(fc_pool* pool, int32_t* dev_block_tables, int max_blocks_per_req,
                           int32_t* host_seq_lens, const void* dev_q_window,
@@ -357,30 +355,16 @@ int fc_set_streaming_sinks(fc_pool* pool, int n_sink);
  *     tokens is handled by one fused kernel (two-pass score -> select -> gather
  *     inside the workgroup that owns the head; scores stay in LDS); longer
  *     heads go through the separate two-pass score, select and gather kernels.
- *     With fc_set_split_threshold, SnapKV requests from a given length on are
- *     scored by the token-split kernel described under FC_SCORE_ONE_PASS.
+ *     (See fc_set_score_pruning for what the fused kernel does with the
+ *     second pass when the call does not ask for the scores.)
  *   FC_SCORE_TWO_PASS: separate kernels for everything; SnapKV scoring streams
- *     K twice (row statistics, then column sums); workgroups never wait for
- *     each other; any length up to FC_MAX_SEQ_LEN.
- *   FC_SCORE_ONE_PASS: every SnapKV request is scored by the token-split
- *     kernel: a head is shared by a team of workgroups that each keep a slice
- *     of its keys in registers, exchange their rows' (max, sum of exp) pairs
- *     and finish the column sums from the registers, so K is read from HBM
- *     once; select and gather follow in one kernel per head.  It is a
- *     persistent kernel that needs its grid co-resident (cooperative launch);
- *     its waits between workgroups are bounded, and one that runs out is
- *     reported as FC_EDEVICE by fc_pool_export_state.  FC_EINVAL if the device
- *     cannot run it or a head has more than 15360 tokens.  As measured on
- *     MI355X it is slower than reading K twice (the exchange between
- *     workgroups costs more than the second pass).
- * All three produce the same scores up to fp32 rounding.
+ *     K twice (row statistics, then column sums); any length up to
+ *     FC_MAX_SEQ_LEN.
+ * Both produce the same scores up to fp32 rounding.  In neither does a
+ * workgroup ever wait for another one.
  */
-enum { FC_SCORE_AUTO = 0, FC_SCORE_TWO_PASS = 1, FC_SCORE_ONE_PASS = 2 };
+enum { FC_SCORE_AUTO = 0, FC_SCORE_TWO_PASS = 1 };
 int fc_set_score_mode(fc_pool* pool, int mode);
-
-/* FC_SCORE_AUTO: SnapKV requests of at least min_tokens tokens take the
- * token-split one-pass score kernel (0, the default: none does). */
-int fc_set_split_threshold(fc_pool* pool, int min_tokens);
 
 /*
  * Pruned second pass of the SnapKV-style score (Algorithm 1, "Batch
@@ -410,7 +394,7 @@ int fc_set_score_pruning(fc_pool* pool, int enable);
  * fc_kernel_name(i) names slot i.  fc_set_profiling(pool, 1) restarts the
  * average.
  */
-#define FC_N_KERNELS 12
+#define FC_N_KERNELS 11
 int fc_set_profiling(fc_pool* pool, int enable);
 int fc_get_kernel_times(fc_pool* pool, float* host_ms);
 const char* fc_kernel_name(int i);

@@ -7,7 +7,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libfastcache.so")
 
-SOURCES = ["fc_api.hip", "fc_kernels.hip", "fc_score_split.hip", "fc_mlp.hip", "fc_decode.hip", "fc_sched.cpp", "fc_plan.cpp"]
+SOURCES = ["fc_api.hip", "fc_kernels.hip", "fc_mlp.hip", "fc_decode.hip", "fc_sched.cpp", "fc_plan.cpp"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -63,15 +63,16 @@ int fail(int code, const char* fmt, ...) {
 const char* const kKernelNames[K_COUNT] = {"plan_alloc", "snapkv_score", "knorm_score",
                                            "select",     "gather",       "reclaim",
                                            "fused_unit", "mlp_compress", "append",
-                                           "decode_attention", "window_lse", "select_gather"};
+                                           "decode_attention", "window_lse"};
 
 // the planning module restates the public constants; they must agree
 static_assert(PLAN_OK == FC_OK && PLAN_EINVAL == FC_EINVAL && PLAN_ENOMEM == FC_ENOMEM, "codes");
 static_assert(PLAN_METHOD_SNAPKV == FC_METHOD_SNAPKV && PLAN_METHOD_KNORM == FC_METHOD_KNORM &&
               PLAN_METHOD_STREAMING == FC_METHOD_STREAMING && PLAN_METHOD_NONE == FC_METHOD_NONE,
               "methods");
-static_assert(PLAN_SCORE_AUTO == FC_SCORE_AUTO && PLAN_SCORE_TWO_PASS == FC_SCORE_TWO_PASS &&
-              PLAN_SCORE_ONE_PASS == FC_SCORE_ONE_PASS, "score modes");
+static_assert(PLAN_SCORE_AUTO == FC_SCORE_AUTO && PLAN_SCORE_TWO_PASS == FC_SCORE_TWO_PASS,
+              "score modes");
+static_assert(K_COUNT == FC_N_KERNELS, "timing slots");
 static_assert(kPlanBlockSize == FC_BLOCK_SIZE && kPlanMaxWindow == FC_MAX_WINDOW &&
               kPlanMaxSeqLen == FC_MAX_SEQ_LEN && kPlanMaxPoolKernel == FC_MAX_POOL_KERNEL &&
               kPlanFusedMaxLen == kFusedMaxLen && kPlanClasses == FC_MAX_WINDOW / 16 + 1,
@@ -150,11 +151,7 @@ struct fc_pool {
   hipEvent_t meta_event = nullptr;
   bool meta_pending = false;
 
-  // token-split one-pass SnapKV score kernel
-  uint64_t* split_xchg = nullptr;
-  size_t split_xchg_cap = 0;      // 64-bit words
-  int split_min_len = 0;          // FC_SCORE_AUTO: heads at least this long take it (0: none)
-  int32_t* error_flag = nullptr;  // device, one int, zero unless a bounded wait ran out
+  int32_t* error_flag = nullptr;  // device, one int, zero unless a kernel found something wrong
   int score_mode = FC_SCORE_AUTO;
   bool score_pruning = true;       // the fused kernel prunes the second pass of SnapKV units
   int n_sink = 4;
@@ -165,7 +162,6 @@ struct fc_pool {
   _Float16* mlp_w2p[2] = {nullptr, nullptr};
   float* mlp_b1[2] = {nullptr, nullptr};
   float* mlp_b2[2] = {nullptr, nullptr};
-  int split_grid[FC_MAX_WINDOW / 16 + 1] = {};  // co-resident grid per query-tile count, -1 = none
 
   bool profiling = false;
   // event ring: the last kProfRing profiled calls, [call][kernel][start, stop]
@@ -268,7 +264,6 @@ int fc_pool_destroy(fc_pool* p) {
   if (p->raw_scores) (void)hipFree(p->raw_scores);
   if (p->kept) (void)hipFree(p->kept);
   if (p->ids) (void)hipFree(p->ids);
-  if (p->split_xchg) (void)hipFree(p->split_xchg);
   if (p->error_flag) (void)hipFree(p->error_flag);
   for (int m = 0; m < 2; ++m) {
     if (p->mlp_w1p[m]) (void)hipFree(p->mlp_w1p[m]);  // w2p lies in the same allocation
@@ -333,8 +328,6 @@ int fc_pool_export_state(fc_pool* p, int32_t* host_stack, int* top) {
     // reported once: the flag starts over, so that a later export says what happened since
     FC_HIP(launch_zero_ints(p->error_flag, 1, nullptr));
     FC_HIP(hipDeviceSynchronize());
-    if (flag & 0xFF)
-      return fail(FC_EDEVICE, "a bounded wait between workgroups ran out in an earlier call");
     return fail(FC_EDEVICE, "ownership checks: a block that was popped off the free stack was "
                             "not free (the free list is corrupt)");
   }
@@ -375,7 +368,7 @@ int fc_set_streaming_sinks(fc_pool* p, int n_sink) {
 
 int fc_set_score_mode(fc_pool* p, int mode) {
   if (!p) return fail(FC_EINVAL, "pool is NULL");
-  if (mode != FC_SCORE_AUTO && mode != FC_SCORE_TWO_PASS && mode != FC_SCORE_ONE_PASS)
+  if (mode != FC_SCORE_AUTO && mode != FC_SCORE_TWO_PASS)
     return fail(FC_EINVAL, "unknown score mode %d", mode);
   p->score_mode = mode;
   return FC_OK;
@@ -399,13 +392,6 @@ int fc_set_debug_checks(fc_pool* p, int enable) {
 int fc_set_score_pruning(fc_pool* p, int enable) {
   if (!p) return fail(FC_EINVAL, "pool is NULL");
   p->score_pruning = enable != 0;
-  return FC_OK;
-}
-
-int fc_set_split_threshold(fc_pool* p, int min_tokens) {
-  if (!p) return fail(FC_EINVAL, "pool is NULL");
-  if (min_tokens < 0) return fail(FC_EINVAL, "min_tokens < 0");
-  p->split_min_len = min_tokens;
   return FC_OK;
 }
 
@@ -450,7 +436,7 @@ int fc_pool_import_state_dev(fc_pool* p, const int32_t* dev_stack, int top, void
 
 namespace {
 
-PoolView pool_view(fc_pool* p, bool want_split) {
+PoolView pool_view(fc_pool* p) {
   PoolView v;
   v.n_layers = p->n_layers;
   v.n_heads = p->n_heads;
@@ -458,18 +444,6 @@ PoolView pool_view(fc_pool* p, bool want_split) {
   v.n_free = p->top;
   v.score_mode = p->score_mode;
   v.in_place = p->compact_mode == FC_COMPACT_IN_PLACE;
-  v.split_min_len = p->split_min_len;
-  v.split_cap_blocks = split_blocks_per_workgroup();
-  if (want_split) {
-    // the co-resident grid of the token-split score kernel, asked once per query-tile count
-    for (int nt = 1; nt <= FC_MAX_WINDOW / 16; ++nt) {
-      if (p->split_grid[nt] == 0) {
-        const int gsz = split_grid_size(p->head_dim, 16 * nt);
-        p->split_grid[nt] = gsz > 0 ? gsz : -1;
-      }
-      v.split_grid[nt] = p->split_grid[nt];
-    }
-  }
   return v;
 }
 
@@ -540,10 +514,7 @@ int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_blocks_pe
   a.need_lse = need_lse;
   a.q_ok = dev_q_window && (reinterpret_cast<uintptr_t>(dev_q_window) & 15) == 0;
   a.lse_ok = dev_lse_window && (reinterpret_cast<uintptr_t>(dev_lse_window) & 3) == 0;
-  const bool want_split = !no_alloc && !need_lse &&
-                          (p->score_mode == FC_SCORE_ONE_PASS ||
-                           (p->score_mode == FC_SCORE_AUTO && p->split_min_len > 0));
-  const PoolView pv = pool_view(p, want_split);
+  const PoolView pv = pool_view(p);
   CompressPlan plan;
   if (plan_compress(pv, a, &plan) != PLAN_OK) return fail(plan.code, "%s", plan.message);
   const int n_comp = (int)plan.descs.size();
@@ -563,7 +534,7 @@ int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_blocks_pe
     if (n_comp > FC_NOALLOC_MAX_REQUESTS)
       return fail(FC_EINVAL, "%d requests exceed the %d of the allocation-free call", n_comp,
                   FC_NOALLOC_MAX_REQUESTS);
-    if (plan.raw_floats > 0 || !plan.split_launches.empty())
+    if (plan.raw_floats > 0)
       return fail(FC_EINVAL, "the allocation-free call takes heads of at most %d tokens with "
                              "the default scheduling", kFusedMaxLen);
     if (!dev_kept_out && plan.kept_entries > kNoAllocKeptInts)
@@ -584,9 +555,6 @@ int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_blocks_pe
     const bool bounded_call = p->score_pruning && !dev_scores_out && !need_lse;
     if ((rc = grow(&p->raw_scores, &p->raw_cap,
                    std::max(plan.raw_floats, bounded_call ? 2 * plan.score_entries : (size_t)0))) != FC_OK)
-      return rc;
-    if (!plan.split_launches.empty() &&
-        (rc = grow(&p->split_xchg, &p->split_xchg_cap, (size_t)2 * plan.split_grid_max * 64)) != FC_OK)
       return rc;
     if ((rc = grow_meta(p, meta_bytes)) != FC_OK) return rc;
     if (!kept_buf) kept_buf = p->kept;
@@ -623,9 +591,6 @@ int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_blocks_pe
   bp.n_knorm = n_list[LIST_KNORM];
   bp.n_unfused = n_list[LIST_ALL];
   // per launch: order_snap / n_snap, order_fused / n_fused, window (of the class)
-  bp.order_split = dev_list(LIST_SPLIT);
-  bp.n_split = n_list[LIST_SPLIT];
-  bp.split_xchg = p->split_xchg;
   bp.block_tables = dev_block_tables;
   bp.max_blocks = max_blocks_per_req;
   bp.old_ids = ids_buf;
@@ -677,20 +642,8 @@ int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_blocks_pe
     return e;
   };
   FC_HIP_STAGE(p, run(K_PLAN_ALLOC, true, [&] { return launch_plan_alloc(bp, stream); }));
-  FC_HIP_STAGE(p, run(K_SNAPKV_SCORE, ns > 0 || !plan.split_launches.empty(), [&] {
+  FC_HIP_STAGE(p, run(K_SNAPKV_SCORE, ns > 0, [&] {
     hipError_t e = hipSuccess;
-    for (const SplitLaunch& sl : plan.split_launches) {
-      if (e != hipSuccess) break;
-      const int grid = p->split_grid[sl.nt];
-      // (a fill kernel, not a memset: the call may be captured into a graph)
-      e = launch_zero_ints(reinterpret_cast<int32_t*>(p->split_xchg), 2 * grid * 64 * 2, stream);
-      BatchParams bc = bp;
-      bc.order_split = dev_list(LIST_SPLIT) + sl.first;
-      bc.n_split = sl.count;
-      bc.split_team = sl.team;
-      bc.window = 16 * sl.nt;
-      if (e == hipSuccess) e = launch_snapkv_split(bc, grid, stream);
-    }
     for (int c = 1; c < kPlanClasses && e == hipSuccess; ++c) {
       if (n_list[LIST_SNAP + c] == 0) continue;
       BatchParams bc = bp;
@@ -700,9 +653,6 @@ int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_blocks_pe
       e = launch_snapkv_score(bc, stream);
     }
     return e;
-  }));
-  FC_HIP_STAGE(p, run(K_SELECT_GATHER, bp.n_split > 0, [&] {
-    return launch_select_gather(bp, plan.max_len[LIST_SPLIT], stream);
   }));
   FC_HIP_STAGE(p, run(K_KNORM_SCORE, bp.n_knorm > 0, [&] { return launch_knorm_score(bp, stream); }));
   FC_HIP_STAGE(p, run(K_SELECT, bp.n_unfused > 0,
@@ -793,7 +743,7 @@ int fc_window_lse(fc_pool* p, const int32_t* dev_block_tables, int max_blocks_pe
   if (reinterpret_cast<uintptr_t>(dev_lse_out) & 3)
     return fail(FC_EINVAL, "dev_lse_out must be 4-byte aligned");
   LsePlan plan;
-  if (plan_window_lse(pool_view(p, false), n_req, max_blocks_per_req, host_seq_lens, host_method,
+  if (plan_window_lse(pool_view(p), n_req, max_blocks_per_req, host_seq_lens, host_method,
                       window, &plan) != PLAN_OK)
     return fail(plan.code, "%s", plan.message);
   if (plan.descs.empty()) return FC_OK;
@@ -888,7 +838,7 @@ int fc_compress_batch_mlp(fc_pool* p, int32_t* dev_block_tables, int max_blocks_
   if (p->mlp_k == 0) return fail(FC_EINVAL, "fc_mlp_set_weights has not been called");
   if (n_req > 0 && !dev_block_tables) return fail(FC_EINVAL, "NULL argument");
   MlpPlan plan;
-  if (plan_mlp(pool_view(p, false), n_req, max_blocks_per_req, host_seq_lens, host_img_begin,
+  if (plan_mlp(pool_view(p), n_req, max_blocks_per_req, host_seq_lens, host_img_begin,
                host_img_end, host_enable, p->mlp_k, mlp_rows_per_tile(p->mlp_hidden),
                &plan) != PLAN_OK)
     return fail(plan.code, "%s", plan.message);
@@ -1035,7 +985,7 @@ int decode_attention_impl(fc_pool* p, const int32_t* dev_block_tables, int max_b
     return fail(FC_EINVAL, "NULL argument");
   if (reinterpret_cast<uintptr_t>(dev_q) & 15) return fail(FC_EINVAL, "dev_q must be 16-byte aligned");
   DecodePlan plan;
-  if (plan_decode_attention(pool_view(p, false), n_req, max_blocks_per_req, host_seq_lens,
+  if (plan_decode_attention(pool_view(p), n_req, max_blocks_per_req, host_seq_lens,
                             dev_kept ? host_budget : nullptr, &plan) != PLAN_OK)
     return fail(plan.code, "%s", plan.message);
   int rc;
@@ -1069,7 +1019,7 @@ int fc_append_batch(fc_pool* p, int32_t* dev_block_tables, int max_blocks_per_re
   if (reinterpret_cast<uintptr_t>(dev_new_kv) & 15)
     return fail(FC_EINVAL, "dev_new_kv must be 16-byte aligned");
   DecodePlan plan;
-  if (plan_append(pool_view(p, false), n_req, max_blocks_per_req, host_seq_lens, host_enable,
+  if (plan_append(pool_view(p), n_req, max_blocks_per_req, host_seq_lens, host_enable,
                   &plan) != PLAN_OK)
     return fail(plan.code, "%s", plan.message);
   if (plan.reqs.empty()) return FC_OK;

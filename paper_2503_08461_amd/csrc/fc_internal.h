@@ -56,9 +56,7 @@ struct BatchParams {
   const int32_t* order_snap;   // [n_snap]
   const int32_t* order_knorm;  // [n_knorm]
   const int32_t* order_fused;  // [n_fused] units handled by the fused kernel (both methods)
-  const int32_t* order_split;  // [n_split] SnapKV requests of a token-split score launch, or all
-                               // of them for the select + gather launch that follows
-  int32_t n_comp, n_snap, n_knorm, n_unfused, n_fused, n_split;
+  int32_t n_comp, n_snap, n_knorm, n_unfused, n_fused;
   int32_t* block_tables;       // caller's [n_req][max_blocks]
   int32_t max_blocks;
   int32_t* old_ids;            // [total_old] saved pre-compression ids
@@ -75,10 +73,7 @@ struct BatchParams {
   float* raw_scores;           // un-pooled scores of the units that take the separate kernels
   float* scores_out;           // nullable
   int32_t* kept;               // kept indices, packed
-  // token-split one-pass SnapKV score kernel (persistent, co-resident grid)
-  int32_t split_team;          // workgroups that share one (layer, head) in this launch
-  uint64_t* split_xchg;        // [2][grid][64] tagged (max, sum) pairs, zeroed before the launch
-  int32_t* error_flag;         // set if a bounded wait ran out or an ownership check failed
+  int32_t* error_flag;         // set if a kernel finds something wrong (an ownership check that fails)
   int32_t bounded;             // 1: the fused kernel prunes the second pass of its SnapKV units
   int32_t* owner;              // ownership checks (debug mode): [n_blocks] 0 free, 1 handed out,
                                // 2 being released; NULL when the checks are off
@@ -101,8 +96,7 @@ enum KernelSlot {
   K_APPEND = 8,
   K_DECODE_ATTENTION = 9,
   K_WINDOW_LSE = 10,
-  K_SELECT_GATHER = 11,
-  K_COUNT = 12
+  K_COUNT = 11
 };
 
 // Launchers (fc_kernels.hip).  Each returns the hipError_t of the launch.
@@ -122,15 +116,8 @@ hipError_t launch_owner_check_tables(const BatchParams& p, int32_t* word, bool r
                                      hipStream_t s);
 hipError_t launch_plan_alloc(const BatchParams& p, hipStream_t s);
 hipError_t launch_snapkv_score(const BatchParams& p, hipStream_t s);
-// Token-split one-pass variant (fc_score_split.hip).  split_blocks_per_workgroup()
-// is how many 16-token blocks of a head one workgroup can hold; split_grid_size()
-// is the co-resident grid (0 if the device cannot run it); launch_zero_ints
-// clears the exchange buffers; launch_select_gather finishes the heads scored so.
-int split_blocks_per_workgroup();
-int split_grid_size(int head_dim, int window);
+// a fill kernel (not a memset: calls may be captured into a graph)
 hipError_t launch_zero_ints(int32_t* p, int n, hipStream_t s);
-hipError_t launch_snapkv_split(const BatchParams& p, int grid, hipStream_t s);
-hipError_t launch_select_gather(const BatchParams& p, int max_seq_len, hipStream_t s);
 hipError_t launch_knorm_score(const BatchParams& p, hipStream_t s);
 hipError_t launch_select(const BatchParams& p, int max_seq_len, hipStream_t s);
 hipError_t launch_gather(const BatchParams& p, hipStream_t s);

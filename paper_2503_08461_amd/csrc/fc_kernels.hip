@@ -1416,27 +1416,11 @@ __global__ __launch_bounds__(kThreads, 3) void fused_bounded_kernel(BatchParams 
   gather_unit<D>(p, rd, lh, ids_in_lds ? sm_ids : p.old_ids + rd.old_off);
 }
 
-// ---------------------------------------------------------------------------
-// select + gather of the heads whose scores came through the score scratch
-// (those of the token-split one-pass score kernel)
-// ---------------------------------------------------------------------------
-
-template <int D>
-__global__ __launch_bounds__(kThreads) void select_gather_kernel(BatchParams p) {
-  extern __shared__ uint32_t keys[];
-  __shared__ SelectShared sh;
-  __shared__ int32_t sm_ids[kFusedMaxLen / 16];
-  const int n_lh = p.n_layers * p.n_heads;
-  const int slot = blockIdx.x / n_lh;
-  const int lh = blockIdx.x - slot * n_lh;
-  const ReqDesc rd = p.descs[p.order_split[slot]];
-  const bool ids_in_lds = rd.n_old <= kFusedMaxLen / 16;
-  if (ids_in_lds)
-    for (int i = threadIdx.x; i < rd.n_old; i += kThreads)
-      sm_ids[i] = clamp_block(p.old_ids[rd.old_off + i], p.n_blocks);
-  select_unit<false>(p, rd, lh, keys, sh);
-  __syncthreads();  // the kept list (global memory, this workgroup's own) is complete
-  gather_unit<D>(p, rd, lh, ids_in_lds ? sm_ids : p.old_ids + rd.old_off);
+// a fill kernel for small device arrays (flags, verdict words): calls may be
+// captured into a graph, where a memset node is not wanted
+__global__ void zero_ints_kernel(int32_t* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
 }
 
 // ---------------------------------------------------------------------------
@@ -1448,12 +1432,6 @@ hipError_t kernels_one_time_setup() {
   // (the fused kernel never does: kFusedMaxLen * 4 = 32 KiB)
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, 32768 * 4);
-  if (e == hipSuccess)
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(select_gather_kernel<128>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, 32768 * 4);
-  if (e == hipSuccess)
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(select_gather_kernel<64>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, 32768 * 4);
   return e;
 }
 
@@ -1602,16 +1580,9 @@ hipError_t launch_gather(const BatchParams& p, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_select_gather(const BatchParams& p, int max_seq_len, hipStream_t s) {
-  if (p.n_split == 0) return hipSuccess;
-  const unsigned grid = (unsigned)p.n_split * p.n_layers * p.n_heads;
-  const size_t lds = (size_t)max_seq_len * sizeof(uint32_t);
-  if (p.head_dim == 128)
-    select_gather_kernel<128><<<grid, kThreads, lds, s>>>(p);
-  else if (p.head_dim == 64)
-    select_gather_kernel<64><<<grid, kThreads, lds, s>>>(p);
-  else
-    return hipErrorInvalidValue;
+hipError_t launch_zero_ints(int32_t* p, int n, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  zero_ints_kernel<<<(n + 255) / 256, 256, 0, s>>>(p, n);
   return hipGetLastError();
 }
 

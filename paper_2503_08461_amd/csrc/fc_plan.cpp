@@ -31,10 +31,6 @@ int fail(Plan* plan, int code, const char* fmt, ...) {
   return code;
 }
 
-// Team sizes of the token-split score kernel when a batch has more distinct
-// ones than launches are worth: a head takes the next size of this ladder.
-const int kTeamLadder[] = {1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 14, 16, 20, 24, 28, 32, 40, 48, 56, 64};
-
 }  // namespace
 
 int plan_compress(const PoolView& pool, const CompressArgs& a, CompressPlan* plan) {
@@ -89,8 +85,6 @@ int plan_compress(const PoolView& pool, const CompressArgs& a, CompressPlan* pla
         return fail(plan, PLAN_EINVAL, "dev_q_window must be a 16-byte aligned device pointer");
       if (a.need_lse && !a.lse_ok)
         return fail(plan, PLAN_EINVAL, "dev_lse_window must be a 4-byte aligned device pointer");
-      if (a.need_lse && pool.score_mode == PLAN_SCORE_ONE_PASS)
-        return fail(plan, PLAN_EINVAL, "the one-pass scheduling takes no log-sum-exp input");
       plan->window_hi = std::max(plan->window_hi, win);
     }
     ReqDesc d = {};
@@ -132,44 +126,6 @@ int plan_compress(const PoolView& pool, const CompressArgs& a, CompressPlan* pla
   plan->top_after = pool.in_place ? pool.n_free + (int)total_released
                                   : pool.n_free - (int)total_new + (int)total_old;
 
-  // ---- token-split one-pass SnapKV scoring: which requests, which team sizes ----
-  // A request takes it if the scheduling asks for it (ONE_PASS: every SnapKV
-  // request; AUTO: those of at least split_min_len tokens, if set), the device
-  // can hold the kernel's grid co-resident and the head fits a team.
-  std::vector<int> split_team(n_comp, 0);  // 0: not split
-  int n_split_req = 0;
-  if (!a.need_lse && pool.score_mode != PLAN_SCORE_TWO_PASS) {
-    const int cap = std::max(pool.split_cap_blocks, 1);
-    for (int i = 0; i < n_comp; ++i) {
-      const ReqDesc& d = descs[i];
-      if (d.method != PLAN_METHOD_SNAPKV) continue;
-      if (pool.score_mode == PLAN_SCORE_AUTO &&
-          (pool.split_min_len == 0 || d.seq_len < pool.split_min_len))
-        continue;
-      const int nt = (d.window + 15) / 16;
-      const int grid = pool.split_grid[nt];
-      const int g = (d.n_old + cap - 1) / cap;
-      if (grid > 0 && g <= kPlanSplitMaxTeam && g <= grid) {
-        split_team[i] = g;
-        ++n_split_req;
-      } else if (pool.score_mode == PLAN_SCORE_ONE_PASS) {
-        return fail(plan, PLAN_EINVAL,
-                    "request %d: one-pass scoring is not possible on this device (no "
-                    "co-resident grid, or more than %d tokens)",
-                    d.table_row, kPlanSplitMaxTeam * cap * kPlanBlockSize);
-      }
-    }
-    // few launches: with many distinct team sizes, round them up along the ladder
-    std::vector<int> sizes;
-    for (int g : split_team)
-      if (g > 0) sizes.push_back(g);
-    std::sort(sizes.begin(), sizes.end());
-    sizes.erase(std::unique(sizes.begin(), sizes.end()), sizes.end());
-    if ((int)sizes.size() > kPlanSplitMaxClasses)
-      for (int& g : split_team)
-        if (g > 0) g = *std::lower_bound(std::begin(kTeamLadder), std::end(kTeamLadder), g);
-  }
-
   // ---- work lists ------------------------------------------------------------------
   // Descriptor indices, heaviest first so that the tail of each launch is made
   // of light units.  Heads short enough for the fused kernel (score -> select ->
@@ -194,7 +150,7 @@ int plan_compress(const PoolView& pool, const CompressArgs& a, CompressPlan* pla
     const ReqDesc& d = descs[i];
     // (streaming: no score, no LDS, so the fused kernel whatever the length)
     return d.method == PLAN_METHOD_STREAMING ||
-           (allow_fused && split_team[i] == 0 && d.seq_len <= kPlanFusedMaxLen);
+           (allow_fused && d.seq_len <= kPlanFusedMaxLen);
   };
   // Units without queries (key-norm, streaming) ride in the launch of the
   // SnapKV class that has the most fused units, if there is one: one launch
@@ -215,12 +171,6 @@ int plan_compress(const PoolView& pool, const CompressArgs& a, CompressPlan* pla
     int li;
     if (fused(di)) {
       li = LIST_FUSED + (snap ? cls : home_class);
-    } else if (split_team[di] > 0) {
-      // scores through the scratch; listed below, grouped by launch
-      d.raw_off = (int64_t)raw_need;
-      raw_need += n_lh * (size_t)d.seq_len;
-      plan->max_len[LIST_SPLIT] = std::max(plan->max_len[LIST_SPLIT], d.seq_len);
-      continue;
     } else {
       // scores of these units travel through the library's scratch
       d.raw_off = (int64_t)raw_need;
@@ -234,25 +184,6 @@ int plan_compress(const PoolView& pool, const CompressArgs& a, CompressPlan* pla
     if (d.method != PLAN_METHOD_STREAMING) plan->max_len[li] = std::max(plan->max_len[li], d.seq_len);
   }
   plan->raw_floats = raw_need;
-  // token-split launches: one per (team size, query-tile count), requests of a
-  // launch contiguous in LIST_SPLIT, heaviest first inside it
-  if (n_split_req > 0) {
-    std::vector<int> idx;
-    for (int di : sorted)
-      if (split_team[di] > 0) idx.push_back(di);
-    auto key = [&](int i) { return split_team[i] * 8 + (descs[i].window + 15) / 16; };
-    std::stable_sort(idx.begin(), idx.end(), [&](int x, int y) { return key(x) > key(y); });
-    for (int di : idx) {
-      const int nt = (descs[di].window + 15) / 16;
-      if (plan->split_launches.empty() || plan->split_launches.back().team != split_team[di] ||
-          plan->split_launches.back().nt != nt) {
-        plan->split_launches.push_back({split_team[di], nt, (int)plan->lists[LIST_SPLIT].size(), 0});
-        plan->split_grid_max = std::max(plan->split_grid_max, pool.split_grid[nt]);
-      }
-      ++plan->split_launches.back().count;
-      plan->lists[LIST_SPLIT].push_back(di);
-    }
-  }
   return PLAN_OK;
 }
 

@@ -18,14 +18,12 @@ namespace fc {
 // translation unit that includes both checks it).
 enum { PLAN_OK = 0, PLAN_EINVAL = -1, PLAN_ENOMEM = -2 };
 enum { PLAN_METHOD_NONE = 0, PLAN_METHOD_SNAPKV = 1, PLAN_METHOD_KNORM = 2, PLAN_METHOD_STREAMING = 3 };
-enum { PLAN_SCORE_AUTO = 0, PLAN_SCORE_TWO_PASS = 1, PLAN_SCORE_ONE_PASS = 2 };
+enum { PLAN_SCORE_AUTO = 0, PLAN_SCORE_TWO_PASS = 1 };
 static constexpr int kPlanBlockSize = 16;
 static constexpr int kPlanMaxWindow = 64;
 static constexpr int kPlanMaxSeqLen = 32768;
 static constexpr int kPlanMaxPoolKernel = 63;
 static constexpr int kPlanFusedMaxLen = 8192;   // longest head the fused kernel takes
-static constexpr int kPlanSplitMaxTeam = 64;    // largest team of the token-split score kernel
-static constexpr int kPlanSplitMaxClasses = 12; // launches of it per call before sizes are merged
 static constexpr int kPlanClasses = 5;          // query-tile counts 0..4 (0: no queries)
 
 // What the pool contributes to a plan.
@@ -34,9 +32,6 @@ struct PoolView {
   int n_free = 0;                       // free blocks on entry
   int score_mode = PLAN_SCORE_AUTO;
   bool in_place = false;
-  int split_min_len = 0;                // AUTO: SnapKV requests at least this long are split (0: none)
-  int split_cap_blocks = 15;            // blocks of a head one workgroup of the split kernel holds
-  int split_grid[kPlanClasses] = {};    // its co-resident grid per query-tile count, <= 0: cannot run
 };
 
 // The caller's arguments of fc_compress_batch / _var / _lse, pointers reduced
@@ -60,12 +55,7 @@ enum {
   LIST_SNAP = kPlanClasses,        // + class: separate two-pass score kernel
   LIST_KNORM = 2 * kPlanClasses,   // separate key-norm score kernel
   LIST_ALL,                        // select and gather of the separate path
-  LIST_SPLIT,                      // token-split score launches (contiguous per launch), select_gather
   N_LISTS
-};
-
-struct SplitLaunch {
-  int team, nt, first, count;  // team size, query tiles, range in LIST_SPLIT
 };
 
 struct CompressPlan {
@@ -74,13 +64,11 @@ struct CompressPlan {
   std::vector<ReqDesc> descs;                 // compressed requests, batch order
   std::vector<int32_t> lists[N_LISTS];
   int max_len[N_LISTS] = {};
-  std::vector<SplitLaunch> split_launches;
   int total_new = 0, total_old = 0, total_released = 0;
   int window_hi = 0;                          // largest window of a SnapKV request
   size_t kept_entries = 0;                    // ints of the kept buffer
   size_t score_entries = 0;                   // floats of a packed scores_out
   size_t raw_floats = 0;                      // floats of un-pooled score scratch
-  int split_grid_max = 0;                     // largest grid among the split launches
   int top_after = 0;                          // free blocks after the call
 };
 

@@ -102,15 +102,11 @@ class DeviceWorkload:
         kept = int(wl.budgets[comp].astype(np.int64).sum())
         return n_lh * (tokens * row + kept * 4 * row)
 
-    def kernel_algorithmic_bytes(self, score_mode="auto", split_min_len=0, fused_max_len=8192,
-                                 split_max_blocks=64 * 15):
+    def kernel_algorithmic_bytes(self, score_mode="auto", fused_max_len=8192):
         """Algorithmic bytes per launch of each kernel that moves bulk data,
-        following the library's scheduling: SnapKV heads that take the
-        token-split score kernel (one_pass: all that fit a team; auto: those of
-        at least `split_min_len` tokens) are scored there and finished by
-        select_gather; with auto, the other heads of at most `fused_max_len`
-        tokens run in the fused kernel (score + gather bytes); the rest in the
-        separate kernels."""
+        following the library's scheduling: with auto, heads of at most
+        `fused_max_len` tokens run in the fused kernel (score + gather bytes);
+        the rest in the separate kernels."""
         wl = self.wl
         n_lh = wl.n_layers * wl.n_heads
         row = 2 * wl.head_dim
@@ -119,20 +115,12 @@ class DeviceWorkload:
         snap = wl.methods == synth.METHOD_SNAPKV
         kn = wl.methods == synth.METHOD_KNORM
         stream = wl.methods == synth.METHOD_STREAMING
-        fits_team = (L + 15) // 16 <= split_max_blocks
-        if score_mode == "one_pass":
-            split = snap & fits_team
-        elif score_mode == "auto":
-            split = snap & fits_team & (L >= split_min_len) & (split_min_len > 0)
-        else:
-            split = snap & False
-        fused = (snap | kn) & ~split & (L <= fused_max_len) & (score_mode == "auto")
-        sep = (snap | kn) & ~split & ~fused
+        fused = (snap | kn) & (L <= fused_max_len) & (score_mode == "auto")
+        sep = (snap | kn) & ~fused
         return {
             "fused_unit": n_lh * int((L[fused] * row + B[fused] * 4 * row).sum()
                                      + (B[stream] * 4 * row).sum()),
-            "snapkv_score": n_lh * int(L[snap & (split | sep)].sum()) * row,
+            "snapkv_score": n_lh * int(L[snap & sep].sum()) * row,
             "knorm_score": n_lh * int(L[kn & sep].sum()) * row,
             "gather": n_lh * int(B[sep].sum()) * 4 * row,
-            "select_gather": n_lh * int(B[split].sum()) * 4 * row,
         }

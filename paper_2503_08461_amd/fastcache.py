@@ -15,8 +15,8 @@ FC_OK, FC_EINVAL, FC_ENOMEM, FC_EDEVICE = 0, -1, -2, -3
 FC_METHOD_NONE, FC_METHOD_SNAPKV, FC_METHOD_KNORM, FC_METHOD_STREAMING = 0, 1, 2, 3
 FC_DTYPE_F16 = 0
 FC_BLOCK_SIZE = 16
-FC_N_KERNELS = 12
-FC_SCORE_AUTO, FC_SCORE_TWO_PASS, FC_SCORE_ONE_PASS = 0, 1, 2
+FC_N_KERNELS = 11
+FC_SCORE_AUTO, FC_SCORE_TWO_PASS = 0, 1
 FC_COMPACT_FRESH, FC_COMPACT_IN_PLACE = 0, 1
 FC_ACT_GELU_ERF, FC_ACT_GELU_TANH = 0, 1
 
@@ -29,7 +29,7 @@ EXPORTS = [
     "fc_compress_batch", "fc_compress_batch_noalloc", "fc_compress_batch_var", "fc_compress_batch_lse", "fc_window_lse",
     "fc_append_batch", "fc_decode_attention",
     "fc_decode_attention_kept",
-    "fc_mlp_set_weights", "fc_compress_batch_mlp", "fc_set_compaction_mode", "fc_set_streaming_sinks", "fc_set_score_mode", "fc_set_split_threshold", "fc_set_score_pruning", "fc_set_debug_checks", "fc_set_profiling", "fc_get_kernel_times",
+    "fc_mlp_set_weights", "fc_compress_batch_mlp", "fc_set_compaction_mode", "fc_set_streaming_sinks", "fc_set_score_mode", "fc_set_score_pruning", "fc_set_debug_checks", "fc_set_profiling", "fc_get_kernel_times",
     "fc_kernel_name", "fc_last_error",
     "fc_sched_create", "fc_sched_destroy", "fc_sched_submit", "fc_sched_pending",
     "fc_sched_batch_target", "fc_sched_ready", "fc_sched_form_batch", "fc_sched_adjust",
@@ -99,7 +99,6 @@ def load_library():
     lib.fc_mlp_set_weights.argtypes = [vp, ctypes.POINTER(MlpWeights), vp]
     lib.fc_compress_batch_mlp.argtypes = [vp, vp, i, i32p, i32p, i32p, i32p, i, vp]
     lib.fc_set_score_mode.argtypes = [vp, i]
-    lib.fc_set_split_threshold.argtypes = [vp, i]
     lib.fc_set_score_pruning.argtypes = [vp, i]
     lib.fc_set_debug_checks.argtypes = [vp, i]
     lib.fc_set_streaming_sinks.argtypes = [vp, i]
@@ -489,10 +488,6 @@ def fc_set_debug_checks(pool, enable):
 
 def fc_set_score_pruning(pool, enable):
     _check(load_library().fc_set_score_pruning(pool.ptr, 1 if enable else 0))
-
-
-def fc_set_split_threshold(pool, min_tokens):
-    _check(load_library().fc_set_split_threshold(pool.ptr, int(min_tokens)))
 
 
 def fc_set_profiling(pool, enable):

@@ -81,7 +81,7 @@ class SideBySide:
     """Small workloads only: the whole pool lives on the host too."""
 
     def __init__(self, wl, device="cuda:0", kv_host=None, q_host=None, score_mode=None,
-                 in_place=False, split_threshold=None):
+                 in_place=False):
         import torch
         from paper_2503_08461_amd import fastcache as fc
         self.torch, self.fc, self.wl = torch, fc, wl
@@ -94,8 +94,6 @@ class SideBySide:
                                       wl.head_dim)
         if score_mode is not None:
             fc.fc_set_score_mode(self.pool, score_mode)
-        if split_threshold is not None:
-            fc.fc_set_split_threshold(self.pool, split_threshold)
         self.in_place = in_place
         fc.fc_set_compaction_mode(self.pool, 1 if in_place else 0)
         self.stack = fo.FreeStack(wl.n_blocks)

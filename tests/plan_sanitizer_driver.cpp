@@ -5,7 +5,7 @@
 // and checked by test_plan_sanitizers.py.
 //
 // Input, one case per block of lines (all integers):
-//   compress nl nh d n_free mode in_place split_min cap g1 g2 g3 g4 n_req max_blocks per_req
+//   compress nl nh d n_free mode in_place n_req max_blocks per_req
 //            window pool_kernel need_lse q_ok lse_ok null_mask
 //     then lines: seq_lens, methods, budgets, and with per_req = 1 windows, pool_kernels
 //   lse nl nh d n_req max_blocks window has_method        then seq_lens [, methods]
@@ -47,11 +47,9 @@ int main() {
     if (k == "compress") {
       int mode, in_place, n_req, max_blocks, per_req, need_lse, q_ok, lse_ok, null_mask;
       CompressArgs a;
-      if (scanf("%d %d %d %d %d %d %d %d %d %d %d %d %d %d %d %d %d %d %d %d %d", &pv.n_layers,
-                &pv.n_heads, &pv.head_dim, &pv.n_free, &mode, &in_place, &pv.split_min_len,
-                &pv.split_cap_blocks, &pv.split_grid[1], &pv.split_grid[2], &pv.split_grid[3],
-                &pv.split_grid[4], &n_req, &max_blocks, &per_req, &a.window, &a.pool_kernel,
-                &need_lse, &q_ok, &lse_ok, &null_mask) != 21)
+      if (scanf("%d %d %d %d %d %d %d %d %d %d %d %d %d %d %d", &pv.n_layers, &pv.n_heads,
+                &pv.head_dim, &pv.n_free, &mode, &in_place, &n_req, &max_blocks, &per_req,
+                &a.window, &a.pool_kernel, &need_lse, &q_ok, &lse_ok, &null_mask) != 15)
         return 2;
       pv.score_mode = mode;
       pv.in_place = in_place != 0;
@@ -71,10 +69,9 @@ int main() {
       a.lse_ok = lse_ok != 0;
       CompressPlan plan;
       const int rc = plan_compress(pv, a, &plan);
-      printf("R %d %d %d %d %d %d %zu %zu %zu %d %d %zu\n", rc, plan.code, plan.total_new,
+      printf("R %d %d %d %d %d %d %zu %zu %zu %d %zu\n", rc, plan.code, plan.total_new,
              plan.total_old, plan.total_released, plan.top_after, plan.kept_entries,
-             plan.score_entries, plan.raw_floats, plan.window_hi, plan.split_grid_max,
-             plan.descs.size());
+             plan.score_entries, plan.raw_floats, plan.window_hi, plan.descs.size());
       if (rc != PLAN_OK) continue;
       for (const ReqDesc& d : plan.descs) print_desc(d);
       for (int i = 0; i < N_LISTS; ++i) {
@@ -82,8 +79,6 @@ int main() {
         for (int32_t x : plan.lists[i]) printf(" %d", x);
         printf("\n");
       }
-      for (const SplitLaunch& s : plan.split_launches)
-        printf("S %d %d %d %d\n", s.team, s.nt, s.first, s.count);
     } else if (k == "lse") {
       int n_req, max_blocks, window, has_method;
       if (scanf("%d %d %d %d %d %d %d", &pv.n_layers, &pv.n_heads, &pv.head_dim, &n_req,

@@ -117,14 +117,6 @@ def test_errors_and_untouched_state():
                                      wl.budgets)
         assert e.value.code == fc.FC_EINVAL
         untouched()
-        # the one-pass scheduling takes no such input
-        fc.fc_set_score_mode(s.pool, 2)
-        with pytest.raises(fc.FastCacheError) as e:
-            fc.fc_compress_batch_lse(s.pool, s.bt_dev, s.lens_g, s.q_dev, lse, 16, wl.methods,
-                                     wl.budgets)
-        assert e.value.code == fc.FC_EINVAL
-        untouched()
-        fc.fc_set_score_mode(s.pool, 0)
         # fc_window_lse: window out of range, request shorter than the window
         for w in (0, 65):
             with pytest.raises(fc.FastCacheError) as e:

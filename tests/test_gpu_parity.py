@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 def score_mode(request):
     """Both schedulings of the hot path must meet the same bar (FC_SCORE_AUTO =
     0: fused score/select/gather kernel; FC_SCORE_TWO_PASS = 1: separate
-    kernels).  The opt-in one-pass scheduling has a test file of its own."""
+    kernels)."""
     return request.param
 
 

@@ -20,7 +20,7 @@ ROOT = os.path.dirname(HERE)
 SRC = [os.path.join(HERE, "plan_sanitizer_driver.cpp"),
        os.path.join(ROOT, "paper_2503_08461_amd", "csrc", "fc_plan.cpp")]
 CODES = {None: 0, "EINVAL": -1, "ENOMEM": -2}
-N_LISTS, LIST_SPLIT, LIST_ALL, LIST_KNORM, LIST_SNAP, LIST_FUSED = 13, 12, 11, 10, 5, 0
+N_LISTS, LIST_ALL, LIST_KNORM, LIST_SNAP, LIST_FUSED = 12, 11, 10, 5, 0
 
 
 def _build(tmp_path, name, flags):
@@ -45,14 +45,14 @@ class Case:
     """One fc_compress_batch-shaped call."""
 
     def __init__(self, lens, methods, budgets, n_layers=2, n_heads=3, d=128, n_free=None,
-                 mode=0, in_place=False, split_min=0, cap=15, grids=(512, 512, 512, 512),
+                 mode=0, in_place=False,
                  max_blocks=None, window=32, pool_kernel=7, windows=None, pks=None,
                  need_lse=False, q_ok=True, lse_ok=True, null_mask=0):
         self.lens = np.array(lens, np.int64)
         self.methods = np.array(methods, np.int64)
         self.budgets = np.array(budgets, np.int64)
         self.n_layers, self.n_heads, self.d = n_layers, n_heads, d
-        self.mode, self.in_place, self.split_min, self.cap, self.grids = mode, in_place, split_min, cap, grids
+        self.mode, self.in_place = mode, in_place
         self.window, self.pool_kernel, self.windows, self.pks = window, pool_kernel, windows, pks
         self.need_lse, self.q_ok, self.lse_ok, self.null_mask = need_lse, q_ok, lse_ok, null_mask
         nb = [fo.blocks_for(max(int(x), 0), 16) for x in self.lens]
@@ -64,7 +64,7 @@ class Case:
     def text(self):
         per = self.windows is not None
         head = [self.n_layers, self.n_heads, self.d, self.n_free, self.mode, int(self.in_place),
-                self.split_min, self.cap, *self.grids, len(self.lens), self.max_blocks, int(per),
+                len(self.lens), self.max_blocks, int(per),
                 self.window, self.pool_kernel, int(self.need_lse), int(self.q_ok),
                 int(self.lse_ok), self.null_mask]
         rows = [_ints(self.lens), _ints(self.methods), _ints(self.budgets)]
@@ -113,7 +113,7 @@ def _parse(out):
 
 def _check_compress(case, header, rows):
     rc, code, total_new, total_old, total_rel, top_after, kept_e, score_e, raw_f, window_hi, \
-        grid_max, n_descs = header
+        n_descs = header
     if len(case.lens) == 0:
         assert rc == 0 and n_descs == 0          # an empty batch is accepted as it is
         return
@@ -157,7 +157,7 @@ def _check_compress(case, header, rows):
         if li in (LIST_ALL,):
             continue
         seen += idx
-        if idx and li != LIST_SPLIT:
+        if idx:
             w = [int(L[i]) * (0 if descs[i][3] == 3 else 1 if (descs[i][3] == 2 or case.need_lse)
                               else 2) + 4 * int(B[i]) for i in idx]
             assert w == sorted(w, reverse=True)
@@ -171,33 +171,20 @@ def _check_compress(case, header, rows):
                 assert (descs[i][12] + 15) // 16 == li - LIST_FUSED
     sep = lists[LIST_ALL][1]
     assert sorted(sep) == sorted(lists[LIST_KNORM][1] + sum((lists[LIST_SNAP + c][1] for c in range(5)), []))
-    for i in sep + lists[LIST_SPLIT][1]:
+    for i in sep:
         raw_total += n_lh * int(L[i])
     assert raw_f == raw_total
-    raw_offs = sorted(descs[i][9] for i in sep + lists[LIST_SPLIT][1])
+    raw_offs = sorted(descs[i][9] for i in sep)
     assert len(set(raw_offs)) == len(raw_offs)
-    # token-split launches partition their list; a team holds its head
-    pos = 0
-    for team, nt, first, count in rows.get("S", []):
-        assert first == pos and count > 0
-        for i in lists[LIST_SPLIT][1][first:first + count]:
-            assert descs[i][3] == 1 and (descs[i][12] + 15) // 16 == nt
-            assert team * case.cap >= n_old[i] and team <= 64 and team <= case.grids[nt - 1]
-        pos += count
-    assert pos == len(lists[LIST_SPLIT][1])
-    if case.mode == 2:
-        assert sorted(lists[LIST_SPLIT][1]) == [i for i in range(len(comp)) if descs[i][3] == 1]
 
 
 def _config_cases():
     cases = []
     for c in (1, 2, 3, 4, 5):
         wl = synth.make_workload(c)
-        for mode, split_min in ((0, 0), (1, 0), (2, 0), (0, 2048)):
-            if mode == 2 and int(wl.seq_lens.max()) > 15360:
-                continue
+        for mode in (0, 1):
             cases.append(Case(wl.seq_lens, wl.methods, wl.budgets, wl.n_layers, wl.n_heads,
-                              wl.head_dim, mode=mode, split_min=split_min, window=wl.window,
+                              wl.head_dim, mode=mode, window=wl.window,
                               pool_kernel=wl.pool_kernel))
         cases.append(Case(wl.seq_lens, wl.methods, wl.budgets, wl.n_layers, wl.n_heads,
                           wl.head_dim, in_place=True, n_free=0, window=wl.window))
@@ -230,11 +217,9 @@ def _random_cases(n, seed):
                 B = int(rng.integers(W, L + 1))
             lens.append(L); methods.append(m); budgets.append(B)
         kw = dict(n_layers=int(rng.integers(1, 4)), n_heads=int(rng.integers(1, 5)),
-                  d=int(rng.choice([64, 128])), mode=int(rng.integers(0, 3)),
+                  d=int(rng.choice([64, 128])), mode=int(rng.integers(0, 2)),
                   in_place=bool(rng.integers(0, 2)), window=W,
-                  pool_kernel=int(rng.choice([1, 3, 7, 15, 63, 2, 0])),
-                  split_min=int(rng.choice([0, 1, 3000])), cap=15,
-                  grids=tuple(int(x) for x in rng.choice([512, 512, 40, -1], size=4)))
+                  pool_kernel=int(rng.choice([1, 3, 7, 15, 63, 2, 0])))
         if rng.random() < 0.2:
             kw["n_free"] = int(rng.integers(0, 50))             # often too few
         if rng.random() < 0.15:
@@ -246,30 +231,13 @@ def _random_cases(n, seed):
     return cases
 
 
-def _keep_within_library_limits(case):
-    """The oracle has no notion of the library's own limits (one-pass team
-    capacity, grid availability); those refusals are checked apart."""
-    if case.mode != 2:
-        return True
-    for r in range(len(case.lens)):
-        if case.methods[r] == 1:
-            w = case.windows[r] if case.windows is not None else case.window
-            if not 1 <= w <= 64:
-                continue
-            nt = (w + 15) // 16
-            g = -(-fo.blocks_for(max(int(case.lens[r]), 0), 16) // case.cap)
-            if case.grids[nt - 1] <= 0 or g > 64 or g > case.grids[nt - 1]:
-                return False
-    return True
-
-
 @pytest.mark.skipif(shutil.which("g++") is None, reason="no host compiler")
 def test_planning_is_clean_under_asan_and_ubsan_and_agrees_with_the_oracle(tmp_path):
     plain = _build(tmp_path, "plain", [])
     checked = _build(tmp_path, "checked",
                      ["-fsanitize=address,undefined", "-fno-sanitize-recover=all",
                       "-fno-omit-frame-pointer", "-static-libasan", "-static-libubsan"])
-    cases = _config_cases() + [c for c in _random_cases(400, 2024) if _keep_within_library_limits(c)]
+    cases = _config_cases() + _random_cases(400, 2024)
     text = "".join(c.text() for c in cases)
     out = _run(checked, text)
     assert out == _run(plain, text)
@@ -285,20 +253,16 @@ def test_planning_is_clean_under_asan_and_ubsan_and_agrees_with_the_oracle(tmp_p
     ok = dict(lens=[5000, 300], methods=[1, 2], budgets=[900, 100], window=32)
     bad = [Case(**ok, null_mask=1), Case(**ok, null_mask=2), Case(**ok, null_mask=4),
            Case(**ok, q_ok=False), Case(**ok, need_lse=True, lse_ok=False),
-           Case(**ok, need_lse=True, mode=2),
            Case(lens=[5000], methods=[1], budgets=[900], window=65),
            Case(lens=[5000], methods=[1], budgets=[900], window=32, pool_kernel=65),
            Case(lens=[32769], methods=[2], budgets=[900]),
-           Case(lens=[15361], methods=[1], budgets=[900], mode=2),            # beyond a team of 64
-           Case(lens=[5000], methods=[1], budgets=[900], mode=2, grids=(-1, -1, -1, -1)),
            Case(lens=[5000, 300], methods=[1, 1], budgets=[900, 100], windows=[32, 16], pks=[7, 3],
                 null_mask=8)]
     for (header, _rows), case in zip(_parse(_run(checked, "".join(c.text() for c in bad))), bad):
         assert header[0] == -1, case.text()
-    # the same valid call goes through, and takes the one-pass route when asked to
-    good = Case(**ok, mode=2)
-    header, rows = _parse(_run(checked, good.text()))[0]
-    assert header[0] == 0 and rows["S"] == [[21, 2, 0, 1]]        # 313 blocks, 15 per workgroup
+    # the same valid call goes through
+    header, rows = _parse(_run(checked, Case(**ok, mode=1).text()))[0]
+    assert header[0] == 0 and len(rows["D"]) == 2
 
     # the other planners: window log-sum-exp, chunk MLP, append, decode attention
     other = ("lse 2 3 128 4 80 32 1\n700 100 1200 64\n1 2 1 1\n"
