@@ -156,6 +156,14 @@ def test_structured_attention_patterns(shape):
     _run_pruned(wl, sbs_kw={"kv_host": kv, "q_host": q.astype(np.float16)})
 
 
+def test_heads_beyond_the_fused_limit_share_a_call_with_pruned_ones():
+    """A request too long for the fused kernel goes through the separate score,
+    select and gather kernels, whose un-pooled scores use the same library
+    scratch as the pruned heads' side sums (one after the other on the stream)."""
+    wl = _custom([9000, 3000, 8200], [1500, 600, 4000], [fo.METHOD_SNAPKV] * 3, W=32, d=64, n_heads=2)
+    _run_pruned(wl)
+
+
 def test_repeated_calls_and_in_place_compaction():
     wl = _custom([5000, 3000], [2500, 1200], [fo.METHOD_SNAPKV] * 2, W=64, d=128, n_heads=2)
     s = _pruned(wl)
