@@ -380,7 +380,8 @@ int fc_set_score_mode(fc_pool* pool, int mode);
  * It applies to calls that do not ask for the scores (dev_scores_out == NULL)
  * and do not bring the row log-sum-exps; fc_compress_batch_noalloc and the
  * separate-kernel modes never prune.  The bounds use 8 bytes of the library's
- * score scratch per token of a (layer, head).
+ * score scratch per token of a (layer, head); a call for which that much
+ * device memory cannot be allocated runs without pruning.
  */
 int fc_set_score_pruning(fc_pool* pool, int enable);
 

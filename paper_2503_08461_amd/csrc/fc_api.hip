@@ -186,6 +186,24 @@ int grow(T** buf, size_t* cap, size_t need) {
   return FC_OK;
 }
 
+// For scratch that a call can do without: a buffer that cannot be had leaves
+// the old one in place and returns false (the error is not kept).
+template <typename T>
+bool try_grow(T** buf, size_t* cap, size_t need) {
+  if (need <= *cap) return true;
+  T* fresh = nullptr;
+  const size_t n = round_up(need + need / 8, 4096);
+  if (hipMalloc(reinterpret_cast<void**>(&fresh), n * sizeof(T)) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  (void)hipDeviceSynchronize();  // the old buffer may still be in use by queued work
+  if (*buf) (void)hipFree(*buf);
+  *buf = fresh;
+  *cap = n;
+  return true;
+}
+
 int grow_meta(fc_pool* p, size_t need) {
   if (need <= p->meta_cap) return FC_OK;
   FC_HIP(hipDeviceSynchronize());
@@ -529,6 +547,7 @@ int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_blocks_pe
   int32_t* ids_buf = nullptr;
   char* dev_meta = nullptr;
   int rc;
+  bool pruned_call = !no_alloc && p->score_pruning && !dev_scores_out && !need_lse;
   if (no_alloc) {
     if (!p->fixed_scratch) return fail(FC_EDEVICE, "the fixed scratch array was not set up");
     if (n_comp > FC_NOALLOC_MAX_REQUESTS)
@@ -551,11 +570,12 @@ int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_blocks_pe
     // (growth waits for the device and frees: it happens before anything is queued)
     if (!dev_kept_out && (rc = grow(&p->kept, &p->kept_cap, plan.kept_entries)) != FC_OK) return rc;
     if ((rc = grow(&p->ids, &p->ids_cap, n_ids)) != FC_OK) return rc;
-    // (the pruned second pass keeps three per-tile sums per token, 8 bytes, in the score scratch)
-    const bool bounded_call = p->score_pruning && !dev_scores_out && !need_lse;
-    if ((rc = grow(&p->raw_scores, &p->raw_cap,
-                   std::max(plan.raw_floats, bounded_call ? 2 * plan.score_entries : (size_t)0))) != FC_OK)
-      return rc;
+    if ((rc = grow(&p->raw_scores, &p->raw_cap, plan.raw_floats)) != FC_OK) return rc;
+    // (the pruned second pass keeps three per-tile sums per token, 8 bytes, in the score
+    // scratch; where that much memory is not to be had the call runs without it)
+    if (pruned_call && !try_grow(&p->raw_scores, &p->raw_cap,
+                                 std::max(plan.raw_floats, 2 * plan.score_entries)))
+      pruned_call = false;
     if ((rc = grow_meta(p, meta_bytes)) != FC_OK) return rc;
     if (!kept_buf) kept_buf = p->kept;
     ids_buf = p->ids;
@@ -607,7 +627,7 @@ int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_blocks_pe
   bp.kept = kept_buf;
   bp.error_flag = p->error_flag;
   bp.owner = p->debug_checks ? p->owner : nullptr;
-  bp.bounded = (p->score_pruning && !dev_scores_out && !need_lse && !no_alloc) ? 1 : 0;
+  bp.bounded = pruned_call ? 1 : 0;
 
   if (p->debug_checks) {
     // the table rows that the stage will release: every id in range, handed out, named once
