@@ -378,10 +378,9 @@ int fc_set_score_mode(fc_pool* pool, int mode);
  * addition, so between scores that agree to fp32 rounding the choice may
  * differ); the compacted caches and the pool follow from it in the same way.
  * It applies to calls that do not ask for the scores (dev_scores_out == NULL)
- * and do not bring the row log-sum-exps; fc_compress_batch_noalloc and the
- * separate-kernel modes never prune.  The bounds use 8 bytes of the library's
- * score scratch per token of a (layer, head); a call for which that much
- * device memory cannot be allocated runs without pruning.
+ * and do not bring the row log-sum-exps; the separate-kernel modes never
+ * prune.  The bounds live in the kernel's local memory: no device memory
+ * beyond that of the two-pass path is used.
  */
 int fc_set_score_pruning(fc_pool* pool, int enable);
 

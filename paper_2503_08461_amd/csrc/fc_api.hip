@@ -186,23 +186,6 @@ int grow(T** buf, size_t* cap, size_t need) {
   return FC_OK;
 }
 
-// For scratch that a call can do without: a buffer that cannot be had leaves
-// the old one in place and returns false (the error is not kept).
-template <typename T>
-bool try_grow(T** buf, size_t* cap, size_t need) {
-  if (need <= *cap) return true;
-  T* fresh = nullptr;
-  const size_t n = round_up(need + need / 8, 4096);
-  if (hipMalloc(reinterpret_cast<void**>(&fresh), n * sizeof(T)) != hipSuccess) {
-    (void)hipGetLastError();
-    return false;
-  }
-  (void)hipDeviceSynchronize();  // the old buffer may still be in use by queued work
-  if (*buf) (void)hipFree(*buf);
-  *buf = fresh;
-  *cap = n;
-  return true;
-}
 
 int grow_meta(fc_pool* p, size_t need) {
   if (need <= p->meta_cap) return FC_OK;
@@ -547,7 +530,7 @@ int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_blocks_pe
   int32_t* ids_buf = nullptr;
   char* dev_meta = nullptr;
   int rc;
-  bool pruned_call = !no_alloc && p->score_pruning && !dev_scores_out && !need_lse;
+  const bool pruned_call = p->score_pruning && !dev_scores_out && !need_lse;
   if (no_alloc) {
     if (!p->fixed_scratch) return fail(FC_EDEVICE, "the fixed scratch array was not set up");
     if (n_comp > FC_NOALLOC_MAX_REQUESTS)
@@ -571,11 +554,6 @@ int compress_batch_impl(fc_pool* p, int32_t* dev_block_tables, int max_blocks_pe
     if (!dev_kept_out && (rc = grow(&p->kept, &p->kept_cap, plan.kept_entries)) != FC_OK) return rc;
     if ((rc = grow(&p->ids, &p->ids_cap, n_ids)) != FC_OK) return rc;
     if ((rc = grow(&p->raw_scores, &p->raw_cap, plan.raw_floats)) != FC_OK) return rc;
-    // (the pruned second pass keeps three per-tile sums per token, 8 bytes, in the score
-    // scratch; where that much memory is not to be had the call runs without it)
-    if (pruned_call && !try_grow(&p->raw_scores, &p->raw_cap,
-                                 std::max(plan.raw_floats, 2 * plan.score_entries)))
-      pruned_call = false;
     if ((rc = grow_meta(p, meta_bytes)) != FC_OK) return rc;
     if (!kept_buf) kept_buf = p->kept;
     ids_buf = p->ids;

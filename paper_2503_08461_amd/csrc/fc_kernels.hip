@@ -744,12 +744,14 @@ __device__ __forceinline__ void select_unit(const BatchParams& p, const ReqDesc&
 // row's sum over what the workgroup has read so far, renewed at fixed steps by
 // all wavefronts together), so the exact weight of logit (i, j) is that
 // numerator times rho_i = 2^(ref_i - lse_i) <= 1, a factor that is only known at
-// the end but is the same for every token of an epoch.  With c_j^g the sum of a
-// token's numerators over the rows of the g-th 16-row tile of the window,
-//     sum_g c_j^g min_(i in g) rho_i  <=  a_j  <=  sum_g c_j^g max_(i in g) rho_i .
-// (The sum over all rows stays in LDS, the per-tile sums but one go through a
-// scratch buffer in HBM: 12 bytes per token written and read once, against 256
-// bytes per row that is not re-read.)
+// the end but is the same for every token of an epoch.  With c_j the sum of a
+// token's numerators e_ij over the window rows and s_j the root of the sum of
+// their squares, for any number m (here the mean of the rho_i)
+//     a_j = sum_i e_ij rho_i = m c_j + sum_i e_ij (rho_i - m),
+//     | a_j - m c_j |  <=  s_j sqrt(sum_i (rho_i - m)^2)        (Cauchy-Schwarz),
+// and also c_j min_i rho_i <= a_j <= c_j max_i rho_i.  Both numbers of a token
+// share its word of the LDS score array until the pass ends (c_j in the leading
+// 20 bits, s_j / c_j <= 1 in the other 12), so the bounds cost no memory traffic.
 // After the pass: bounds of the max-pooled scores, a lower and an upper bound of
 // the selection threshold from two histograms, and the tokens whose pooled
 // interval contains neither are decided without a second look.  For the others
@@ -766,19 +768,30 @@ __device__ __forceinline__ void select_unit(const BatchParams& p, const ReqDesc&
 // overflow, the row's log-sum-exp is not finite, and the head falls back to
 // the two-pass code.
 
-typedef _Float16 half4v __attribute__((ext_vector_type(4)));
-
 struct BoundShared {
   float fin[64];                   // log2 of every row's soft-max denominator
   float pub[2][kWaves][64];        // the wavefronts' row sums at a renewal, absolute log2
   float ref[kBoundMaxEpochs][64];  // the reference of every epoch
 };
 
-struct BoundKeep {                    // what survives into the selection's LDS
-  float rmax[kBoundMaxEpochs][4];     // largest factor of an epoch over the rows of a 16-row tile
-  float rmin[kBoundMaxEpochs][4];     // smallest
-  int bad;                            // a row's log-sum-exp is not finite: fall back
+struct BoundKeep {                 // what survives into the selection's LDS
+  float rmax[kBoundMaxEpochs];     // largest factor of an epoch over the window rows (widened)
+  float rmin[kBoundMaxEpochs];     // smallest
+  float rmean[kBoundMaxEpochs];    // their mean
+  float rdev[kBoundMaxEpochs];     // root of the sum of their squared deviations from it (widened)
+  int bad;                         // a row's log-sum-exp is not finite: fall back
 };
+
+// A token's two sums during the pass, in one word: the leading 20 bits of the
+// sum c of its numerators (truncated: at most 2^-11 below c) and, in 12 bits, a
+// number k with sqrt(s2) <= k / 4095 * c, s2 the sum of their squares (the ratio
+// is at most 1; where the squares left the fp32 range, or c is too small for
+// them to be trusted, k = 4095 says just that).
+__device__ __forceinline__ uint32_t pack_sums(float c, float s2) {
+  const float r = sqrtf(s2) / c;  // not a number <= 1 when c is 0 or either sum overflowed
+  const uint32_t k = (c >= 1.0e-12f && r <= 1.f) ? min(4095u, (uint32_t)(r * 4095.f) + 2u) : 4095u;
+  return (__float_as_uint(c) & 0xFFFFF000u) | k;
+}
 
 // A token's bounds share one 32-bit word of LDS: the upper bound rounded up to
 // its leading 16 bits, the lower bound rounded down to its leading 16 bits
@@ -797,13 +810,12 @@ __device__ __forceinline__ int bound_epoch_of_token(int j) {
 }
 
 // First pass with bounds.  On return stage[j] holds the packed bounds of the
-// column sum of every prefix token j and bs.fin the rows' log-sum-exps.  aux:
-// room for L - W entries of four halves (the sums of tiles 1..3) of this head in HBM.  All threads of the
-// workgroup call; ends with a barrier.
+// column sum of every prefix token j and bs.fin the rows' log-sum-exps.  All
+// threads of the workgroup call; ends with a barrier.
 template <int D, int NT>
 __device__ __forceinline__ void snapkv_bounds(const BatchParams& p, const ReqDesc& rd, int lh,
                                               const int32_t* old_ids, BoundShared& bs,
-                                              BoundKeep& keep, float* stage, half4v* aux,
+                                              BoundKeep& keep, float* stage,
                                               half8 (&qreg)[NT][D / 32]) {
   constexpr int KS = D / 32;
   const int layer = lh / p.n_heads;
@@ -886,7 +898,7 @@ __device__ __forceinline__ void snapkv_bounds(const BatchParams& p, const ReqDes
       buf ^= 1;  // the other buffer is written next: its readers passed a barrier since
     }
     if (b < nb) {  // uniform per wavefront
-      float col[NT][4];
+      float cs[4] = {0.f, 0.f, 0.f, 0.f}, ss[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
         floatx4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -915,34 +927,22 @@ __device__ __forceinline__ void snapkv_bounds(const BatchParams& p, const ReqDes
         for (int r = 0; r < 4; ++r) {
           const float e = __builtin_amdgcn_exp2f(tv[r] - ref[nt]);
           zacc[nt] += e;
-          col[nt][r] = e;
+          cs[r] += e;
+          ss[r] = fmaf(e, e, ss[r]);
         }
       }
-      // sums over the 16 rows of every tile (the lanes of a row of 16); lane
-      // c16 < 4 of each row keeps those of token 4 q4 + c16
-      float mine[NT];
+      // sums over the window rows (the lanes of a row of 16, after the tiles in
+      // the lane); lane c16 < 4 of each row keeps those of token 4 q4 + c16
+      float mc = 0.f, ms = 0.f;
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        mine[nt] = 0.f;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const float v = row16_sum(col[nt][r]);
-          mine[nt] = c16 == r ? v : mine[nt];
-        }
+      for (int r = 0; r < 4; ++r) {
+        const float vc = row16_sum(cs[r]);
+        const float vs = row16_sum(ss[r]);
+        mc = c16 == r ? vc : mc;
+        ms = c16 == r ? vs : ms;
       }
       const int tok = b * 16 + q4 * 4 + c16;
-      if (c16 < 4 && tok < n_prefix) {
-        float total = 0.f;
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) total += mine[nt];
-        stage[tok] = total;
-        if (NT > 1) {
-          half4v hv = {0, 0, 0, 0};
-#pragma unroll
-          for (int nt = 1; nt < NT; ++nt) hv[nt - 1] = (_Float16)mine[nt];
-          aux[tok] = hv;  // 16 lanes x 8 bytes: one full line per block
-        }
-      }
+      if (c16 < 4 && tok < n_prefix) reinterpret_cast<uint32_t*>(stage)[tok] = pack_sums(mc, ms);
     }
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) kc[ks] = kn[ks];
@@ -957,61 +957,48 @@ __device__ __forceinline__ void snapkv_bounds(const BatchParams& p, const ReqDes
     if (row < W && !(fabsf(lse) < 3.0e38f)) keep.bad = 1;
   }
   __syncthreads();
-  // the factor range of every epoch and tile: rho_i = 2^(ref_i - lse_i), i in the tile
+  // the factors of every epoch, rho_i = 2^(ref_i - lse_i) over the window rows:
+  // range, mean and deviation from the mean
   for (int e = 1 + wave; e <= epoch; e += kWaves) {
     const bool ok = lane < W;
     const float rho = ok ? __builtin_amdgcn_exp2f(bs.ref[e][lane] - bs.fin[lane]) : 0.f;
-    float lo = ok ? rho : INFINITY, hi = rho;
+    float lo = ok ? rho : INFINITY, hi = rho, sum = rho;
 #pragma unroll
-    for (int o = 8; o > 0; o >>= 1) {
+    for (int o = 32; o > 0; o >>= 1) {
       lo = fminf(lo, __shfl_xor(lo, o));
       hi = fmaxf(hi, __shfl_xor(hi, o));
+      sum += __shfl_xor(sum, o);
     }
-    if (c16 == 0) {
-      // (margins far above the rounding of the numerators, the sums and the factors;
-      // a tile without window rows carries no weight at all)
-      keep.rmax[e][q4] = hi * 1.0002f;
-      keep.rmin[e][q4] = lo == INFINITY ? 0.f : lo * 0.9998f;
+    const float mean = sum / (float)W;
+    float dev = ok ? (rho - mean) * (rho - mean) : 0.f;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) dev += __shfl_xor(dev, o);
+    if (lane == 0) {
+      // (margins far above the rounding of the numerators, the sums and the factors)
+      keep.rmax[e] = hi * 1.0002f;
+      keep.rmin[e] = lo * 0.9998f;
+      keep.rmean[e] = mean;
+      keep.rdev[e] = sqrtf(dev) * 1.001f + 1.0e-6f * hi;
     }
   }
   __syncthreads();
-  // per token: the tiles' sums -> bounds, packed in place
+  // per token: the two sums -> bounds, packed in place
   {
     const float trivial = (float)W;  // every row contributes at most 1
-    // (four tokens per thread at a time, so that their loads from the scratch travel together)
-    for (int j0 = threadIdx.x; j0 < n_prefix; j0 += 4 * kThreads) {
-      half4v v[4];
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const half4v z = {0, 0, 0, 0};
-        v[u] = NT > 1 ? aux[min(j0 + u * kThreads, n_prefix - 1)] : z;
+    for (int j = threadIdx.x; j < n_prefix; j += kThreads) {
+      const int e = bound_epoch_of_token(j);
+      const uint32_t w = reinterpret_cast<const uint32_t*>(stage)[j];
+      const float c_lo = __uint_as_float(w & 0xFFFFF000u);
+      float lo = 0.f, hi = trivial;
+      if (e > 0 && c_lo < 3.0e38f) {  // (a sum that left the fp32 range says nothing)
+        const float c_hi = c_lo * 1.00049f + 1.0e-30f;  // what the truncation to 20 bits took, at most
+        const float width = (float)(w & 0xFFFu) * (1.f / 4095.f) * c_hi * keep.rdev[e];
+        const float h = fminf(c_hi * keep.rmax[e], (keep.rmean[e] * c_hi + width) * 1.0002f);
+        const float l = fmaxf(c_lo * keep.rmin[e], (keep.rmean[e] * c_lo - width) * 0.9998f);
+        lo = fmaxf(l, 0.f);
+        hi = fminf(h, trivial);
       }
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int j = j0 + u * kThreads;
-        if (j >= n_prefix) break;
-        const int e = bound_epoch_of_token(j);
-        float lo = 0.f, hi = trivial;
-        if (e > 0) {
-          const float total = stage[j];
-          float rest = total, l = 0.f, h = 0.f;
-#pragma unroll
-          for (int nt = 1; nt < NT; ++nt) {
-            // (a tile's sum went through fp16: 2^-11 relative, or flushed below 6e-8)
-            const float x = (float)v[u][nt - 1];
-            rest -= x;
-            l += x * 0.999f * keep.rmin[e][nt];
-            h += (x * 1.001f + 1.0e-7f) * keep.rmax[e][nt];
-          }
-          // tile 0 by subtraction: off by the roundings of the others at most
-          const float slack = total * 1.0e-3f + 3.0e-7f;
-          l += fmaxf(rest - slack, 0.f) * keep.rmin[e][0];
-          h += (fmaxf(rest, 0.f) + slack) * keep.rmax[e][0];
-          lo = l;
-          hi = fminf(h, trivial);
-        }
-        reinterpret_cast<uint32_t*>(stage)[j] = pack_bounds(lo, hi);
-      }
+      reinterpret_cast<uint32_t*>(stage)[j] = pack_bounds(lo, hi);
     }
   }
   __syncthreads();
@@ -1133,24 +1120,9 @@ __device__ __forceinline__ void bound_classify(const ReqDesc& rd, const float* s
   };
   // thresholds: the buckets that hold the k_sel-th largest lower and the k_sel-th
   // largest upper bound (two histograms from one evaluation of the pooled bounds)
-  const uint32_t kmin = score_key(0.f), kmax = score_key(vmax);
-  const int shift = kmax > kmin ? max(0, 32 - __clz(kmax - kmin) - kBucketBits) : 0;
   int* hist_lo = sh.hist;
   int* hist_hi = reinterpret_cast<int*>(sh.cand);
   static_assert(kMaxCand >= kBuckets, "the candidate list doubles as the second histogram");
-#pragma unroll
-  for (int i = 0; i < kBuckets / kThreads; ++i) {
-    hist_lo[tid + i * kThreads] = 0;
-    hist_hi[tid + i * kThreads] = 0;
-  }
-  __syncthreads();
-  for (int j = tid; j < n_sel; j += kThreads) {
-    float plo, phi;
-    pooled(j, plo, phi);
-    atomicAdd(&hist_lo[(score_key(plo) - kmin) >> shift], 1);
-    atomicAdd(&hist_hi[(score_key(phi) - kmin) >> shift], 1);
-  }
-  __syncthreads();
   // the bucket of the k_sel-th largest entry of a histogram -> sel[which]
   auto kth_bucket = [&](const int* hist, int which) {
     int own[kBuckets / kThreads];
@@ -1182,10 +1154,50 @@ __device__ __forceinline__ void bound_classify(const ReqDesc& rd, const float* s
     }
     __syncthreads();
   };
-  kth_bucket(hist_lo, 0);
-  kth_bucket(hist_hi, 1);
-  const uint32_t t_lo = kmin + ((uint32_t)sh.sel[0] << shift);               // <= the threshold's key
-  const uint32_t t_hi = kmin + (((uint32_t)sh.sel[1] + 1u) << shift) - 1u;  // >= the threshold's key
+  // buckets of 2^shift keys from kmin upwards; what lies below kmin counts in bucket 0
+  auto find_buckets = [&](uint32_t kmin, int shift) {
+#pragma unroll
+    for (int i = 0; i < kBuckets / kThreads; ++i) {
+      hist_lo[tid + i * kThreads] = 0;
+      hist_hi[tid + i * kThreads] = 0;
+    }
+    __syncthreads();
+    for (int j = tid; j < n_sel; j += kThreads) {
+      float plo, phi;
+      pooled(j, plo, phi);
+      const uint32_t klo = score_key(plo), khi = score_key(phi);
+      // (no key exceeds the largest upper bound; the clamp keeps the index in range whatever the bounds hold)
+      atomicAdd(&hist_lo[klo > kmin ? min((klo - kmin) >> shift, (uint32_t)kBuckets - 1u) : 0u], 1);
+      atomicAdd(&hist_hi[khi > kmin ? min((khi - kmin) >> shift, (uint32_t)kBuckets - 1u) : 0u], 1);
+    }
+    __syncthreads();
+    kth_bucket(hist_lo, 0);
+    kth_bucket(hist_hi, 1);
+  };
+  // The bounds carry 16 significant bits, the whole range of keys from 0 to the
+  // largest upper bound only fits 2048 buckets that are up to 12 % of a value
+  // wide.  So first with buckets of 1.6 % (2^17 keys) over the 32 octaves below
+  // the largest upper bound; should the k_sel-th largest lower bound lie below
+  // all of that, once more over the whole range.
+  const uint32_t kzero = score_key(0.f), kmax = score_key(vmax);
+  const int coarse = kmax > kzero ? max(0, 32 - __clz(kmax - kzero) - kBucketBits) : 0;
+  constexpr int kFine = 17;
+  uint32_t kmin = kzero;
+  int shift = coarse;
+  if (coarse > kFine) {
+    kmin = kmax - ((uint32_t)kBuckets << kFine) + 1u;
+    shift = kFine;
+  }
+  find_buckets(kmin, shift);
+  if (kmin != kzero && sh.sel[0] == 0) {  // uniform: read after a barrier
+    __syncthreads();                      // (everyone has read sel before it is written again)
+    kmin = kzero;
+    shift = coarse;
+    find_buckets(kmin, shift);
+  }
+  // (bucket 0 also holds what lies below kmin)
+  const uint32_t t_lo = sh.sel[0] == 0 ? kzero : kmin + ((uint32_t)sh.sel[0] << shift);  // <= the threshold's key
+  const uint32_t t_hi = kmin + (((uint32_t)sh.sel[1] + 1u) << shift) - 1u;                // >= the threshold's key
   for (int j = tid; j < n_sel; j += kThreads) {
     float plo, phi;
     pooled(j, plo, phi);
@@ -1383,13 +1395,11 @@ __global__ __launch_bounds__(kThreads, 3) void fused_bounded_kernel(BatchParams 
       const int q4 = (threadIdx.x & 63) >> 4;
       half8 qreg[NT][KS];
       load_window_queries<D, NT>(p, rd, lh, qreg);
-      // (room for the per-tile sums: 8 bytes per token of the call behind p.raw_scores)
-      half4v* aux = reinterpret_cast<half4v*>(p.raw_scores) + (size_t)rd.score_off + (size_t)lh * rd.seq_len;
       // Short heads and generous budgets gain nothing (the first blocks of a head
       // have no useful bounds, and with half of the tokens kept most pooled
       // intervals straddle the threshold): they take the two passes.
       const bool prune = rd.seq_len >= kBoundMinLen && 2 * rd.budget <= rd.seq_len;  // uniform
-      if (prune) snapkv_bounds<D, NT>(p, rd, lh, sm_ids, sh.bound, keep, stage, aux, qreg);
+      if (prune) snapkv_bounds<D, NT>(p, rd, lh, sm_ids, sh.bound, keep, stage, qreg);
       if (!prune || keep.bad) {  // bad: not representable against a running reference
         snapkv_unit_q<D, NT>(p, rd, lh, sm_ids, sh.score, qreg, [&](int j, float v) { stage[j] = v; });
       } else {

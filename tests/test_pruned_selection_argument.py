@@ -1,11 +1,14 @@
 """The argument behind the pruned second pass of the SnapKV-style score, checked
 on the CPU in fp64 with a small model of what the kernel keeps (host logic, no
-GPU): one pass over the keys that only knows, for every token, the sums of its
-soft-max numerators over the 16-row tiles of the window, taken against a
-reference of the row sums that is renewed at fixed steps, must
+GPU): one pass over the keys that only knows, for every token, the sum of its
+soft-max numerators over the window rows and the sum of their squares, taken
+against a reference of the row sums that is renewed at fixed steps, must
 
   * enclose every exact column sum between the two bounds it forms at the end
-    (per tile: smallest and largest factor between reference and final sum),
+    (the factors between reference and final sum of the rows: their mean times
+    the sum, give or take the Cauchy-Schwarz product of the root of the squares
+    with the factors' deviation from the mean; and the sum times the smallest
+    and the largest factor),
   * and lead to exactly the oracle's kept set when the tokens that can still
     decide the selection are re-scored exactly and all others keep their
     upper bound (Algorithm 1, batch compression: the top-budget set with the
@@ -24,7 +27,6 @@ from oracle import fastcache_oracle as fo
 
 
 STEP = 64          # tokens of one step (four blocks of 16)
-TILE = 16          # rows of a tile of the window
 
 
 def _epoch_of_step(t):
@@ -49,13 +51,13 @@ def _bounds(logits, lse, W):
             jj = np.arange(j0, min(j1, n_prefix))
             num = np.exp(logits[:, jj] - ref[:, None])            # numerators against the reference
             rho = np.exp(ref - lse)                               # factor to the exact weight, per row
-            l = np.zeros(len(jj))
-            h = np.zeros(len(jj))
-            for g in range(0, W, TILE):
-                c = num[g:g + TILE].sum(axis=0)
-                l += c * rho[g:g + TILE].min()
-                h += c * rho[g:g + TILE].max()
-            lo[jj], hi[jj] = l, np.minimum(h, float(W))
+            c = num.sum(axis=0)
+            s = np.sqrt((num ** 2).sum(axis=0))
+            mean = rho.mean()
+            dev = np.sqrt(((rho - mean) ** 2).sum())
+            l = np.maximum(c * rho.min(), mean * c - s * dev)
+            h = np.minimum(c * rho.max(), mean * c + s * dev)
+            lo[jj], hi[jj] = np.maximum(l, 0.0), np.minimum(h, float(W))
         run = np.logaddexp(run, np.logaddexp.reduce(logits[:, j0:j1], axis=1))
     return lo, hi
 

@@ -45,9 +45,6 @@ def test_two_calls_in_a_row_match_the_allocating_entry_point():
                         budgets, 23, False, True)
     a, b = SideBySide(wl), SideBySide(wl)     # identical pools, tables and queries
     try:
-        # the new entry point never prunes the second pass of the score: bit-equal kept
-        # lists can only be asked of the same evaluation on the other side
-        fc.fc_set_score_pruning(a.pool, False)
         n_lh = wl.n_layers * wl.n_heads
         comp = methods != fo.METHOD_NONE
         n_scores = int(np.array(lens)[comp].sum()) * n_lh
