@@ -748,8 +748,13 @@ __device__ __forceinline__ void select_unit(const BatchParams& p, const ReqDesc&
 // token's numerators e_ij over the window rows and s_j the root of the sum of
 // their squares, for any number m (here the mean of the rho_i)
 //     a_j = sum_i e_ij rho_i = m c_j + sum_i e_ij (rho_i - m),
-//     | a_j - m c_j |  <=  s_j sqrt(sum_i (rho_i - m)^2)        (Cauchy-Schwarz),
-// and also c_j min_i rho_i <= a_j <= c_j max_i rho_i.  Both numbers of a token
+// and because no e_ij is negative, with (x)+ = max(x, 0) and Cauchy-Schwarz,
+//     a_j <= m c_j + s_j sqrt(sum_i ((rho_i - m)+)^2),
+//     a_j >= m c_j - s_j sqrt(sum_i ((m - rho_i)+)^2),
+// for any number m: a few values of m around the mean of the rho_i are tried for
+// each side (the least upper bound over all m is the exact maximum of a_j over
+// all non-negative e_ij with these two sums), next to
+// c_j min_i rho_i <= a_j <= c_j max_i rho_i.  Both numbers of a token
 // share its word of the LDS score array until the pass ends (c_j in the leading
 // 20 bits, s_j / c_j <= 1 in the other 12), so the bounds cost no memory traffic.
 // After the pass: bounds of the max-pooled scores, a lower and an upper bound of
@@ -768,18 +773,25 @@ __device__ __forceinline__ void select_unit(const BatchParams& p, const ReqDesc&
 // overflow, the row's log-sum-exp is not finite, and the head falls back to
 // the two-pass code.
 
+static constexpr int kBoundCentres = 3;  // values of m tried per side
+
+struct BoundEpoch {  // the factors rho_i of one epoch over the window rows
+  float rmax, rmin;               // largest (widened), smallest (narrowed)
+  float m_up[kBoundCentres];      // centres for the upper bound ...
+  float p_up[kBoundCentres];      // ... and sqrt(sum ((rho_i - m)+)^2) for each (widened)
+  float m_dn[kBoundCentres];      // the same for the lower bound, with (m - rho_i)+
+  float p_dn[kBoundCentres];
+};
+
 struct BoundShared {
   float fin[64];                   // log2 of every row's soft-max denominator
   float pub[2][kWaves][64];        // the wavefronts' row sums at a renewal, absolute log2
   float ref[kBoundMaxEpochs][64];  // the reference of every epoch
+  BoundEpoch stat[kBoundMaxEpochs];
 };
 
-struct BoundKeep {                 // what survives into the selection's LDS
-  float rmax[kBoundMaxEpochs];     // largest factor of an epoch over the window rows (widened)
-  float rmin[kBoundMaxEpochs];     // smallest
-  float rmean[kBoundMaxEpochs];    // their mean
-  float rdev[kBoundMaxEpochs];     // root of the sum of their squared deviations from it (widened)
-  int bad;                         // a row's log-sum-exp is not finite: fall back
+struct BoundKeep {  // what survives into the selection's LDS
+  int bad;          // a row's log-sum-exp is not finite: fall back
 };
 
 // A token's two sums during the pass, in one word: the leading 20 bits of the
@@ -957,8 +969,9 @@ __device__ __forceinline__ void snapkv_bounds(const BatchParams& p, const ReqDes
     if (row < W && !(fabsf(lse) < 3.0e38f)) keep.bad = 1;
   }
   __syncthreads();
-  // the factors of every epoch, rho_i = 2^(ref_i - lse_i) over the window rows:
-  // range, mean and deviation from the mean
+  // the factors of every epoch, rho_i = 2^(ref_i - lse_i) over the window rows
+  // (one per lane): range, and for centres at the mean and half a standard
+  // deviation to either side of it the one-sided deviations
   for (int e = 1 + wave; e <= epoch; e += kWaves) {
     const bool ok = lane < W;
     const float rho = ok ? __builtin_amdgcn_exp2f(bs.ref[e][lane] - bs.fin[lane]) : 0.f;
@@ -970,15 +983,41 @@ __device__ __forceinline__ void snapkv_bounds(const BatchParams& p, const ReqDes
       sum += __shfl_xor(sum, o);
     }
     const float mean = sum / (float)W;
-    float dev = ok ? (rho - mean) * (rho - mean) : 0.f;
+    float var = ok ? (rho - mean) * (rho - mean) : 0.f;
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) dev += __shfl_xor(dev, o);
+    for (int o = 32; o > 0; o >>= 1) var += __shfl_xor(var, o);
+    const float half_sd = 0.5f * sqrtf(var / (float)W);
+    float m_up[kBoundCentres], m_dn[kBoundCentres], p_up[kBoundCentres], p_dn[kBoundCentres];
+#pragma unroll
+    for (int k = 0; k < kBoundCentres; ++k) {
+      // (any centre gives a valid bound; none below zero, so that widening the sum widens the bound)
+      m_up[k] = fmaxf(mean + (float)(k - 1) * half_sd, 0.f);
+      m_dn[k] = fmaxf(mean - (float)(k - 1) * half_sd, 0.f);
+      const float du = ok ? fmaxf(rho - m_up[k], 0.f) : 0.f;
+      const float dd = ok ? fmaxf(m_dn[k] - rho, 0.f) : 0.f;
+      p_up[k] = du * du;
+      p_dn[k] = dd * dd;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+#pragma unroll
+      for (int k = 0; k < kBoundCentres; ++k) {
+        p_up[k] += __shfl_xor(p_up[k], o);
+        p_dn[k] += __shfl_xor(p_dn[k], o);
+      }
+    }
     if (lane == 0) {
       // (margins far above the rounding of the numerators, the sums and the factors)
-      keep.rmax[e] = hi * 1.0002f;
-      keep.rmin[e] = lo * 0.9998f;
-      keep.rmean[e] = mean;
-      keep.rdev[e] = sqrtf(dev) * 1.001f + 1.0e-6f * hi;
+      BoundEpoch& st = bs.stat[e];
+      st.rmax = hi * 1.0002f;
+      st.rmin = lo * 0.9998f;
+#pragma unroll
+      for (int k = 0; k < kBoundCentres; ++k) {
+        st.m_up[k] = m_up[k];
+        st.m_dn[k] = m_dn[k];
+        st.p_up[k] = sqrtf(p_up[k]) * 1.001f + 1.0e-6f * hi;
+        st.p_dn[k] = sqrtf(p_dn[k]) * 1.001f + 1.0e-6f * hi;
+      }
     }
   }
   __syncthreads();
@@ -991,10 +1030,15 @@ __device__ __forceinline__ void snapkv_bounds(const BatchParams& p, const ReqDes
       const float c_lo = __uint_as_float(w & 0xFFFFF000u);
       float lo = 0.f, hi = trivial;
       if (e > 0 && c_lo < 3.0e38f) {  // (a sum that left the fp32 range says nothing)
+        const BoundEpoch& st = bs.stat[e];
         const float c_hi = c_lo * 1.00049f + 1.0e-30f;  // what the truncation to 20 bits took, at most
-        const float width = (float)(w & 0xFFFu) * (1.f / 4095.f) * c_hi * keep.rdev[e];
-        const float h = fminf(c_hi * keep.rmax[e], (keep.rmean[e] * c_hi + width) * 1.0002f);
-        const float l = fmaxf(c_lo * keep.rmin[e], (keep.rmean[e] * c_lo - width) * 0.9998f);
+        const float s_hi = (float)(w & 0xFFFu) * (1.f / 4095.f) * c_hi;
+        float h = c_hi * st.rmax, l = c_lo * st.rmin;
+#pragma unroll
+        for (int k = 0; k < kBoundCentres; ++k) {
+          h = fminf(h, (st.m_up[k] * c_hi + s_hi * st.p_up[k]) * 1.0002f);
+          l = fmaxf(l, (st.m_dn[k] * c_lo - s_hi * st.p_dn[k]) * 0.9998f);
+        }
         lo = fmaxf(l, 0.f);
         hi = fminf(h, trivial);
       }

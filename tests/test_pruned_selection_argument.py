@@ -5,10 +5,12 @@ soft-max numerators over the window rows and the sum of their squares, taken
 against a reference of the row sums that is renewed at fixed steps, must
 
   * enclose every exact column sum between the two bounds it forms at the end
-    (the factors between reference and final sum of the rows: their mean times
-    the sum, give or take the Cauchy-Schwarz product of the root of the squares
-    with the factors' deviation from the mean; and the sum times the smallest
-    and the largest factor),
+    from the factors between reference and final sum of the rows: a centre times
+    the sum, plus the root of the squares times the root of the squared
+    excesses of the factors over the centre (no numerator is negative, so only
+    the excesses count; Cauchy-Schwarz), likewise downwards, for three centres
+    around the factors' mean; and the sum times the smallest and the largest
+    factor,
   * and lead to exactly the oracle's kept set when the tokens that can still
     decide the selection are re-scored exactly and all others keep their
     upper bound (Algorithm 1, batch compression: the top-budget set with the
@@ -53,10 +55,12 @@ def _bounds(logits, lse, W):
             rho = np.exp(ref - lse)                               # factor to the exact weight, per row
             c = num.sum(axis=0)
             s = np.sqrt((num ** 2).sum(axis=0))
-            mean = rho.mean()
-            dev = np.sqrt(((rho - mean) ** 2).sum())
-            l = np.maximum(c * rho.min(), mean * c - s * dev)
-            h = np.minimum(c * rho.max(), mean * c + s * dev)
+            l, h = c * rho.min(), c * rho.max()
+            for t in (-0.5, 0.0, 0.5):
+                up = max(rho.mean() + t * rho.std(), 0.0)
+                dn = max(rho.mean() - t * rho.std(), 0.0)
+                h = np.minimum(h, up * c + s * np.sqrt((np.maximum(rho - up, 0.0) ** 2).sum()))
+                l = np.maximum(l, dn * c - s * np.sqrt((np.maximum(dn - rho, 0.0) ** 2).sum()))
             lo[jj], hi[jj] = np.maximum(l, 0.0), np.minimum(h, float(W))
         run = np.logaddexp(run, np.logaddexp.reduce(logits[:, j0:j1], axis=1))
     return lo, hi
