@@ -718,7 +718,9 @@ def run_stage(args, wl, cpu_seconds, lse_variant=False):
         "roofline": {
             "kernel": dom,
             # the name rocprofv3 shows for it (profiles/ summaries are keyed by that name)
-            "kernel_symbol": kernel_symbol(dom, wl, bool(args.score_pruning)),
+            # (a call that brings the row log-sum-exps has no second pass to prune)
+            "kernel_symbol": kernel_symbol(dom, wl, bool(args.score_pruning)
+                                           and not args.workload.endswith("_lse")),
             "bound": "hbm",
             "achieved": dom_gbps,
             "peak": HBM_PEAK_GBPS,
