@@ -129,13 +129,17 @@ def _keys_by_token(wl, make_key):
     return kv
 
 
-@pytest.mark.parametrize("shape", ["ramp", "sinks", "late_and_uneven"])
+@pytest.mark.parametrize("shape", ["ramp", "sinks", "late_and_uneven", "giant_sinks", "late_giants"])
 def test_structured_attention_patterns(shape):
     """Inputs on which the factor between a row's running sum and its final sum
     behaves in the three extreme ways: it keeps shrinking along the whole head
     (logits that rise with the position), it is one from the start (a few
-    dominant first tokens), and it differs wildly between the rows of one
-    16-row tile (half of the queries see their mass only at the end)."""
+    dominant first tokens), and it differs wildly between the rows
+    (half of the queries see their mass only at the end).  And two on which the
+    scores span more octaves than the fine threshold buckets cover, so that the
+    selection is decided 60 nats below the largest score: a few first tokens
+    that take all the mass, and a few late ones (every reference before them is
+    overtaken by 2^86: the squares of the numerators leave the fp32 range)."""
     d, W = 64, 32
     wl = _custom([3200, 2300], [640, 300], [fo.METHOD_SNAPKV] * 2, W=W, d=d, n_heads=2)
     rng = np.random.default_rng(17)
@@ -149,9 +153,16 @@ def test_structured_attention_patterns(shape):
     elif shape == "sinks":
         key = lambda r, tok: (noise() + (u * 8.0 if tok < 4 else 0.0)).astype(np.float16)
         q[..., :8] += 2.0
-    else:
+    elif shape == "late_and_uneven":
         key = lambda r, tok: (noise() + (u * 5.0 if tok >= int(wl.seq_lens[r]) - 200 else 0.0)).astype(np.float16)
         q[:, :, :, ::2, :8] += 2.5          # every other query row leans on the late keys
+    elif shape == "giant_sinks":
+        key = lambda r, tok: (noise() + (u * 30.0 if tok < 4 else 0.0)).astype(np.float16)
+        q[..., :8] += 2.0
+    else:
+        late = lambda r, tok: int(wl.seq_lens[r]) - tok in (100, 150, 200)
+        key = lambda r, tok: (noise() + (u * 30.0 if late(r, tok) else 0.0)).astype(np.float16)
+        q[..., :8] += 2.0
     kv = _keys_by_token(wl, key)
     _run_pruned(wl, sbs_kw={"kv_host": kv, "q_host": q.astype(np.float16)})
 
