@@ -369,8 +369,8 @@ int fc_set_score_mode(fc_pool* pool, int mode);
 /*
  * Pruned second pass of the SnapKV-style score (Algorithm 1, "Batch
  * compression"; the selection only needs exact scores near its threshold).
- * On by default (enable == 0 turns it off): for heads of at least 2048 tokens
- * whose budget is at most half their length, the fused kernel of the default
+ * On by default (enable == 0 turns it off): for heads of at least 512 tokens
+ * the fused kernel of the default
  * scheduling bounds every column sum during its first pass over K and re-reads
  * only the key rows whose exact score can still decide the selection.  The kept
  * set is the exact top-budget set of the exactly evaluated scores, as on the

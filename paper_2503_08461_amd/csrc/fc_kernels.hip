@@ -175,7 +175,7 @@ __global__ __launch_bounds__(kThreads) void reclaim_kernel(BatchParams p) {
 // then to 2 + t / 4: the references are renewed before t = 1, 2 and every
 // multiple of 4, by all wavefronts together.
 static constexpr int kBoundSeg = 4;
-static constexpr int kBoundMinLen = 2048;  // shorter heads take the two passes
+static constexpr int kBoundMinLen = 512;  // shorter heads take the two passes
 static constexpr int kBoundMaxEpochs = 3 + (kFusedMaxLen / 16 / kWaves + kBoundSeg - 1) / kBoundSeg;
 __host__ __device__ constexpr int bound_epoch_of_step(int t) {
   return t < 2 ? t : (t < kBoundSeg ? 2 : 2 + t / kBoundSeg);
@@ -746,12 +746,12 @@ __device__ __forceinline__ void select_unit(const BatchParams& p, const ReqDesc&
 // numerator times rho_i = 2^(ref_i - lse_i) <= 1, a factor that is only known at
 // the end but is the same for every token of an epoch.  With c_j the sum of a
 // token's numerators e_ij over the window rows and s_j the root of the sum of
-// their squares, for any number m (here the mean of the rho_i)
+// their squares, for any number m
 //     a_j = sum_i e_ij rho_i = m c_j + sum_i e_ij (rho_i - m),
 // and because no e_ij is negative, with (x)+ = max(x, 0) and Cauchy-Schwarz,
 //     a_j <= m c_j + s_j sqrt(sum_i ((rho_i - m)+)^2),
-//     a_j >= m c_j - s_j sqrt(sum_i ((m - rho_i)+)^2),
-// for any number m: a few values of m around the mean of the rho_i are tried for
+//     a_j >= m c_j - s_j sqrt(sum_i ((m - rho_i)+)^2).
+// A few values of m around the mean of the rho_i are tried for
 // each side (the least upper bound over all m is the exact maximum of a_j over
 // all non-negative e_ij with these two sums), next to
 // c_j min_i rho_i <= a_j <= c_j max_i rho_i.  Both numbers of a token
@@ -1439,10 +1439,9 @@ __global__ __launch_bounds__(kThreads, 3) void fused_bounded_kernel(BatchParams 
       const int q4 = (threadIdx.x & 63) >> 4;
       half8 qreg[NT][KS];
       load_window_queries<D, NT>(p, rd, lh, qreg);
-      // Short heads and generous budgets gain nothing (the first blocks of a head
-      // have no useful bounds, and with half of the tokens kept most pooled
-      // intervals straddle the threshold): they take the two passes.
-      const bool prune = rd.seq_len >= kBoundMinLen && 2 * rd.budget <= rd.seq_len;  // uniform
+      // Short heads gain nothing (the tokens of the first step have no bounds,
+      // those of the next few loose ones): they take the two passes.
+      const bool prune = rd.seq_len >= kBoundMinLen;  // uniform
       if (prune) snapkv_bounds<D, NT>(p, rd, lh, sm_ids, sh.bound, keep, stage, qreg);
       if (!prune || keep.bad) {  // bad: not representable against a running reference
         snapkv_unit_q<D, NT>(p, rd, lh, sm_ids, sh.score, qreg, [&](int j, float v) { stage[j] = v; });

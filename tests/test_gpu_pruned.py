@@ -37,10 +37,13 @@ def _run_pruned(wl, repeats=1, sbs_kw=None, **kw):
 @pytest.mark.parametrize("L,W,d,pct", [(640, 32, 128, 25), (2048, 64, 128, 20), (4556, 64, 128, 20),
                                        (7040, 64, 128, 20), (8192, 48, 64, 10), (3000, 16, 128, 50),
                                        (2049, 33, 64, 35), (2500, 1, 128, 5), (5000, 17, 64, 3),
-                                       (2111, 64, 128, 45), (4097, 64, 64, 99)])
+                                       (2111, 64, 128, 45), (4097, 64, 64, 99), (512, 32, 128, 50),
+                                       (511, 64, 64, 30), (700, 64, 128, 80), (1200, 48, 64, 60),
+                                       (1031, 16, 128, 10)])
 def test_pruned_pass_keeps_what_two_passes_keep(L, W, d, pct):
-    """Heads on both sides of the length and budget limits of the pruned path,
-    every number of query tiles, ragged last blocks."""
+    """Heads on both sides of the length limit of the pruned path (the second
+    request of a case has half the length of the first), small and large
+    budgets, every number of query tiles, ragged last blocks."""
     B = max(W, L * pct // 100)
     _run_pruned(_custom([L, L // 2 + 9], [B, max(W, (L // 2 + 9) * pct // 100)],
                         [fo.METHOD_SNAPKV] * 2, W=W, d=d, n_heads=4))
@@ -223,8 +226,8 @@ def test_random_long_batches(seed):
     lens, methods, budgets = [], [], []
     for _ in range(n_req):
         m = int(rng.choice([fo.METHOD_SNAPKV, fo.METHOD_KNORM], p=[0.8, 0.2]))
-        L = int(rng.integers(1900, 8193))
-        B = int(rng.integers(max(W, 1), max(W + 1, L // 2)))
+        L = int(rng.integers(400, 8193))
+        B = int(rng.integers(max(W, 1), L))
         lens.append(L); methods.append(m); budgets.append(B)
     wl = _custom(lens, budgets, methods, W=W, d=d, n_heads=int(rng.integers(1, 3)), seed=300 + seed)
     print("seed", seed, lens, budgets, methods, W, d, flush=True)
